@@ -1,0 +1,209 @@
+"""ctypes front end of the CPU oracle (test infrastructure, not product code).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this.
+It takes plain numpy arrays, calls `liboracle.so` (built from
+`parcae_oracle.c` with gcc) and returns numpy arrays.  It imports nothing from
+the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "parcae_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib: Optional[ct.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add, OpenMP for the unit loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a: np.ndarray, ty):
+    return a.ctypes.data_as(ct.POINTER(ty))
+
+
+def lib() -> ct.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ct.CDLL(_LIB)
+        _lib.orc_word.restype = ct.c_uint32
+        _lib.orc_word.argtypes = [ct.c_uint64, ct.c_uint32, ct.c_uint32, ct.c_uint32, ct.c_uint32]
+        _lib.orc_dp_f32.restype = ct.c_int
+        _lib.orc_dp_f64.restype = ct.c_double
+        _lib.orc_num_threads.restype = ct.c_int
+    return _lib
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c, ct.c_uint32), _p(k, ct.c_uint32), _p(out, ct.c_uint32))
+    return out
+
+
+def word(seed: int, stream_id: int, unit: int, s: int, i: int) -> int:
+    return int(lib().orc_word(ct.c_uint64(seed), stream_id, unit, s, i))
+
+
+def sample_preempted(M: int, k: int, seed: int, stream_id: int, unit: int, s: int) -> np.ndarray:
+    out = np.zeros(M, dtype=np.uint8)
+    lib().orc_sample_preempted(ct.c_int(M), ct.c_int(k), ct.c_uint64(seed), ct.c_uint32(stream_id),
+                               ct.c_uint32(unit), ct.c_uint32(s), _p(out, ct.c_uint8))
+    return out
+
+
+def reduce(D: int, P: int, preempted: np.ndarray):
+    pre = np.ascontiguousarray(preempted, dtype=np.uint8)
+    assert pre.size == D * P
+    n_int, d_min = ct.c_int(0), ct.c_int(0)
+    occ = np.zeros(P, dtype=np.int32)
+    lib().orc_reduce(ct.c_int(D), ct.c_int(P), _p(pre, ct.c_uint8), ct.byref(n_int), ct.byref(d_min),
+                     _p(occ, ct.c_int32))
+    return n_int.value, d_min.value, occ
+
+
+def debug_sample(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s0: int, ns: int):
+    masks = np.zeros((ns, 8), dtype=np.uint32)
+    n_int = np.zeros(ns, dtype=np.int32)
+    d_min = np.zeros(ns, dtype=np.int32)
+    lib().orc_debug_sample(ct.c_int(D), ct.c_int(P), ct.c_int(a_next), ct.c_uint64(seed),
+                           ct.c_uint32(stream_id), ct.c_uint32(unit), ct.c_uint32(s0), ct.c_uint32(ns),
+                           _p(masks, ct.c_uint32), _p(n_int, ct.c_int32), _p(d_min, ct.c_int32))
+    return masks, n_int, d_min
+
+
+def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1):
+    """Histograms [T][L] of one query over scenarios [s_begin, s_end)."""
+    configs = np.ascontiguousarray(configs, dtype=np.int32)
+    thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
+    avail = np.ascontiguousarray(avail, dtype=np.int32)
+    C, T, L = configs.shape[0], avail.shape[0] - 1, int(thr_off[-1])
+    hi = np.zeros((T, L), dtype=np.uint32)
+    hm = np.zeros((T, L), dtype=np.uint32)
+    lib().orc_eval_hist(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
+                        _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
+                        ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
+                        ct.c_int(n_threads))
+    return hi, hm
+
+
+@dataclass
+class Tables:
+    liveput_d: np.ndarray  # [3][T][C] double
+    teff_d: np.ndarray
+    gain_d: np.ndarray
+    liveput_f: np.ndarray  # same, fixed-order float
+    teff_f: np.ndarray
+    gain_f: np.ndarray
+
+
+def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, hist_min) -> Tables:
+    configs = np.ascontiguousarray(configs, dtype=np.int32)
+    thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
+    avail = np.ascontiguousarray(avail, dtype=np.int32)
+    thr = np.ascontiguousarray(thr, dtype=np.float32)
+    cost = np.ascontiguousarray(cost, dtype=np.float32)
+    hi = np.ascontiguousarray(hist_int, dtype=np.uint32)
+    hm = np.ascontiguousarray(hist_min, dtype=np.uint32)
+    C, T = configs.shape[0], avail.shape[0] - 1
+    out = Tables(np.zeros((3, T, C)), np.zeros((T, C)), np.zeros((T, C)),
+                 np.zeros((3, T, C), np.float32), np.zeros((T, C), np.float32), np.zeros((T, C), np.float32))
+    lib().orc_finalise(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
+                       _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
+                       ct.c_uint32(S), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
+                       _p(out.liveput_d, ct.c_double), _p(out.teff_d, ct.c_double), _p(out.gain_d, ct.c_double),
+                       _p(out.liveput_f, ct.c_float), _p(out.teff_f, ct.c_float), _p(out.gain_f, ct.c_float))
+    return out
+
+
+def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: int, cur_config: int,
+               hist_int, hist_min):
+    """W[T][C][C] in double and in fixed-order float."""
+    configs = np.ascontiguousarray(configs, dtype=np.int32)
+    thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
+    avail = np.ascontiguousarray(avail, dtype=np.int32)
+    thr = np.ascontiguousarray(thr, dtype=np.float32)
+    cost = np.ascontiguousarray(cost, dtype=np.float32)
+    hi = np.ascontiguousarray(hist_int, dtype=np.uint32)
+    hm = np.ascontiguousarray(hist_min, dtype=np.uint32)
+    C, T = configs.shape[0], avail.shape[0] - 1
+    W_d = np.zeros((T, C, C), dtype=np.float64)
+    W_f = np.zeros((T, C, C), dtype=np.float32)
+    lib().orc_transition(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
+                         _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
+                         ct.c_uint32(S), ct.c_int(p_min), ct.c_int(cur_config),
+                         _p(hi, ct.c_uint32), _p(hm, ct.c_uint32), _p(W_d, ct.c_double), _p(W_f, ct.c_float))
+    return W_d, W_f
+
+
+@dataclass
+class Plan:
+    F: np.ndarray          # [T+1][C] float32
+    bp: np.ndarray         # [T][C] int32
+    plan: np.ndarray       # [T] int32
+    start: int
+    objective: float       # float32 value
+    feasible: bool
+
+
+def dp_f32(W: np.ndarray) -> Plan:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    T, C = W.shape[0], W.shape[1]
+    F = np.zeros((T + 1, C), dtype=np.float32)
+    bp = np.zeros((T, C), dtype=np.int32)
+    plan = np.zeros(T, dtype=np.int32)
+    start = ct.c_int32(0)
+    obj = ct.c_float(0)
+    ok = lib().orc_dp_f32(ct.c_int(T), ct.c_int(C), _p(W, ct.c_float), _p(F, ct.c_float), _p(bp, ct.c_int32),
+                          _p(plan, ct.c_int32), ct.byref(start), ct.byref(obj))
+    return Plan(F, bp, plan, int(start.value), float(obj.value), bool(ok))
+
+
+def dp_f64(W: np.ndarray) -> float:
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    return float(lib().orc_dp_f64(ct.c_int(W.shape[0]), ct.c_int(W.shape[1]), _p(W, ct.c_double)))
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+# ---------------------------------------------------------------- whole-batch helpers
+
+@dataclass
+class QueryResult:
+    hist_int: np.ndarray
+    hist_min: np.ndarray
+    tables: Tables
+    W_d: np.ndarray
+    W_f: np.ndarray
+    plan: Plan
+    objective_d: float
+
+
+def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int = 1, want_plan: bool = True) -> QueryResult:
+    """Whole path for query q of a batch object that carries the input arrays."""
+    S = batch.n_scenarios if n_scenarios is None else int(n_scenarios)
+    hi, hm = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
+                       0, S, n_threads)
+    tab = finalise(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
+                   batch.interval_sec, S, hi, hm)
+    if not want_plan:
+        return QueryResult(hi, hm, tab, None, None, None, float("nan"))
+    W_d, W_f = transition(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
+                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm)
+    return QueryResult(hi, hm, tab, W_d, W_f, dp_f32(W_f), dp_f64(W_d))

@@ -1,0 +1,425 @@
+/*
+ * CPU oracle for the liveput optimizer's hot path (Parcae, arXiv 2403.14097).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the GPU library must compute.  It shares no code with the GPU library, is
+ * never linked into it, and nothing in the product path may call it.  Only
+ * tests, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * What it follows:
+ *   - preemption counts per interval         section 4.2 (N+ / N- rule)
+ *   - uniform preemption mapping             section 5.1
+ *   - Monte-Carlo preemption-mapping sampler section 6.3
+ *   - which migration a scenario needs       section 5.2, section 7 (fault tolerance)
+ *   - liveput as an expectation              Definition 1, Eq. 1
+ *   - committed samples of one interval      Eq. 3-4 (phi, T_eff = T - T_mig)
+ *   - look-ahead dynamic program             Eq. 6 and the final max after it
+ *   - transition-cost rule                   section 6.2 (depth change => pipeline migration ...)
+ *
+ * The paper leaves the random number generator, the subset-drawing method
+ * and the number of trials open.  This oracle fixes them as follows.
+ *   Random words: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel random
+ *   numbers: as easy as 1, 2, 3", SC'11), key = (seed low, seed high),
+ *   counter = (scenario, word index / 4, interval * C + config, stream id);
+ *   word i is output lane i mod 4.
+ *   Subset: R. Floyd's sampling (Bentley & Floyd, CACM 1987) of the smaller
+ *   of the preempted / surviving sets, bounded integers by multiply-shift.
+ *
+ * Precision: every floating-point result is produced twice, in double
+ * (the reference value) and in float with one fixed operation order and no
+ * fused multiply-add (what decides the integer plan; compile with
+ * -ffp-contract=off).  Pinned by tests/test_oracle_*.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_MAX_INSTANCES 256
+
+/* ---------------------------------------------------------------- Philox */
+
+/* One Philox4x32 block with 10 rounds (SC'11, section 3.3 and table 2 constants). */
+void orc_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t out[4])
+{
+    const uint32_t mul_a = 0xD2511F53u, mul_b = 0xCD9E8D57u;
+    const uint32_t weyl_a = 0x9E3779B9u, weyl_b = 0xBB67AE85u;
+    uint32_t c0 = ctr_in[0], c1 = ctr_in[1], c2 = ctr_in[2], c3 = ctr_in[3];
+    uint32_t k0 = key_in[0], k1 = key_in[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t prod_a = (uint64_t)mul_a * (uint64_t)c0;
+        uint64_t prod_b = (uint64_t)mul_b * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(prod_b >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)prod_b;
+        uint32_t n2 = (uint32_t)(prod_a >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)prod_a;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += weyl_a;
+        k1 += weyl_b;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Random word i of scenario s of unit (interval t, config c); unit = t * C + c. */
+uint32_t orc_word(uint64_t seed, uint32_t stream_id, uint32_t unit, uint32_t s, uint32_t i)
+{
+    uint32_t ctr[4] = { s, i / 4u, unit, stream_id };
+    uint32_t key[2] = { (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return out[i % 4u];
+}
+
+/* ---------------------------------------------------------------- sampler */
+
+/*
+ * Preempted set of one scenario (section 6.3: a vector v with exactly k ones
+ * among the M instances, every instance equally likely, section 5.1).
+ * preempted[j] in {0,1}, j = logical instance = pipeline * P + stage.
+ * Floyd's method draws the smaller of the two sets: m = min(k, M - k) words.
+ */
+void orc_sample_preempted(int M, int k, uint64_t seed, uint32_t stream_id, uint32_t unit,
+                          uint32_t s, uint8_t *preempted)
+{
+    uint8_t chosen[ORC_MAX_INSTANCES];
+    int m = (k < M - k) ? k : M - k;
+    memset(chosen, 0, sizeof chosen);
+    for (int i = 0; i < m; ++i) {
+        int j = M - m + i;
+        uint32_t w = orc_word(seed, stream_id, unit, s, (uint32_t)i);
+        uint32_t r = (uint32_t)(((uint64_t)w * (uint64_t)(j + 1)) >> 32); /* in [0, j] */
+        if (chosen[r]) chosen[j] = 1; else chosen[r] = 1;
+    }
+    int complement = (k > M - k);
+    for (int j = 0; j < M; ++j) preempted[j] = complement ? (uint8_t)!chosen[j] : chosen[j];
+}
+
+/* ---------------------------------------------------------------- reducer */
+
+/*
+ * What survives a scenario on a D x P grid (section 5.2):
+ *   occ[s]  = instances of stage s still alive,
+ *   d_min   = min over stages of occ[s]  (pipelines that re-routing inside
+ *             stages can complete; 0 means a stage is gone, section 7),
+ *   n_int   = pipelines that lost no instance (run on with no migration).
+ */
+void orc_reduce(int D, int P, const uint8_t *preempted, int *n_int, int *d_min, int *occ)
+{
+    int intact = 0, least = D;
+    for (int s = 0; s < P; ++s) {
+        int alive = 0;
+        for (int d = 0; d < D; ++d) alive += preempted[d * P + s] ? 0 : 1;
+        if (occ) occ[s] = alive;
+        if (alive < least) least = alive;
+    }
+    for (int d = 0; d < D; ++d) {
+        int hit = 0;
+        for (int s = 0; s < P; ++s) hit |= preempted[d * P + s];
+        intact += hit ? 0 : 1;
+    }
+    *n_int = intact;
+    *d_min = least;
+}
+
+/* Pool size and preempted count of unit (t, c): the D*P used instances lose
+ * max(0, D*P - a_t) of them when availability drops to a_t (section 4.2). */
+static void unit_pool(int D, int P, int a_next, int *M, int *k)
+{
+    *M = D * P;
+    *k = (*M - a_next > 0) ? (*M - a_next) : 0;
+}
+
+/*
+ * Debug view of scenarios [s0, s0 + ns) of one unit: packed masks
+ * (bit j of word j/32 = instance j preempted, 8 words per scenario) and the
+ * two per-scenario integers.
+ */
+void orc_debug_sample(int D, int P, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+                      uint32_t s0, uint32_t ns, uint32_t *masks, int32_t *n_int, int32_t *d_min)
+{
+    uint8_t pre[ORC_MAX_INSTANCES];
+    int M, k;
+    unit_pool(D, P, a_next, &M, &k);
+    for (uint32_t x = 0; x < ns; ++x) {
+        int ni, dm;
+        orc_sample_preempted(M, k, seed, stream_id, unit, s0 + x, pre);
+        orc_reduce(D, P, pre, &ni, &dm, NULL);
+        for (int w = 0; w < 8; ++w) masks[x * 8u + (uint32_t)w] = 0u;
+        for (int j = 0; j < M; ++j)
+            if (pre[j]) masks[x * 8u + (uint32_t)(j / 32)] |= (1u << (j % 32));
+        n_int[x] = ni;
+        d_min[x] = dm;
+    }
+}
+
+/*
+ * Histograms of one query over scenarios [s_begin, s_end):
+ *   hist_int[t][off[c] + n_int] += 1, hist_min[t][off[c] + d_min] += 1.
+ * configs = (D, P) pairs; avail[0] = availability now, avail[1 + t] = a_t.
+ * Buffers are [T][off[C]] and are overwritten.  n_threads > 1 splits the
+ * independent units over OpenMP threads (no effect on the integers).
+ */
+void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
+                   uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
+                   uint32_t *hist_int, uint32_t *hist_min, int n_threads)
+{
+    const int L = thr_off[C];
+    memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
+    memset(hist_min, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
+    (void)n_threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads > 0 ? n_threads : 1)
+#endif
+    for (int u = 0; u < T * C; ++u) {
+        int t = u / C, c = u % C;
+        int D = configs[2 * c], P = configs[2 * c + 1];
+        int M, k;
+        uint8_t pre[ORC_MAX_INSTANCES];
+        unit_pool(D, P, avail[t + 1], &M, &k);
+        uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
+        uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+        for (uint32_t s = s_begin; s < s_end; ++s) {
+            int ni, dm;
+            orc_sample_preempted(M, k, seed, stream_id, (uint32_t)u, s, pre);
+            orc_reduce(D, P, pre, &ni, &dm, NULL);
+            hi[ni] += 1u;
+            hm[dm] += 1u;
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- tables */
+
+static double dmax0(double x) { return x > 0.0 ? x : 0.0; }
+static float fmax0(float x) { return x > 0.0f ? x : 0.0f; }
+
+/*
+ * Scenario counts by migration class when the unit's histograms are read for a
+ * same-depth target of width `width` (section 5.2, section 6.2, section 7):
+ *   n[0] no migration   : width <= n_int
+ *   n[1] intra-stage    : n_int < width <= d_min
+ *   n[3] rollback       : width > d_min and d_min == 0 (a stage lost every replica)
+ *   n[2] inter-stage    : everything else
+ */
+static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int width, uint32_t S, uint32_t n[4])
+{
+    uint32_t none = 0, upto_intra = 0;
+    for (int j = width; j <= D; ++j) { none += hi[j]; upto_intra += hm[j]; }
+    n[0] = none;
+    n[1] = upto_intra - none;
+    n[3] = (width >= 1) ? hm[0] : 0u;
+    n[2] = S - upto_intra - n[3];
+}
+
+/*
+ * Liveput tables of one query (Definition 1 / Eq. 1 and Eq. 4) from histograms
+ * taken over S scenarios.  Levels: 0 = no migration (only untouched pipelines
+ * run), 1 = intra-stage re-routing only, 2 = all live migrations (as many
+ * pipelines as the survivors can fill, floor(survivors / P), capped at D).
+ * teff = expected effective seconds (interval minus the class's migration
+ * cost, not below zero) when the configuration keeps its depth through the
+ * boundary; gain = throughput after migration times teff.
+ * Outputs: liveput [3][T][C], teff [T][C], gain [T][C], each in double (*_d)
+ * and in the fixed float order (*_f).
+ */
+void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
+                  const float *thr, const float *cost, float tau, uint32_t S,
+                  const uint32_t *hist_int, const uint32_t *hist_min,
+                  double *liveput_d, double *teff_d, double *gain_d,
+                  float *liveput_f, float *teff_f, float *gain_f)
+{
+    const int L = thr_off[C];
+    for (int t = 0; t < T; ++t) {
+        for (int c = 0; c < C; ++c) {
+            int D = configs[2 * c], P = configs[2 * c + 1];
+            int M, k;
+            unit_pool(D, P, avail[t + 1], &M, &k);
+            const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
+            const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+            const float *th = thr + thr_off[c];
+            const float *co = cost + 3 * c;
+
+            double a_d = 0.0, b_d = 0.0;
+            float a_f = 0.0f, b_f = 0.0f;
+            for (int j = 0; j <= D; ++j) {
+                a_d += (double)hi[j] * (double)th[j];
+                b_d += (double)hm[j] * (double)th[j];
+                float pa = (float)hi[j] * th[j];
+                float pb = (float)hm[j] * th[j];
+                a_f = a_f + pa;
+                b_f = b_f + pb;
+            }
+            int d_cap = (M - k) / P;
+            int d_star = D < d_cap ? D : d_cap;
+            size_t o = (size_t)t * C + c, lvl = (size_t)T * C;
+            liveput_d[0 * lvl + o] = a_d / (double)S;
+            liveput_d[1 * lvl + o] = b_d / (double)S;
+            liveput_d[2 * lvl + o] = (double)th[d_star];
+            liveput_f[0 * lvl + o] = a_f / (float)S;
+            liveput_f[1 * lvl + o] = b_f / (float)S;
+            liveput_f[2 * lvl + o] = th[d_star];
+
+            uint32_t n[4];
+            class_counts(hi, hm, D, d_star, S, n);
+            double e_d[3];
+            float e_f[3];
+            for (int x = 0; x < 3; ++x) {
+                e_d[x] = dmax0((double)tau - (double)co[x]);
+                e_f[x] = fmax0(tau - co[x]);
+            }
+            double td = ((double)n[0] * (double)tau + (double)n[1] * e_d[0] + (double)n[2] * e_d[1]
+                         + (double)n[3] * e_d[2]) / (double)S;
+            float q0 = (float)n[0] * tau, q1 = (float)n[1] * e_f[0];
+            float q2 = (float)n[2] * e_f[1], q3 = (float)n[3] * e_f[2];
+            float sum = q0 + q1;
+            sum = sum + q2;
+            sum = sum + q3;
+            float tf = sum / (float)S;
+            teff_d[o] = td;
+            teff_f[o] = tf;
+            gain_d[o] = (double)th[d_star] * td;
+            gain_f[o] = th[d_star] * tf;
+        }
+    }
+}
+
+/*
+ * Transition weights W[t][c][c'] = phi of Eq. 4 for leaving configuration c
+ * (run during interval t-1) for c' (run during interval t):
+ *   -inf              if c does not fit avail[t] or c' does not fit avail[t+1],
+ *                     if either depth is below p_min, or if t == 0 and a
+ *                     current configuration is given and c is not it;
+ *   depth changes     thr(c') * max(0, tau - repartition cost of c')   (section 6.2);
+ *   same depth        thr(c') * expected effective seconds, the expectation
+ *                     taken over the unit's scenarios by migration class,
+ *                     costs from the target's row.
+ * Both outputs are [T][C][C], row c, column c' contiguous.
+ */
+void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
+                    const float *thr, const float *cost, float tau, uint32_t S, int p_min, int cur_config,
+                    const uint32_t *hist_int, const uint32_t *hist_min, double *W_d, float *W_f)
+{
+    const int L = thr_off[C];
+    for (int t = 0; t < T; ++t) {
+        for (int c = 0; c < C; ++c) {
+            int D = configs[2 * c], P = configs[2 * c + 1];
+            int from_ok = (D * P <= avail[t]) && (P >= p_min) && (t > 0 || cur_config < 0 || c == cur_config);
+            const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
+            const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+            for (int c2 = 0; c2 < C; ++c2) {
+                int D2 = configs[2 * c2], P2 = configs[2 * c2 + 1];
+                int to_ok = (D2 * P2 <= avail[t + 1]) && (P2 >= p_min);
+                size_t o = ((size_t)t * C + c) * C + c2;
+                if (!from_ok || !to_ok) {
+                    W_d[o] = -INFINITY;
+                    W_f[o] = -INFINITY;
+                    continue;
+                }
+                const float *co = cost + 3 * c2;
+                float full = thr[thr_off[c2] + D2];
+                if (P2 != P) {
+                    W_d[o] = (double)full * dmax0((double)tau - (double)co[2]);
+                    W_f[o] = full * fmax0(tau - co[2]);
+                    continue;
+                }
+                uint32_t n[4];
+                /* a target wider than the source (D2 > D) sums over no bins: nothing is kept or re-routed */
+                class_counts(hi, hm, D, D2, S, n);
+                double e_d[3];
+                float e_f[3];
+                for (int x = 0; x < 3; ++x) {
+                    e_d[x] = dmax0((double)tau - (double)co[x]);
+                    e_f[x] = fmax0(tau - co[x]);
+                }
+                double td = ((double)n[0] * (double)tau + (double)n[1] * e_d[0] + (double)n[2] * e_d[1]
+                             + (double)n[3] * e_d[2]) / (double)S;
+                float q0 = (float)n[0] * tau, q1 = (float)n[1] * e_f[0];
+                float q2 = (float)n[2] * e_f[1], q3 = (float)n[3] * e_f[2];
+                float sum = q0 + q1;
+                sum = sum + q2;
+                sum = sum + q3;
+                float tf = sum / (float)S;
+                W_d[o] = (double)full * td;
+                W_f[o] = full * tf;
+            }
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- dynamic program */
+
+/*
+ * Eq. 6 in float: F[0][c] = 0; F[t+1][c'] = max over c of F[t][c] + W[t][c][c'].
+ * bp[t][c'] = smallest c reaching the max, -1 when the max is -inf.
+ * Then the final max over c (smallest index on ties), and the walk back:
+ * plan[T-1] = best, plan[t-1] = bp[t][plan[t]], start = bp[0][plan[0]].
+ * A query with no finite path gets plan = -1 everywhere, start = -1,
+ * objective = -inf.  Returns 1 if a finite plan exists, else 0.
+ */
+int orc_dp_f32(int T, int C, const float *W, float *F, int32_t *bp, int32_t *plan, int32_t *start,
+               float *objective)
+{
+    for (int c = 0; c < C; ++c) F[c] = 0.0f;
+    for (int t = 0; t < T; ++t) {
+        for (int c2 = 0; c2 < C; ++c2) {
+            float best = -INFINITY;
+            int arg = -1;
+            for (int c = 0; c < C; ++c) {
+                float v = F[(size_t)t * C + c] + W[((size_t)t * C + c) * C + c2];
+                if (v > best) { best = v; arg = c; }
+            }
+            F[(size_t)(t + 1) * C + c2] = best;
+            bp[(size_t)t * C + c2] = arg;
+        }
+    }
+    float top = -INFINITY;
+    int last = -1;
+    for (int c = 0; c < C; ++c)
+        if (F[(size_t)T * C + c] > top) { top = F[(size_t)T * C + c]; last = c; }
+    *objective = top;
+    if (last < 0) {
+        for (int t = 0; t < T; ++t) plan[t] = -1;
+        *start = -1;
+        return 0;
+    }
+    plan[T - 1] = last;
+    for (int t = T - 1; t >= 1; --t) plan[t - 1] = bp[(size_t)t * C + plan[t]];
+    *start = bp[plan[0]];
+    return 1;
+}
+
+/* The same recurrence in double, for the value of the objective only. */
+double orc_dp_f64(int T, int C, const double *W)
+{
+    double *cur = (double *)calloc((size_t)C, sizeof(double));
+    double *nxt = (double *)calloc((size_t)C, sizeof(double));
+    for (int t = 0; t < T; ++t) {
+        for (int c2 = 0; c2 < C; ++c2) {
+            double best = -INFINITY;
+            for (int c = 0; c < C; ++c) {
+                double v = cur[c] + W[((size_t)t * C + c) * C + c2];
+                if (v > best) best = v;
+            }
+            nxt[c2] = best;
+        }
+        double *tmp = cur; cur = nxt; nxt = tmp;
+    }
+    double top = -INFINITY;
+    for (int c = 0; c < C; ++c) if (cur[c] > top) top = cur[c];
+    free(cur);
+    free(nxt);
+    return top;
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,280 @@
+"""Seeded synthetic planning inputs for the liveput optimizer.
+
+This module only *draws inputs* (availability walks, throughput tables,
+migration-cost tables, candidate lists, seeds).  It contains none of the
+method's arithmetic: no sampling of preemption scenarios, no liveput, no
+dynamic program.  Both the CPU oracle's tests and the GPU library's tests and
+benchmark import it so that the two sides see byte-identical arrays.
+
+The recipes stand in for the paper's measured inputs, which are not public:
+predicted availability of a 32-instance spot cluster (section 9.1, Table 1),
+profiled throughputs (appendix C.1) and profiled migration costs (appendix A,
+Table 4).  Shapes follow the paper (N = 32 with a 12-interval look-ahead of
+one-minute intervals in the "small" workload); magnitudes of the three cost
+classes sit inside Table 4's ranges.
+
+Randomness is SplitMix64 (Steele, Lea, Flood 2014), written out here so the
+streams do not depend on the numpy version.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence
+
+import numpy as np
+
+BASE_SEED = 0x240314097
+_GOLDEN = 0x9E3779B97F4A7C15
+_MASK64 = (1 << 64) - 1
+
+
+def _mix64(z: int) -> int:
+    z &= _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
+class SplitMix64:
+    """Sequential SplitMix64 stream."""
+
+    def __init__(self, seed: int):
+        self.state = seed & _MASK64
+
+    def next_u64(self) -> int:
+        self.state = (self.state + _GOLDEN) & _MASK64
+        return _mix64(self.state)
+
+    def uniform(self, lo: float, hi: float) -> float:
+        u = (self.next_u64() >> 11) * (1.0 / (1 << 53))
+        return lo + (hi - lo) * u
+
+    def randint(self, lo: int, hi: int) -> int:
+        """Integer in [lo, hi] (inclusive)."""
+        return lo + self.next_u64() % (hi - lo + 1)
+
+
+@dataclass(frozen=True)
+class WorkloadSpec:
+    """One row of the workload table (sizes, walk and scenario count)."""
+
+    name: str
+    n_queries: int
+    n_instances: int
+    n_intervals: int
+    interval_sec: float
+    depths: Sequence[int]
+    p_min: int
+    walk_step: int
+    burst_drop: int
+    burst_prob: float          # fixed probability, or upper end of U[0, x] if burst_prob_random
+    burst_prob_random: bool
+    avail_floor: int
+    n_scenarios: int
+
+
+WORKLOADS: Dict[str, WorkloadSpec] = {
+    "tiny": WorkloadSpec("tiny", 1, 8, 4, 60.0, (1, 2, 4, 8), 1, 2, 0, 0.0, False, 1, 256),
+    "small": WorkloadSpec("small", 1, 32, 12, 60.0, (1, 2, 4, 8, 16), 2, 4, 8, 0.1, False, 2, 4096),
+    "medium": WorkloadSpec("medium", 1, 64, 30, 60.0, (1, 2, 4, 8, 16, 32), 4, 6, 16, 0.05, False, 4, 16384),
+    "large": WorkloadSpec("large", 1, 256, 60, 30.0, (1, 2, 4, 8, 16, 32, 64), 8, 16, 64, 0.03, False, 8, 65536),
+    "sweep": WorkloadSpec("sweep", 1024, 64, 30, 60.0, (1, 2, 4, 8, 16, 32), 4, 6, 16, 0.15, True, 4, 4096),
+}
+_WORKLOAD_INDEX = {"tiny": 0, "small": 1, "medium": 2, "large": 3, "sweep": 4}
+
+
+@dataclass
+class ProblemBatch:
+    """A batch of planning queries that share the candidate list and sizes.
+
+    Arrays (all C-contiguous numpy):
+      configs     int32  [C, 2]      (D, P) per candidate, sorted by P then D
+      thr_off     int32  [C + 1]     offsets of each candidate's throughput row
+      avail       int32  [nq, T + 1] avail[q, 0] = availability now, avail[q, 1 + t] = interval t
+      thr         float32 [nq, sum(D+1)] thr[q, thr_off[c] + d] = throughput of d pipelines of depth P_c
+      cost        float32 [nq, C, 3] seconds: intra-stage, inter-stage, re-partition
+      seed        uint64 [nq]
+      stream_id   uint32 [nq]
+      cur_config  int32  [nq]        index of the configuration running now, or -1
+    """
+
+    name: str
+    n_instances: int
+    n_intervals: int
+    interval_sec: float
+    p_min: int
+    n_scenarios: int
+    configs: np.ndarray
+    thr_off: np.ndarray
+    avail: np.ndarray
+    thr: np.ndarray
+    cost: np.ndarray
+    seed: np.ndarray
+    stream_id: np.ndarray
+    cur_config: np.ndarray
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def n_queries(self) -> int:
+        return int(self.avail.shape[0])
+
+    @property
+    def n_configs(self) -> int:
+        return int(self.configs.shape[0])
+
+    @property
+    def hist_len(self) -> int:
+        return int(self.thr_off[-1])
+
+    def take(self, queries: Sequence[int]) -> "ProblemBatch":
+        """Sub-batch holding the listed queries."""
+        idx = np.asarray(list(queries), dtype=np.int64)
+        return ProblemBatch(
+            self.name, self.n_instances, self.n_intervals, self.interval_sec, self.p_min,
+            self.n_scenarios, self.configs, self.thr_off,
+            np.ascontiguousarray(self.avail[idx]), np.ascontiguousarray(self.thr[idx]),
+            np.ascontiguousarray(self.cost[idx]), np.ascontiguousarray(self.seed[idx]),
+            np.ascontiguousarray(self.stream_id[idx]), np.ascontiguousarray(self.cur_config[idx]),
+            dict(self.meta))
+
+    def with_scenarios(self, n_scenarios: int) -> "ProblemBatch":
+        """Same inputs with another scenario count (scenario s never depends on the count)."""
+        out = self.take(range(self.n_queries))
+        out.n_scenarios = int(n_scenarios)
+        return out
+
+
+def candidate_list(n_instances: int, depths: Sequence[int], p_min: int, feasible_only: bool = True) -> np.ndarray:
+    """All (D, P) with P in `depths`, D * P <= N, ordered by P then D.
+
+    feasible_only drops depths below the memory floor p_min; otherwise they are
+    kept (the planner treats them as infeasible).
+    """
+    out: List[tuple] = []
+    for p in sorted(set(int(x) for x in depths)):
+        if feasible_only and p < p_min:
+            continue
+        for d in range(1, n_instances // p + 1):
+            out.append((d, p))
+    return np.asarray(out, dtype=np.int32).reshape(-1, 2)
+
+
+def throughput_offsets(configs: np.ndarray) -> np.ndarray:
+    off = np.zeros(configs.shape[0] + 1, dtype=np.int32)
+    np.cumsum(configs[:, 0].astype(np.int64) + 1, out=off[1:])
+    return off
+
+
+def availability_walk(rng: SplitMix64, n: int, t: int, step: int, drop: int, p_drop: float, floor: int) -> np.ndarray:
+    """a[0] = N; a[i] = clip(a[i-1] + U{-step..step} - drop * Bernoulli(p_drop), floor, N)."""
+    a = np.empty(t + 1, dtype=np.int32)
+    a[0] = n
+    cur = n
+    for i in range(1, t + 1):
+        delta = rng.randint(-step, step)
+        burst = drop if (rng.uniform(0.0, 1.0) < p_drop) else 0
+        cur = min(n, max(floor, cur + delta - burst))
+        a[i] = cur
+    return a
+
+
+def throughput_table(configs: np.ndarray, thr_off: np.ndarray, c0: float, c1: float, c2: float) -> np.ndarray:
+    """thr(d, P) = d / (c0 / P + c1 + c2 * (P - 1) / P), evaluated in fp32 in this order."""
+    f = np.float32
+    c0, c1, c2 = f(c0), f(c1), f(c2)
+    out = np.zeros(int(thr_off[-1]), dtype=np.float32)
+    for c in range(configs.shape[0]):
+        d_max, p = int(configs[c, 0]), int(configs[c, 1])
+        denom = f(f(f(c0 / f(p)) + c1) + f(f(c2 * f(p - 1)) / f(p)))
+        for d in range(d_max + 1):
+            out[thr_off[c] + d] = f(f(d) / denom)
+    return out
+
+
+def make_batch(spec: WorkloadSpec, *, dense: bool = False, n_queries: int | None = None,
+               n_scenarios: int | None = None, seed: int | None = None) -> ProblemBatch:
+    """Draw one batch for a workload row.
+
+    dense=True keeps candidate depths below p_min (planner-infeasible rows that
+    make the configuration-by-configuration transition matrix large).
+    """
+    nq = spec.n_queries if n_queries is None else int(n_queries)
+    base = (BASE_SEED + _WORKLOAD_INDEX.get(spec.name, 99)) if seed is None else int(seed)
+    configs = candidate_list(spec.n_instances, spec.depths, spec.p_min, feasible_only=not dense)
+    thr_off = throughput_offsets(configs)
+    n_cfg = configs.shape[0]
+    t = spec.n_intervals
+
+    avail = np.empty((nq, t + 1), dtype=np.int32)
+    thr = np.empty((nq, int(thr_off[-1])), dtype=np.float32)
+    cost = np.empty((nq, n_cfg, 3), dtype=np.float32)
+    seeds = np.empty(nq, dtype=np.uint64)
+    cur = np.empty(nq, dtype=np.int32)
+    p_drops = np.empty(nq, dtype=np.float64)
+    for q in range(nq):
+        rng = SplitMix64(_mix64(base * 0x100000001B3 + q))
+        p_drop = rng.uniform(0.0, spec.burst_prob) if spec.burst_prob_random else spec.burst_prob
+        p_drops[q] = p_drop
+        avail[q] = availability_walk(rng, spec.n_instances, t, spec.walk_step, spec.burst_drop,
+                                     p_drop, spec.avail_floor)
+        c0 = rng.uniform(0.5, 1.0)
+        c1 = rng.uniform(0.02, 0.05)
+        c2 = rng.uniform(0.01, 0.03)
+        thr[q] = throughput_table(configs, thr_off, c0, c1, c2)
+        for c in range(n_cfg):
+            cost[q, c, 0] = rng.uniform(1.0, 3.0)
+            cost[q, c, 1] = rng.uniform(5.0, 15.0)
+            cost[q, c, 2] = rng.uniform(20.0, 60.0)
+        seeds[q] = rng.next_u64()
+        # configuration running now: highest-throughput candidate that fits avail[0] and the memory floor
+        full = thr[q, thr_off[1:] - 1].astype(np.float64)
+        ok = (configs[:, 0] * configs[:, 1] <= avail[q, 0]) & (configs[:, 1] >= spec.p_min)
+        cur[q] = int(np.argmax(np.where(ok, full, -1.0))) if ok.any() else -1
+
+    return ProblemBatch(
+        name=spec.name + ("-dense" if dense else ""),
+        n_instances=spec.n_instances, n_intervals=t, interval_sec=float(spec.interval_sec),
+        p_min=spec.p_min, n_scenarios=spec.n_scenarios if n_scenarios is None else int(n_scenarios),
+        configs=configs, thr_off=thr_off, avail=avail, thr=thr, cost=cost, seed=seeds,
+        stream_id=np.zeros(nq, dtype=np.uint32), cur_config=cur,
+        meta={"burst_prob": p_drops, "base_seed": base, "dense": dense})
+
+
+def workload(name: str, **kw) -> ProblemBatch:
+    """Batch for one of the named workloads: tiny, small, medium, large, sweep."""
+    return make_batch(WORKLOADS[name], **kw)
+
+
+def custom_batch(n_instances: int, configs: Sequence[Sequence[int]], avail: Sequence[Sequence[int]],
+                 thr_per_pipeline: Sequence[float] | None = None, cost: Sequence[Sequence[float]] | None = None,
+                 *, interval_sec: float = 60.0, p_min: int = 1, n_scenarios: int = 256,
+                 seed: int = 1, cur_config: int = -1, thr: np.ndarray | None = None) -> ProblemBatch:
+    """Hand-built batch for small worked examples.
+
+    thr_per_pipeline[c] gives a linear table thr[c][d] = d * thr_per_pipeline[c]
+    unless an explicit flat `thr` is passed.
+    """
+    cfg = np.asarray(configs, dtype=np.int32).reshape(-1, 2)
+    off = throughput_offsets(cfg)
+    av = np.atleast_2d(np.asarray(avail, dtype=np.int32))
+    nq = av.shape[0]
+    if thr is None:
+        row = np.zeros(int(off[-1]), dtype=np.float32)
+        for c in range(cfg.shape[0]):
+            for d in range(int(cfg[c, 0]) + 1):
+                row[off[c] + d] = np.float32(d) * np.float32(thr_per_pipeline[c])
+        thr_arr = np.tile(row, (nq, 1))
+    else:
+        thr_arr = np.ascontiguousarray(np.broadcast_to(np.asarray(thr, dtype=np.float32), (nq, int(off[-1]))))
+    if cost is None:
+        cost_arr = np.tile(np.asarray([2.0, 10.0, 40.0], dtype=np.float32), (nq, cfg.shape[0], 1))
+    else:
+        cost_arr = np.ascontiguousarray(
+            np.broadcast_to(np.asarray(cost, dtype=np.float32).reshape(-1, 3), (nq, cfg.shape[0], 3)))
+    seeds = np.asarray([_mix64(seed + i) for i in range(nq)], dtype=np.uint64)
+    return ProblemBatch(
+        name="custom", n_instances=int(n_instances), n_intervals=av.shape[1] - 1,
+        interval_sec=float(interval_sec), p_min=int(p_min), n_scenarios=int(n_scenarios),
+        configs=cfg, thr_off=off, avail=np.ascontiguousarray(av), thr=np.ascontiguousarray(thr_arr),
+        cost=np.ascontiguousarray(cost_arr), seed=seeds, stream_id=np.zeros(nq, dtype=np.uint32),
+        cur_config=np.full(nq, cur_config, dtype=np.int32))
