@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the liveput optimizer's hot path on one MI355X.
+
+One step = one pass of the whole path (validate inputs, clear and sample histograms, liveput tables,
+look-ahead dynamic program, walk back) over one batch of synthetic planning queries whose inputs are
+already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload sweep|large|medium|small|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as ct
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Plain 32-bit vector ALU issue peak: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz.
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+
+
+def algorithmic_lane_ops(configs, avail, n_scenarios):
+    """Sum over units of S * A(M, k, P): the 32-bit lane operations the method itself needs.
+
+    A(M, k, P) = 33 m + 2 P W + P + W (log2 P + 2) + 10 with m = min(k, M - k) random words (25 operations for a
+    quarter of a Philox4x32-10 block plus 8 for one step of the subset draw), W = ceil(M / 32) mask words (an
+    and + popcount per stage and word, a min per stage, an OR-fold per word for the untouched pipelines) and 10
+    for the two histogram updates.  Units with k = 0 or k = M have a closed form and count as zero.
+    Returns (total lane-ops, scenarios of non-trivial units).
+    """
+    import numpy as np
+    D = configs[:, 0].astype(np.int64)
+    P = configs[:, 1].astype(np.int64)
+    M = D * P
+    k = np.maximum(0, M[None, None, :] - avail[:, 1:, None].astype(np.int64))          # [nq, T, C]
+    m = np.minimum(k, M[None, None, :] - k)
+    W = (M + 31) // 32
+    lg = np.ceil(np.log2(np.maximum(P, 1))).astype(np.int64)
+    fixed = 2 * P * W + P + W * (lg + 2) + 10
+    A = np.where(m > 0, 33 * m + fixed[None, None, :], 0)
+    return float(A.sum()) * n_scenarios, int((m > 0).sum()) * n_scenarios
+
+
+class HipEvents:
+    """HIP events through the runtime torch already loaded (timing on the stream the kernels run on)."""
+
+    def __init__(self):
+        import torch  # noqa: F401
+        self.hip = ct.CDLL("libamdhip64.so.7") if _soname_loaded("libamdhip64.so.7") else ct.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ct.POINTER(ct.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ct.POINTER(ct.c_float), ct.c_void_p, ct.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ct.c_void_p]
+
+    def create(self) -> int:
+        ev = ct.c_void_p()
+        rc = self.hip.hipEventCreate(ct.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        out = ct.c_float(0)
+        rc = self.hip.hipEventElapsedTime(ct.byref(out), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(out.value)
+
+    def destroy(self, ev: int):
+        self.hip.hipEventDestroy(ev)
+
+
+def _soname_loaded(name: str) -> bool:
+    try:
+        with open("/proc/self/maps") as fh:
+            return any(name in line for line in fh)
+    except OSError:
+        return False
+
+
+def cpu_baseline(batch, budget_queries: int):
+    """The oracle, as it stands, on a bounded sample of the same workload (first queries, all scenarios)."""
+    import oracle
+    threads = min(oracle.num_threads(), os.cpu_count() or 1)
+    nq = min(budget_queries, batch.n_queries)
+    units = batch.n_intervals * batch.n_configs
+    s_cpu = min(batch.n_scenarios, max(256, int(2.5e8 // (units * nq))))   # scenario prefix if one query is too big
+    t0 = time.perf_counter()
+    for q in range(nq):
+        oracle.run_query(batch, q, n_scenarios=s_cpu, n_threads=threads)
+    dt = time.perf_counter() - t0
+    scen = nq * units * s_cpu
+    return {"value": scen / dt, "unit": "evals/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nq} of {batch.n_queries} queries, first {s_cpu} of {batch.n_scenarios} scenarios per "
+                      f"unit, sampling + tables + plan, {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="sweep", choices=["tiny", "small", "medium", "large", "sweep"])
+    ap.add_argument("--dense", action="store_true", help="keep candidate depths below the memory floor")
+    ap.add_argument("--queries", type=int, default=None, help="override the number of queries in the batch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU; --gpus N with N > 1 is not supported "
+              "(queries would shard across GPUs with no exchange, which this build does not launch)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2403_14097_amd as pk
+    import parcae_inputs as pi
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    pk.load_library()
+
+    batch = pi.workload(args.workload, dense=args.dense, n_queries=args.queries)
+    prob = pk.upload(batch, device="cuda:0")
+    ev_out = pk.alloc_eval_out(prob)
+    pl_out = pk.alloc_plan_out(prob)
+    nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
+    scenarios = nq * T * C * S
+    cells = nq * T * C * C
+    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S)
+
+    events = HipEvents()
+    pairs = [(events.create(), events.create()) for _ in range(args.steps)]
+
+    for _ in range(args.warmup):
+        pk.parcae_liveput_plan(prob, ev_out, pl_out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        prob.event_before_sampling, prob.event_after_sampling = pairs[i]
+        pk.parcae_liveput_plan(prob, ev_out, pl_out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prob.event_before_sampling = prob.event_after_sampling = None
+    kern_ms = [events.elapsed_ms(a, b) for a, b in pairs]
+    for a, b in pairs:
+        events.destroy(a)
+        events.destroy(b)
+    kern_avg_s = sum(kern_ms) / len(kern_ms) / 1e3
+
+    # the DP alone, from the histograms already in memory (same timed-region rules)
+    for _ in range(2):
+        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dp_reps = max(3, args.steps)
+    for _ in range(dp_reps):
+        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
+    torch.cuda.synchronize()
+    dp_s = (time.perf_counter() - t1) / dp_reps
+
+    status = pl_out.status.cpu().numpy()
+    ms_per_step = dt / args.steps * 1e3
+    achieved = alg_ops / kern_avg_s
+    out = {
+        "metric": "liveput_evals_per_sec",
+        "value": scenarios / (dt / args.steps),
+        "unit": "evals/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32+f32",
+        "data": "synthetic",
+        "config": {"workload": batch.name, "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
+                   "n_configs": C, "n_scenarios": S, "scenarios_per_step": scenarios,
+                   "nontrivial_scenarios_per_step": nontrivial, "dp_cells_per_step": cells,
+                   "infeasible_queries": int((status != 0).sum())},
+        "nontrivial_evals_per_sec": nontrivial / (dt / args.steps),
+        "dp_cells_per_sec": cells / dp_s,
+        "dp_ms": dp_s * 1e3,
+        "sampling_kernel_ms": kern_avg_s * 1e3,
+        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
+                     "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
+                     "kernel": "eval_hist_kernel", "algorithmic_lane_ops_per_launch": alg_ops},
+    }
+    if not args.no_cpu_baseline:
+        per_query = T * C * S
+        budget = args.cpu_queries or max(1, min(nq, int(2.5e8 // max(per_query, 1)) or 1))
+        out["cpu_baseline"] = cpu_baseline(batch, budget)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,251 @@
+/*
+ * parcae.h - C ABI of the liveput optimizer's hot path on one AMD CDNA4 GPU.
+ *
+ * The library evaluates, for every candidate parallel configuration (D
+ * data-parallel pipelines x P pipeline stages) and every look-ahead interval,
+ * the Monte-Carlo statistics that liveput needs (Parcae, arXiv 2403.14097,
+ * Definition 1 / Eq. 1 and section 6.3), and runs the look-ahead dynamic program
+ * that picks the configuration sequence with the most committed samples net of
+ * migration cost (Eq. 3-6, section 6.2).
+ *
+ * ------------------------------------------------------------------------
+ * Conventions common to all calls
+ * ------------------------------------------------------------------------
+ * Memory.  A pointer is marked HOST or DEVICE.  The caller owns every buffer;
+ * the library allocates nothing, frees nothing and keeps no state between
+ * calls.  DEVICE buffers must be ordinary device allocations of the current
+ * HIP device and must not overlap each other.  HOST data is read before the
+ * call returns.
+ *
+ * Asynchrony.  Work is enqueued on `stream` (a hipStream_t passed as void*,
+ * NULL = the null stream).  Outputs are valid once the stream has been
+ * synchronised.  No call synchronises the device; a call enqueues kernels
+ * only (no memset or memcpy nodes: memory is cleared by kernels and the
+ * candidate table travels as kernel arguments).
+ *
+ * Errors.  Every call returns 0 (PARCAE_OK) or a negative code.  Shape errors
+ * that the host can see (NULL pointers, sizes out of range, candidate list not
+ * sorted, workspace too small) are returned at once and nothing is enqueued.
+ * Errors that live in DEVICE data are found by the kernels and reported per
+ * query in the DEVICE array `status` (see parcae_liveput_plan).  The library
+ * never throws, never writes errno and never prints.
+ *
+ * ------------------------------------------------------------------------
+ * The problem (one batch of nq independent planning queries)
+ * ------------------------------------------------------------------------
+ * All queries of a batch share N, T, the interval length, the candidate list
+ * and the scenario count; each query has its own availability sequence,
+ * throughput table, cost table, seed and current configuration.
+ *
+ * Candidate c = (D_c, P_c): D_c >= 1, P_c >= 1, D_c * P_c <= N <= 256.  The
+ * list is strictly increasing in (P, D) lexicographic order (so index order
+ * prefers shallower, then narrower configurations when the planner breaks
+ * ties).  off[c] = sum over c' < c of (D_c' + 1); L = off[C].
+ *
+ * Availability (section 4.2): avail[q][0] is the number of instances now,
+ * avail[q][1 + t] is the predicted number in look-ahead interval t,
+ * t = 0..T-1; every entry lies in [0, N].  Preemptions and allocations happen
+ * only at interval starts.
+ *
+ * Throughput: thr[q][off[c] + d] = samples per second of d pipelines of depth
+ * P_c, d = 0..D_c; finite, >= 0, thr[q][off[c]] == 0.  A configuration that
+ * does not fit device memory is expressed by P_c < p_min (section 6.2: such a
+ * configuration has no throughput and is never chosen).
+ *
+ * Migration cost (section 5.2, section 8.4): cost[q][c] = seconds of an
+ * intra-stage migration, an inter-stage migration and a re-partition
+ * (pipeline migration) INTO configuration c; finite, 0 <= intra <= inter <=
+ * re-partition.
+ */
+#ifndef PARCAE_H
+#define PARCAE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PARCAE_MAX_INSTANCES 256        /* N limit: one preemption mask is 256 bits */
+#define PARCAE_MAX_SCENARIOS 16777216   /* S limit: counts stay exact in float      */
+#define PARCAE_MASK_WORDS 8
+
+#define PARCAE_OK 0
+#define PARCAE_EINVAL (-1)       /* bad argument or bad input data                       */
+#define PARCAE_EWORKSPACE (-2)   /* workspace NULL, misaligned (256 B) or too small      */
+#define PARCAE_EHIP (-3)         /* a HIP call or kernel launch failed                   */
+#define PARCAE_EINFEASIBLE (-4)  /* per query: no configuration sequence is feasible     */
+
+typedef struct parcae_config {
+    int32_t D; /* data-parallel pipelines */
+    int32_t P; /* pipeline stages         */
+} parcae_config;
+
+typedef struct parcae_problem {
+    int32_t n_queries;   /* nq >= 1                                                     */
+    int32_t n_instances; /* N, 1..PARCAE_MAX_INSTANCES                                  */
+    int32_t n_intervals; /* T >= 1 look-ahead intervals (the paper's I)                 */
+    int32_t n_configs;   /* C >= 1, C * T < 2^31                                        */
+    int32_t n_scenarios; /* S, 1..PARCAE_MAX_SCENARIOS Monte-Carlo scenarios per (t, c) */
+    int32_t p_min;       /* smallest pipeline depth that fits device memory             */
+    float interval_sec;  /* interval length in seconds (the paper's T), > 0, finite     */
+    uint32_t flags;      /* must be 0                                                   */
+    const parcae_config *configs; /* HOST   [C]                                         */
+    const int32_t *avail;         /* DEVICE [nq][T + 1]                                 */
+    const float *thr;             /* DEVICE [nq][L]                                     */
+    const float *cost;            /* DEVICE [nq][C][3]                                  */
+    const uint64_t *seed;         /* DEVICE [nq]  Philox key of the query               */
+    const uint32_t *stream_id;    /* DEVICE [nq] or NULL (= 0): Philox counter word 3   */
+    const int32_t *cur_config;    /* DEVICE [nq] or NULL (= -1): index of the
+                                     configuration running now, -1 = any               */
+    void *event_before_sampling;  /* hipEvent_t or NULL: recorded on the stream right
+                                     before the scenario sampling kernel is launched   */
+    void *event_after_sampling;   /* hipEvent_t or NULL: recorded right after it       */
+} parcae_problem;
+
+/*
+ * ------------------------------------------------------------------------
+ * What is computed (the definitions every entry point refers to)
+ * ------------------------------------------------------------------------
+ * Unit (q, t, c): configuration c, running in interval t - 1 (now, for
+ * t = 0), meets the boundary into interval t.  Its M = D * P instances lose
+ * k = max(0, M - avail[q][1 + t]) of them (section 4.2: N- = max(0, N_{i-1} -
+ * N_i), here for the instances the job uses).  Logical instance j = d * P + s
+ * is stage s of pipeline d.
+ *
+ * Scenario s of a unit (section 6.3, section 5.1: every instance equally
+ * likely) is a k-subset of [0, M) drawn as follows.  Random word i is output
+ * word (i mod 4) of Philox4x32-10 (Salmon et al., SC'11; multipliers
+ * 0xD2511F53, 0xCD9E8D57; key increments 0x9E3779B9, 0xBB67AE85) with
+ * key = (seed & 0xffffffff, seed >> 32) and counter = (s, i / 4, t * C + c,
+ * stream_id).  With m = min(k, M - k): start from the empty set; for
+ * i = 0..m-1: j = M - m + i, r = (word(i) * (j + 1)) >> 32 (64-bit product);
+ * insert j if r is already in the set, else insert r.  The preempted set is
+ * that set if k <= M - k, otherwise its complement in [0, M).
+ *
+ * Per scenario (section 5.2, section 7): occ_s = alive instances of stage s;
+ * d_min = min over s of occ_s (pipelines that intra-stage re-routing can
+ * complete; 0 = a stage lost every replica, only a checkpoint rollback
+ * helps); n_int = pipelines that lost no instance.
+ *   hist_int[q][t][off[c] + n_int] and hist_min[q][t][off[c] + d_min]
+ * count the S scenarios of the unit.
+ *
+ * Migration class of a scenario for a same-depth target of width w:
+ * none if w <= n_int; else intra-stage if w <= d_min; else rollback if
+ * d_min == 0; else inter-stage.  Class costs: 0, cost[.][0], cost[.][1], and
+ * cost[.][2] for a rollback.  From the histograms of a unit and a width w
+ * (bins above D count as empty):
+ *   n0 = sum_{j >= w} hist_int[j], n01 = sum_{j >= w} hist_min[j],
+ *   n1 = n01 - n0, n3 = (w >= 1 ? hist_min[0] : 0), n2 = S - n01 - n3,
+ *   e_x = max(0, tau - cost[.][x]),
+ *   teff(w, cost row) = (((float)n0 * tau + (float)n1 * e_0) + (float)n2 * e_1
+ *                        + (float)n3 * e_2) / (float)S
+ * evaluated in float exactly in this order, every product and sum rounded
+ * separately (no fused multiply-add), one correctly rounded division.
+ *
+ * Liveput tables (Eq. 1, Eq. 4), all float, sums in ascending bin order,
+ * acc = acc + (float)count * thr (product and sum rounded separately):
+ *   liveput[q][0][t][c] = (sum_j hist_int[j] * thr[c][j]) / S   no migration
+ *   liveput[q][1][t][c] = (sum_j hist_min[j] * thr[c][j]) / S   intra-stage only
+ *   liveput[q][2][t][c] = thr[c][D*], D* = min(D, (M - k) / P)  all live migrations
+ *   teff[q][t][c] = teff(D*, cost[q][c]);  gain[q][t][c] = thr[c][D*] * teff[q][t][c]
+ *
+ * Transition weight (Eq. 4 with the rule of section 6.2), c -> c' at step t:
+ *   -inf if D*P > avail[q][t] or P < p_min or D'*P' > avail[q][1+t] or
+ *        P' < p_min, or if t == 0, cur_config[q] >= 0 and c != cur_config[q];
+ *   thr[c'][D'] * max(0, tau - cost[q][c'][2])           if P' != P;
+ *   thr[c'][D'] * teff(D', cost[q][c']) of unit (q,t,c)  if P' == P.
+ *
+ * Dynamic program (Eq. 6): F[q][0][c] = 0; F[q][t+1][c'] = max over c of
+ * F[q][t][c] + W_t[c][c'] in float; bp[q][t][c'] = the smallest c reaching the
+ * maximum, or -1 if it is -inf.  best = smallest arg-max of F[q][T][.];
+ * objective[q] = F[q][T][best]; plan[q][T-1] = best, plan[q][t-1] =
+ * bp[q][t][plan[q][t]], start[q] = bp[q][0][plan[q][0]].  plan[q][t] is the
+ * configuration to run in interval t.  If objective is -inf the query is
+ * infeasible (section 7: training would be suspended): plan and start are -1.
+ */
+
+/* Bytes of DEVICE workspace the calls below need for this problem (HOST out). */
+int parcae_workspace_bytes(const parcae_problem *p, size_t *bytes);
+
+/* L = sum of (D_c + 1) over the HOST candidate list, or a negative code. */
+int64_t parcae_hist_len(const parcae_config *configs, int32_t n_configs);
+
+/*
+ * Monte-Carlo liveput evaluation (section 6.3, Eq. 1, Eq. 4).
+ *   hist_int, hist_min  DEVICE out [nq][T][L] uint32, required, overwritten
+ *   liveput             DEVICE out [nq][3][T][C] float, or NULL
+ *   teff, gain          DEVICE out [nq][T][C] float, or NULL
+ *   status              DEVICE out [nq] int32, or NULL: PARCAE_OK, or PARCAE_EINVAL
+ *                       if the query's DEVICE inputs break the rules above (its
+ *                       other outputs are then computed from clamped inputs and
+ *                       carry no meaning)
+ *   workspace           DEVICE, 256-byte aligned, >= parcae_workspace_bytes()
+ */
+int parcae_liveput_eval(const parcae_problem *p, uint32_t *hist_int, uint32_t *hist_min, float *liveput,
+                        float *teff, float *gain, int32_t *status, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
+ * Look-ahead plan from histograms computed earlier (section 6.3 notes that the
+ * sampling can be done in advance; Eq. 6).
+ *   hist_int, hist_min  DEVICE in  [nq][T][L]
+ *   F                   DEVICE out [nq][T + 1][C] float, or NULL
+ *   bp                  DEVICE out [nq][T][C] int32, or NULL
+ *   plan                DEVICE out [nq][T] int32, required
+ *   start               DEVICE out [nq] int32, or NULL
+ *   objective           DEVICE out [nq] float, or NULL
+ *   status              DEVICE out [nq] int32, or NULL: PARCAE_OK, PARCAE_EINVAL
+ *                       (bad DEVICE inputs) or PARCAE_EINFEASIBLE
+ */
+int parcae_plan_from_hist(const parcae_problem *p, const uint32_t *hist_int, const uint32_t *hist_min, float *F,
+                          int32_t *bp, int32_t *plan, int32_t *start, float *objective, int32_t *status,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The whole path: parcae_liveput_eval followed by parcae_plan_from_hist on the
+ * same stream (algorithm 1's LiveputOpt step: current configuration and
+ * availability sequence in, configuration sequence out).  Arguments as above.
+ */
+int parcae_liveput_plan(const parcae_problem *p, uint32_t *hist_int, uint32_t *hist_min, float *liveput,
+                        float *teff, float *gain, float *F, int32_t *bp, int32_t *plan, int32_t *start,
+                        float *objective, int32_t *status, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
+ * Transition weights written out (Eq. 4, section 6.2).
+ *   W  DEVICE out [nq][T][C][C] float; row c (source), column c' (target) contiguous
+ */
+int parcae_transition_weights(const parcae_problem *p, const uint32_t *hist_int, const uint32_t *hist_min,
+                              float *W, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Max-plus dynamic program on transition weights held in memory (Eq. 6).
+ *   W  DEVICE in [nq][T][C][C] float; entries are finite or -inf (never NaN or +inf)
+ *   other arguments as in parcae_plan_from_hist; status is PARCAE_OK or
+ *   PARCAE_EINFEASIBLE.  Needs no workspace.  C <= 4096.
+ */
+int parcae_dp_plan(const float *W, int32_t n_queries, int32_t n_intervals, int32_t n_configs, float *F,
+                   int32_t *bp, int32_t *plan, int32_t *start, float *objective, int32_t *status, void *stream);
+
+/*
+ * Scenarios [s0, s0 + ns) of unit (q, t, c), one by one (section 6.3).
+ *   masks  DEVICE out [ns][8] uint32: bit (j mod 32) of word (j / 32) is set
+ *          iff logical instance j is preempted
+ *   n_int, d_min  DEVICE out [ns] int32
+ */
+int parcae_debug_sample(const parcae_problem *p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,
+                        uint32_t *masks, int32_t *n_int, int32_t *d_min, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* Static, NUL-terminated description of a return code (HOST). */
+const char *parcae_strerror(int code);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int parcae_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARCAE_H */

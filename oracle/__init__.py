@@ -86,6 +86,16 @@ def debug_sample(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: i
     return masks, n_int, d_min
 
 
+def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s_begin: int, s_end: int):
+    """Histograms [D + 1] of one unit (unit = t * C + c) over scenarios [s_begin, s_end)."""
+    hi = np.zeros(D + 1, dtype=np.uint32)
+    hm = np.zeros(D + 1, dtype=np.uint32)
+    lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(a_next), ct.c_uint64(seed), ct.c_uint32(stream_id),
+                        ct.c_uint32(unit), ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32),
+                        _p(hm, ct.c_uint32))
+    return hi, hm
+
+
 def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1):
     """Histograms [T][L] of one query over scenarios [s_begin, s_end)."""
     configs = np.ascontiguousarray(configs, dtype=np.int32)

@@ -157,6 +157,26 @@ void orc_debug_sample(int D, int P, int a_next, uint64_t seed, uint32_t stream_i
 }
 
 /*
+ * Histograms of a single unit over scenarios [s_begin, s_end): bins [D + 1] each, overwritten.
+ * unit = t * C + c is the value that enters the random-word counter.
+ */
+void orc_eval_unit(int D, int P, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+                   uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min)
+{
+    uint8_t pre[ORC_MAX_INSTANCES];
+    int M, k;
+    unit_pool(D, P, a_next, &M, &k);
+    for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; }
+    for (uint32_t s = s_begin; s < s_end; ++s) {
+        int ni, dm;
+        orc_sample_preempted(M, k, seed, stream_id, unit, s, pre);
+        orc_reduce(D, P, pre, &ni, &dm, NULL);
+        bins_int[ni] += 1u;
+        bins_min[dm] += 1u;
+    }
+}
+
+/*
  * Histograms of one query over scenarios [s_begin, s_end):
  *   hist_int[t][off[c] + n_int] += 1, hist_min[t][off[c] + d_min] += 1.
  * configs = (D, P) pairs; avail[0] = availability now, avail[1 + t] = a_t.

@@ -1,0 +1,318 @@
+// C ABI of the liveput optimizer's hot path: argument checks, workspace layout and kernel launches.
+// The semantics of every entry point are stated in include/parcae.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "../../include/parcae.h"
+#include "device_common.hpp"
+#include "eval_kernels.hpp"
+#include "plan_kernels.hpp"
+
+namespace {
+
+using parcae::Batch;
+using parcae::CfgRec;
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxConfigsDp = 4096;
+constexpr size_t kMaxPlanLds = 64 * 1024;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t cfg_off, valid_off, bp_off, total;
+    int64_t L;
+};
+
+// Host-visible shape checks; fills the packed candidate table.
+int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* lay)
+{
+    if (!p || !p->configs || !p->avail || !p->thr || !p->cost || !p->seed) return PARCAE_EINVAL;
+    if (p->n_queries < 1 || p->n_intervals < 1 || p->n_configs < 1) return PARCAE_EINVAL;
+    if (p->n_instances < 1 || p->n_instances > PARCAE_MAX_INSTANCES) return PARCAE_EINVAL;
+    if (p->n_scenarios < 1 || p->n_scenarios > PARCAE_MAX_SCENARIOS) return PARCAE_EINVAL;
+    if (p->flags != 0u) return PARCAE_EINVAL;
+    if (!(p->interval_sec > 0.0f) || !std::isfinite(p->interval_sec)) return PARCAE_EINVAL;
+    if ((int64_t)p->n_configs * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    int64_t L = 0;
+    if (table) table->resize((size_t)p->n_configs);
+    for (int c = 0; c < p->n_configs; ++c) {
+        const parcae_config g = p->configs[c];
+        if (g.D < 1 || g.P < 1 || (int64_t)g.D * g.P > p->n_instances) return PARCAE_EINVAL;
+        if (c > 0) {
+            const parcae_config h = p->configs[c - 1];
+            if (!(h.P < g.P || (h.P == g.P && h.D < g.D))) return PARCAE_EINVAL;  // strictly increasing (P, D)
+        }
+        if (table) {
+            int lg = -1;
+            if ((g.P & (g.P - 1)) == 0) {
+                lg = 0;
+                while ((1 << lg) < g.P) ++lg;
+            }
+            (*table)[(size_t)c] = CfgRec{g.D, g.P, (int32_t)L, lg};
+        }
+        L += g.D + 1;
+    }
+    if ((int64_t)p->n_queries * p->n_intervals * L >= (int64_t)1 << 40) return PARCAE_EINVAL;
+    if (lay) {
+        lay->L = L;
+        lay->cfg_off = 0;
+        lay->valid_off = align_up(sizeof(CfgRec) * (size_t)p->n_configs);
+        lay->bp_off = lay->valid_off + align_up(sizeof(int32_t) * (size_t)p->n_queries);
+        lay->total = lay->bp_off +
+                     align_up(sizeof(int32_t) * (size_t)p->n_queries * (size_t)p->n_intervals * (size_t)p->n_configs);
+    }
+    return PARCAE_OK;
+}
+
+int check_workspace(const Layout& lay, const void* ws, size_t bytes)
+{
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || bytes < lay.total) return PARCAE_EWORKSPACE;
+    return PARCAE_OK;
+}
+
+Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
+{
+    Batch b;
+    b.nq = p->n_queries; b.N = p->n_instances; b.T = p->n_intervals; b.C = p->n_configs; b.S = p->n_scenarios;
+    b.p_min = p->p_min; b.L = (int32_t)lay.L; b.tau = p->interval_sec;
+    b.cfg = reinterpret_cast<const CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
+    b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
+    b.cur_config = p->cur_config;
+    return b;
+}
+
+// The candidate table reaches the device as kernel arguments, a slice at a time: no host-to-device
+// copy is enqueued, so the host vector may go away as soon as the launches are made.
+constexpr int kTableSlice = 120;
+struct TableSlice {
+    CfgRec rec[kTableSlice];
+};
+
+__global__ void __launch_bounds__(128) table_slice_kernel(TableSlice slice, int count, CfgRec* __restrict__ dst)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = slice.rec[i];
+}
+
+// Writes the candidate table into the workspace and checks the device inputs of every query.
+int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+{
+    CfgRec* dst = reinterpret_cast<CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
+    for (size_t first = 0; first < table.size(); first += kTableSlice) {
+        TableSlice slice;
+        const int count = (int)((table.size() - first < (size_t)kTableSlice) ? table.size() - first : kTableSlice);
+        std::memcpy(slice.rec, table.data() + first, sizeof(CfgRec) * (size_t)count);
+        if (count < kTableSlice) std::memset(slice.rec + count, 0, sizeof(CfgRec) * (size_t)(kTableSlice - count));
+        table_slice_kernel<<<dim3(1), dim3(128), 0, st>>>(slice, count, dst + first);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
+    int32_t* valid = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
+    parcae::validate_kernel<<<dim3((unsigned)b.nq), dim3(256), 0, st>>>(b, valid);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+int32_t* valid_ptr(const Layout& lay, void* ws)
+{
+    return reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
+}
+
+// Scenarios per block of the sampling kernel.
+int pick_chunk_len(int S) { return S < 2048 ? S : 2048; }
+
+int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void* ws, uint32_t* hist_int,
+                uint32_t* hist_min, float* liveput, float* teff, float* gain, int32_t* status, hipStream_t st)
+{
+    const int64_t n_units = (int64_t)b.nq * b.T * b.C;
+    const int chunk_len = pick_chunk_len(b.S);
+    const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
+    if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;
+
+    const int64_t elems = (int64_t)b.nq * b.T * b.L;
+    int64_t prep_blocks = (elems + 255) / 256;
+    if (prep_blocks > 65536) prep_blocks = 65536;
+    parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, hist_int, hist_min);
+    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+
+    if (p->event_before_sampling &&
+        hipEventRecord(static_cast<hipEvent_t>(p->event_before_sampling), st) != hipSuccess)
+        return PARCAE_EHIP;
+    parcae::eval_hist_kernel<<<dim3((unsigned)(n_units * n_chunks)), dim3(parcae::kEvalThreads), 0, st>>>(
+        b, n_chunks, chunk_len, hist_int, hist_min);
+    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    if (p->event_after_sampling &&
+        hipEventRecord(static_cast<hipEvent_t>(p->event_after_sampling), st) != hipSuccess)
+        return PARCAE_EHIP;
+
+    if (liveput || teff || gain) {
+        parcae::finalise_kernel<<<dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, st>>>(b, hist_int, hist_min,
+                                                                                                 liveput, teff, gain);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
+    if (status) {
+        parcae::status_from_valid_kernel<<<dim3((unsigned)((b.nq + 255) / 256)), dim3(256), 0, st>>>(
+            b.nq, valid_ptr(lay, ws), status, PARCAE_EINVAL);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
+    return PARCAE_OK;
+}
+
+int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* hist_int, const uint32_t* hist_min,
+                float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
+                hipStream_t st)
+{
+    const size_t lds = parcae::plan_lds_bytes(b.C, b.L);
+    if (lds > kMaxPlanLds) return PARCAE_EINVAL;
+    int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.bp_off);
+    parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(256), lds, st>>>(
+        b, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status, PARCAE_EINVAL,
+        PARCAE_EINFEASIBLE);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int parcae_version(void) { return 100; }
+
+const char* parcae_strerror(int code)
+{
+    switch (code) {
+        case PARCAE_OK: return "ok";
+        case PARCAE_EINVAL: return "invalid argument or input data";
+        case PARCAE_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case PARCAE_EHIP: return "HIP call or kernel launch failed";
+        case PARCAE_EINFEASIBLE: return "no feasible configuration sequence";
+        default: return "unknown parcae error code";
+    }
+}
+
+int64_t parcae_hist_len(const parcae_config* configs, int32_t n_configs)
+{
+    if (!configs || n_configs < 1) return PARCAE_EINVAL;
+    int64_t L = 0;
+    for (int c = 0; c < n_configs; ++c) {
+        if (configs[c].D < 1 || configs[c].D > PARCAE_MAX_INSTANCES) return PARCAE_EINVAL;
+        L += configs[c].D + 1;
+    }
+    return L;
+}
+
+int parcae_workspace_bytes(const parcae_problem* p, size_t* bytes)
+{
+    if (!bytes) return PARCAE_EINVAL;
+    Layout lay;
+    const int rc = check_problem(p, nullptr, &lay);
+    if (rc != PARCAE_OK) return rc;
+    *bytes = lay.total;
+    return PARCAE_OK;
+}
+
+int parcae_liveput_eval(const parcae_problem* p, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
+                        float* gain, int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(p, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!hist_int || !hist_min) return PARCAE_EINVAL;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    return launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, status, st);
+}
+
+int parcae_plan_from_hist(const parcae_problem* p, const uint32_t* hist_int, const uint32_t* hist_min, float* F,
+                          int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(p, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+}
+
+int parcae_liveput_plan(const parcae_problem* p, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
+                        float* gain, float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective,
+                        int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(p, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    if (parcae::plan_lds_bytes(p->n_configs, (int)lay.L) > kMaxPlanLds) return PARCAE_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
+        return rc;
+    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+}
+
+int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int, const uint32_t* hist_min, float* W,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(p, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!hist_int || !hist_min || !W) return PARCAE_EINVAL;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    const size_t lds = parcae::plan_lds_bytes(p->n_configs, (int)lay.L);
+    if (lds > kMaxPlanLds) return PARCAE_EINVAL;
+    if ((int64_t)p->n_queries * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    parcae::transition_kernel<<<dim3((unsigned)(b.nq * b.T)), dim3(256), lds, st>>>(b, hist_int, hist_min, W);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+int parcae_dp_plan(const float* W, int32_t n_queries, int32_t n_intervals, int32_t n_configs, float* F, int32_t* bp,
+                   int32_t* plan, int32_t* start, float* objective, int32_t* status, void* stream)
+{
+    if (!W || !bp || !plan) return PARCAE_EINVAL;
+    if (n_queries < 1 || n_intervals < 1 || n_configs < 1 || n_configs > kMaxConfigsDp) return PARCAE_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t lds = 2 * sizeof(float) * (size_t)n_configs;
+    parcae::dp_kernel<<<dim3((unsigned)n_queries), dim3(256), lds, st>>>(W, n_intervals, n_configs, F, bp, plan, start,
+                                                                         objective, status, PARCAE_EINFEASIBLE);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+int parcae_debug_sample(const parcae_problem* p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,
+                        uint32_t* masks, int32_t* n_int, int32_t* d_min, void* workspace, size_t workspace_bytes,
+                        void* stream)
+{
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(p, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!masks || !n_int || !d_min) return PARCAE_EINVAL;
+    if (q < 0 || q >= p->n_queries || t < 0 || t >= p->n_intervals || c < 0 || c >= p->n_configs) return PARCAE_EINVAL;
+    if (ns == 0u) return PARCAE_OK;
+    if ((uint64_t)s0 + ns > (uint64_t)1 << 32 || ns > (1u << 30)) return PARCAE_EINVAL;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    parcae::debug_sample_kernel<<<dim3((ns + 255u) / 256u), dim3(256), 0, st>>>(b, q, t, c, s0, ns, masks, n_int,
+                                                                                  d_min);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+}  // extern "C"

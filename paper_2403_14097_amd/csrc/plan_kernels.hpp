@@ -1,0 +1,368 @@
+// Liveput tables, transition weights and the max-plus dynamic program (Eq. 1, Eq. 4, Eq. 6, section 6.2).
+//
+// All float arithmetic here is written with explicit round-to-nearest intrinsics so that
+// no product and sum are ever fused: the integer plan must not depend on contraction.
+#pragma once
+
+#include "device_common.hpp"
+
+namespace parcae {
+
+constexpr float kNegInf = -__builtin_inff();
+
+__device__ __forceinline__ float max0(float x) { return x > 0.0f ? x : 0.0f; }
+
+// Expected effective seconds from the class counts of a unit read at width w (see the header's teff()).
+// n0 = scenarios needing no migration, n01 = those needing at most intra-stage migration,
+// h0 = scenarios that lost a whole stage.
+__device__ __forceinline__ float teff_from_counts(uint32_t n0, uint32_t n01, uint32_t h0, int w, uint32_t S,
+                                                  float tau, float e0, float e1, float e2)
+{
+    const uint32_t n1 = n01 - n0;
+    const uint32_t n3 = (w >= 1) ? h0 : 0u;
+    const uint32_t n2 = S - n01 - n3;
+    const float q0 = __fmul_rn((float)n0, tau);
+    const float q1 = __fmul_rn((float)n1, e0);
+    const float q2 = __fmul_rn((float)n2, e1);
+    const float q3 = __fmul_rn((float)n3, e2);
+    float sum = __fadd_rn(q0, q1);
+    sum = __fadd_rn(sum, q2);
+    sum = __fadd_rn(sum, q3);
+    return __fdiv_rn(sum, (float)S);
+}
+
+// ------------------------------------------------------------------ input checks
+
+// valid[q] = 1 if the query's device inputs obey the documented ranges, else 0.  One block per query.
+__global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restrict__ valid)
+{
+    __shared__ int bad;
+    const int q = blockIdx.x;
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    int my_bad = 0;
+    for (int i = threadIdx.x; i <= b.T; i += blockDim.x) {
+        const int a = b.avail[(int64_t)q * (b.T + 1) + i];
+        if (a < 0 || a > b.N) my_bad = 1;
+    }
+    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+        const CfgRec cr = b.cfg[c];
+        const float* th = b.thr + (int64_t)q * b.L + cr.off;
+        if (!(th[0] == 0.0f)) my_bad = 1;
+        for (int d = 1; d <= cr.D; ++d) {
+            const float v = th[d];
+            if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
+        }
+        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+        const float c0 = co[0], c1 = co[1], c2 = co[2];
+        if (!(c0 >= 0.0f) || !(c0 <= c1) || !(c1 <= c2) || !(c2 < __builtin_inff())) my_bad = 1;
+    }
+    if (threadIdx.x == 0 && b.cur_config) {
+        const int cur = b.cur_config[q];
+        if (cur < -1 || cur >= b.C) my_bad = 1;
+    }
+    if (my_bad) atomicOr(&bad, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) valid[q] = bad ? 0 : 1;
+}
+
+__global__ void __launch_bounds__(256) status_from_valid_kernel(int nq, const int32_t* __restrict__ valid,
+                                                                int32_t* __restrict__ status, int einval)
+{
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nq) status[q] = valid[q] ? 0 : einval;
+}
+
+// ------------------------------------------------------------------ liveput tables (Eq. 1, Eq. 4)
+
+// One thread per unit (q, t, c).
+__global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+                                                       const uint32_t* __restrict__ hist_min,
+                                                       float* __restrict__ liveput, float* __restrict__ teff,
+                                                       float* __restrict__ gain)
+{
+    const int64_t n_units = (int64_t)b.nq * b.T * b.C;
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= n_units) return;
+    const int c = (int)(u % b.C);
+    const int64_t qt = u / b.C;
+    const int t = (int)(qt % b.T);
+    const int q = (int)(qt / b.T);
+    const CfgRec cr = b.cfg[c];
+    int M, k;
+    unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+    const uint32_t* hi = hist_int + qt * b.L + cr.off;
+    const uint32_t* hm = hist_min + qt * b.L + cr.off;
+    const float* th = b.thr + (int64_t)q * b.L + cr.off;
+    const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+    const int d_cap = (M - k) / cr.P;
+    const int d_star = cr.D < d_cap ? cr.D : d_cap;
+    const uint32_t S = (uint32_t)b.S;
+
+    float acc_i = 0.0f, acc_m = 0.0f;
+    uint32_t n0 = 0u, n01 = 0u;
+    for (int j = 0; j <= cr.D; ++j) {
+        const uint32_t a = hi[j], m = hm[j];
+        const float w = th[j];
+        acc_i = __fadd_rn(acc_i, __fmul_rn((float)a, w));
+        acc_m = __fadd_rn(acc_m, __fmul_rn((float)m, w));
+        if (j >= d_star) {
+            n0 += a;
+            n01 += m;
+        }
+    }
+    const float fS = (float)S;
+    const float full = th[d_star];
+    const float te = teff_from_counts(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
+                                      max0(__fsub_rn(b.tau, co[1])), max0(__fsub_rn(b.tau, co[2])));
+    const int64_t lvl = (int64_t)b.T * b.C;
+    const int64_t o = (int64_t)t * b.C + c;
+    if (liveput) {
+        float* lp = liveput + (int64_t)q * 3 * lvl;
+        lp[o] = __fdiv_rn(acc_i, fS);
+        lp[lvl + o] = __fdiv_rn(acc_m, fS);
+        lp[2 * lvl + o] = full;
+    }
+    if (teff) teff[u] = te;
+    if (gain) gain[u] = __fmul_rn(full, te);
+}
+
+// ------------------------------------------------------------------ transition weights from histogram tails
+
+// Per-(q, t) tables held in LDS while a step is processed.
+struct StepTables {
+    uint32_t* tail_int;  // [L] suffix sums of hist_int inside each candidate's row
+    uint32_t* tail_min;  // [L]
+    float* full;         // [C] thr[c][D_c]
+    float* e;            // [C][3] max(0, tau - cost)
+    int* from_ok;        // [C]
+    int* to_ok;          // [C]
+};
+
+// Loads the histograms of (q, t), turns each candidate's row into suffix sums, sets feasibility flags.
+__device__ __forceinline__ void load_step(const Batch& b, const CfgRec* cfg_s, int q, int t,
+                                          const uint32_t* __restrict__ hist_int,
+                                          const uint32_t* __restrict__ hist_min, const StepTables& st)
+{
+    const int64_t base = ((int64_t)q * b.T + t) * b.L;
+    for (int i = threadIdx.x; i < b.L; i += blockDim.x) {
+        st.tail_int[i] = hist_int[base + i];
+        st.tail_min[i] = hist_min[base + i];
+    }
+    const int a_prev = clampi(b.avail[(int64_t)q * (b.T + 1) + t], 0, b.N);
+    const int a_next = clampi(b.avail[(int64_t)q * (b.T + 1) + t + 1], 0, b.N);
+    const int cur = b.cur_config ? b.cur_config[q] : -1;
+    __syncthreads();
+    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+        const CfgRec cr = cfg_s[c];
+        uint32_t ri = 0u, rm = 0u;
+        for (int j = cr.D; j >= 0; --j) {
+            ri += st.tail_int[cr.off + j];
+            rm += st.tail_min[cr.off + j];
+            st.tail_int[cr.off + j] = ri;
+            st.tail_min[cr.off + j] = (j == 0) ? st.tail_min[cr.off] : rm;  // slot 0 keeps the raw bin 0
+        }
+        const int used = cr.D * cr.P;
+        const bool deep = cr.P >= b.p_min;
+        st.from_ok[c] = (used <= a_prev) && deep && (t > 0 || cur < 0 || c == cur);
+        st.to_ok[c] = (used <= a_next) && deep;
+    }
+    __syncthreads();
+}
+
+// W_t[c][c'] from the step tables (cfg_s = candidate table in LDS).
+__device__ __forceinline__ float transition_weight(const Batch& b, const CfgRec* cfg_s, const StepTables& st, int c,
+                                                   int c2)
+{
+    if (!st.from_ok[c] || !st.to_ok[c2]) return kNegInf;
+    const CfgRec a = cfg_s[c], z = cfg_s[c2];
+    const float full = st.full[c2];
+    if (a.P != z.P) return __fmul_rn(full, st.e[3 * c2 + 2]);
+    uint32_t n0 = 0u, n01 = 0u;
+    if (z.D <= a.D) {
+        n0 = st.tail_int[a.off + z.D];
+        n01 = st.tail_min[a.off + z.D];
+    }
+    const uint32_t h0 = st.tail_min[a.off];
+    const float te = teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, st.e[3 * c2], st.e[3 * c2 + 1],
+                                      st.e[3 * c2 + 2]);
+    return __fmul_rn(full, te);
+}
+
+// LDS carve-up shared by the two kernels below.  Returns the number of bytes used.
+__device__ __forceinline__ size_t carve(unsigned char* smem, int C, int L, CfgRec*& cfg_s, StepTables& st, float*& F0,
+                                        float*& F1)
+{
+    size_t o = 0;
+    cfg_s = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
+    st.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)L;
+    st.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)L;
+    st.full = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    st.e = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
+    st.from_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    st.to_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    F0 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    F1 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    return o;
+}
+
+inline size_t plan_lds_bytes(int C, int L) { return sizeof(CfgRec) * (size_t)C + 8 * (size_t)L + 32 * (size_t)C; }
+
+__device__ __forceinline__ void load_query_tables(const Batch& b, int q, CfgRec* cfg_s, const StepTables& st)
+{
+    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+        const CfgRec cr = b.cfg[c];
+        cfg_s[c] = cr;
+        st.full[c] = b.thr[(int64_t)q * b.L + cr.off + cr.D];
+        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+        st.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
+        st.e[3 * c + 1] = max0(__fsub_rn(b.tau, co[1]));
+        st.e[3 * c + 2] = max0(__fsub_rn(b.tau, co[2]));
+    }
+    __syncthreads();
+}
+
+// Writes W[q][t][c][c'] (one block per (q, t)).
+__global__ void __launch_bounds__(256) transition_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+                                                         const uint32_t* __restrict__ hist_min, float* __restrict__ W)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    CfgRec* cfg_s;
+    StepTables st;
+    float *F0, *F1;
+    carve(smem, b.C, b.L, cfg_s, st, F0, F1);
+    const int q = blockIdx.x / b.T;
+    const int t = blockIdx.x - q * b.T;
+    load_query_tables(b, q, cfg_s, st);
+    load_step(b, cfg_s, q, t, hist_int, hist_min, st);
+    float* Wt = W + ((int64_t)q * b.T + t) * b.C * b.C;
+    const int cells = b.C * b.C;
+    for (int i = threadIdx.x; i < cells; i += blockDim.x) {
+        const int c = i / b.C;
+        const int c2 = i - c * b.C;
+        Wt[i] = transition_weight(b, cfg_s, st, c, c2);
+    }
+}
+
+// ------------------------------------------------------------------ dynamic program (Eq. 6)
+
+// Final arg-max and walk back along the back-pointers; thread 0 of the block only.
+__device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_last, const int32_t* bp_q,
+                                            int32_t* plan, int32_t* start, float* objective, int32_t* status,
+                                            bool inputs_valid, int einval, int einfeasible)
+{
+    float top = kNegInf;
+    int last = -1;
+    for (int c = 0; c < C; ++c)
+        if (F_last[c] > top) {
+            top = F_last[c];
+            last = c;
+        }
+    int32_t* pl = plan + (int64_t)q * T;
+    int st = 0;
+    if (last < 0) {
+        for (int t = 0; t < T; ++t) pl[t] = -1;
+        if (start) start[q] = -1;
+        st = einfeasible;
+    } else {
+        pl[T - 1] = last;
+        for (int t = T - 1; t >= 1; --t) {
+            last = bp_q[(int64_t)t * C + last];
+            pl[t - 1] = last;
+        }
+        if (start) start[q] = bp_q[last];
+    }
+    if (objective) objective[q] = top;
+    if (status) status[q] = inputs_valid ? st : einval;
+}
+
+// One block per query: T dependent max-plus steps with the weights computed on the fly from the
+// histogram tails (the weights never touch HBM), then the walk back.
+__global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+                                                         const uint32_t* __restrict__ hist_min,
+                                                         const int32_t* __restrict__ valid, float* __restrict__ F,
+                                                         int32_t* __restrict__ bp, int32_t* __restrict__ plan,
+                                                         int32_t* __restrict__ start, float* __restrict__ objective,
+                                                         int32_t* __restrict__ status, int einval, int einfeasible)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    CfgRec* cfg_s;
+    StepTables st;
+    float *Fc, *Fn;
+    carve(smem, b.C, b.L, cfg_s, st, Fc, Fn);
+    const int q = blockIdx.x;
+    const int C = b.C;
+    load_query_tables(b, q, cfg_s, st);
+    float* Fq = F ? F + (int64_t)q * (b.T + 1) * C : nullptr;
+    int32_t* bpq = bp + (int64_t)q * b.T * C;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        Fc[c] = 0.0f;
+        if (Fq) Fq[c] = 0.0f;
+    }
+    for (int t = 0; t < b.T; ++t) {
+        load_step(b, cfg_s, q, t, hist_int, hist_min, st);  // ends with a barrier (also orders Fc writes)
+        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
+            float best = kNegInf;
+            int arg = -1;
+            if (st.to_ok[c2]) {
+                for (int c = 0; c < C; ++c) {
+                    const float v = __fadd_rn(Fc[c], transition_weight(b, cfg_s, st, c, c2));
+                    if (v > best) {
+                        best = v;
+                        arg = c;
+                    }
+                }
+            }
+            Fn[c2] = best;
+            bpq[(int64_t)t * C + c2] = arg;
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = best;
+        }
+        __syncthreads();
+        float* tmp = Fc; Fc = Fn; Fn = tmp;
+    }
+    if (threadIdx.x == 0)
+        finish_plan(q, b.T, C, Fc, bpq, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
+                    einfeasible);
+}
+
+// One block per query on weights held in memory: W[q][t][c][c'], c' contiguous.
+__global__ void __launch_bounds__(256) dp_kernel(const float* __restrict__ W, int T, int C, float* __restrict__ F,
+                                                 int32_t* __restrict__ bp, int32_t* __restrict__ plan,
+                                                 int32_t* __restrict__ start, float* __restrict__ objective,
+                                                 int32_t* __restrict__ status, int einfeasible)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* Fc = reinterpret_cast<float*>(smem);
+    float* Fn = Fc + C;
+    const int q = blockIdx.x;
+    float* Fq = F ? F + (int64_t)q * (T + 1) * C : nullptr;
+    int32_t* bpq = bp + (int64_t)q * T * C;
+    const float* Wq = W + (int64_t)q * T * C * C;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        Fc[c] = 0.0f;
+        if (Fq) Fq[c] = 0.0f;
+    }
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        const float* Wt = Wq + (int64_t)t * C * C;
+        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
+            float best = kNegInf;
+            int arg = -1;
+            for (int c = 0; c < C; ++c) {
+                const float v = __fadd_rn(Fc[c], Wt[(int64_t)c * C + c2]);
+                if (v > best) {
+                    best = v;
+                    arg = c;
+                }
+            }
+            Fn[c2] = best;
+            bpq[(int64_t)t * C + c2] = arg;
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = best;
+        }
+        __syncthreads();
+        float* tmp = Fc; Fc = Fn; Fn = tmp;
+    }
+    if (threadIdx.x == 0) finish_plan(q, T, C, Fc, bpq, plan, start, objective, status, true, 0, einfeasible);
+}
+
+}  // namespace parcae

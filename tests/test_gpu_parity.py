@@ -1,0 +1,311 @@
+"""GPU library against the CPU oracle, element by element, through the C ABI.
+
+Integers (masks, survivor counts, histograms, back-pointers, plans) must be bit-equal.  Float tables must be
+bit-equal to the oracle's fixed-order float values and within 1e-5 relative of its double values.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import parcae_inputs as pi
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2403_14097_amd as mod
+    mod.load_library()
+    return mod
+
+
+def _np(t, dtype=None):
+    a = t.detach().cpu().numpy()
+    return a.view(dtype) if dtype is not None else a
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _check_query_against_oracle(pk, batch, q, ev, pl, S, threads=8, check_W=None):
+    """Full comparison of one query's outputs with the oracle run at S scenarios."""
+    r = oracle.run_query(batch, q, n_scenarios=S, n_threads=threads)
+    assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int), "hist_int"
+    assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min), "hist_min"
+    if ev.liveput is not None:
+        for name, got, f, d in (("liveput", _np(ev.liveput[q]), r.tables.liveput_f, r.tables.liveput_d),
+                                ("teff", _np(ev.teff[q]), r.tables.teff_f, r.tables.teff_d),
+                                ("gain", _np(ev.gain[q]), r.tables.gain_f, r.tables.gain_d)):
+            assert np.array_equal(got, f), name
+            assert np.all(np.abs(got - d) <= REL * np.abs(d)), name
+    if pl is not None:
+        assert np.array_equal(_np(pl.bp[q]), r.plan.bp), "bp"
+        assert np.array_equal(_np(pl.F[q]), r.plan.F), "F"        # -inf == -inf holds
+        assert np.array_equal(_np(pl.plan[q]), r.plan.plan), "plan"
+        assert int(pl.start[q]) == r.plan.start
+        obj = float(pl.objective[q])
+        assert obj == r.plan.objective
+        if r.plan.feasible:
+            assert abs(obj - r.objective_d) <= REL * abs(r.objective_d)
+            assert int(pl.status[q]) == pk.PARCAE_OK
+        else:
+            assert int(pl.status[q]) == pk.PARCAE_EINFEASIBLE
+    if check_W is not None:
+        assert np.array_equal(_np(check_W[q]), r.W_f), "W"
+        fin = np.isfinite(r.W_d)
+        assert np.all(np.abs(_np(check_W[q])[fin] - r.W_d[fin]) <= REL * np.abs(r.W_d[fin]))
+    return r
+
+
+# ------------------------------------------------------------------ scenarios one by one
+
+UNITS = [
+    # D, P, a_next  (k = max(0, D*P - a_next))
+    (1, 1, 0), (1, 1, 1), (4, 2, 5), (2, 4, 3), (3, 4, 10), (8, 1, 3), (2, 3, 4), (3, 2, 4),
+    (16, 2, 20), (8, 4, 9), (4, 8, 30), (2, 16, 17), (1, 32, 20), (2, 32, 50), (16, 4, 40), (8, 8, 1),
+    (5, 7, 20), (3, 13, 30), (9, 11, 60), (17, 15, 200), (64, 2, 100), (32, 4, 64), (16, 8, 100),
+    (8, 16, 97), (4, 32, 96), (2, 64, 100), (1, 128, 77), (256, 1, 130), (128, 2, 3), (64, 4, 250),
+    (32, 8, 128), (16, 16, 255), (8, 32, 129), (4, 64, 192), (2, 128, 128), (1, 256, 255), (1, 256, 0),
+    (3, 64, 100), (1, 64, 40), (2, 96, 150), (7, 32, 100), (5, 40, 120), (12, 20, 100),
+]
+
+
+def test_scenarios_match_oracle_one_by_one(pk):
+    """Masks, n_int and d_min of individual scenarios: every mask width, both Floyd branches, any depth."""
+    configs = sorted({(d, p) for d, p, _ in UNITS}, key=lambda x: (x[1], x[0]))
+    cfg = np.asarray(configs, np.int32)
+    avs = sorted({a for _, _, a in UNITS})
+    # one query; interval t has availability avs[t]
+    b = pi.custom_batch(256, cfg, [[256] + avs], thr_per_pipeline=[1.0] * len(cfg), n_scenarios=64, seed=1234)
+    b.stream_id[:] = 5
+    p = pk.upload(b)
+    ns, s0 = 192, 1000
+    for D, P, a in UNITS:
+        c = configs.index((D, P))
+        t = avs.index(a)
+        masks, n_int, d_min = pk.parcae_debug_sample(p, 0, t, c, s0, ns)
+        _sync()
+        om, oi, od = oracle.debug_sample(D, P, a, int(b.seed[0]), 5, t * len(cfg) + c, s0, ns)
+        assert np.array_equal(_np(masks, np.uint32), om), (D, P, a)
+        assert np.array_equal(_np(n_int), oi), (D, P, a)
+        assert np.array_equal(_np(d_min), od), (D, P, a)
+
+
+# ------------------------------------------------------------------ whole path on the small workloads
+
+@pytest.mark.parametrize("name", ["tiny", "small"])
+def test_full_workload_parity(pk, name):
+    b = pi.workload(name)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    _check_query_against_oracle(pk, b, 0, ev, pl, b.n_scenarios, check_W=W)
+    # the three ways to the plan agree: fused, from stored histograms, from stored weights
+    pl2 = pk.parcae_plan_from_hist(p, ev.hist_int, ev.hist_min)
+    pl3 = pk.parcae_dp_plan(W)
+    _sync()
+    for other in (pl2, pl3):
+        for f in ("F", "bp", "plan", "start", "objective", "status"):
+            assert np.array_equal(_np(getattr(other, f)), _np(getattr(pl, f))), f
+    # eval alone gives the same tables and a per-query status
+    ev2 = pk.parcae_liveput_eval(p)
+    _sync()
+    for f in ("hist_int", "hist_min", "liveput", "teff", "gain"):
+        assert np.array_equal(_np(getattr(ev2, f)), _np(getattr(ev, f))), f
+    assert int(ev2.status[0]) == pk.PARCAE_OK
+
+
+@pytest.mark.parametrize("name,S,dense", [("medium", 1500, False), ("medium", 777, True), ("large", 640, False),
+                                          ("large", 200, True)])
+def test_prefix_parity_on_larger_workloads(pk, name, S, dense):
+    """Scenario s does not depend on the scenario count, so a prefix of a big workload is a full parity case.
+    S values are ragged (not multiples of the wave or block size)."""
+    b = pi.workload(name, dense=dense, n_scenarios=S)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    _check_query_against_oracle(pk, b, 0, ev, pl, S, check_W=W)
+
+
+def test_batched_queries_parity(pk):
+    """Several queries in one launch, each with its own walk, tables, seed and current configuration."""
+    b = pi.workload("sweep", n_queries=6, n_scenarios=1000)
+    b.stream_id[:] = np.arange(6, dtype=np.uint32) * 7
+    b.cur_config[3] = -1
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in range(6):
+        _check_query_against_oracle(pk, b, q, ev, pl, 1000, check_W=W)
+
+
+def test_multi_chunk_and_ragged_scenario_counts(pk):
+    """Scenario counts around the block chunking (2048 per block) and the wave size."""
+    base = pi.workload("small")
+    for S in (1, 63, 65, 2047, 2049, 4097, 5000):
+        b = base.with_scenarios(S)
+        p = pk.upload(b)
+        ev = pk.parcae_liveput_eval(p)
+        _sync()
+        hi, hm = oracle.eval_hist(b.configs, b.thr_off, b.avail[0], int(b.seed[0]), 0, 0, S, 8)
+        assert np.array_equal(_np(ev.hist_int[0], np.uint32), hi), S
+        assert np.array_equal(_np(ev.hist_min[0], np.uint32), hm), S
+
+
+# ------------------------------------------------------------------ full sizes, sampled
+
+def _sampled_unit_check(pk, b, ev, rng, n_samples, S):
+    C, T = b.n_configs, b.n_intervals
+    used = b.configs[:, 0] * b.configs[:, 1]
+    hi_all = _np(ev.hist_int, np.uint32)
+    hm_all = _np(ev.hist_min, np.uint32)
+    # properties that hold at any size: every unit's bins sum to S; units without sampling have one bin
+    sums_i = np.add.reduceat(hi_all, b.thr_off[:-1], axis=2)
+    sums_m = np.add.reduceat(hm_all, b.thr_off[:-1], axis=2)
+    assert np.all(sums_i == S) and np.all(sums_m == S)
+    k = np.maximum(0, used[None, None, :] - b.avail[:, 1:, None])
+    top = hi_all[:, :, b.thr_off[1:] - 1]
+    assert np.all(top[k == 0] == S)
+    # sampled non-trivial units, computed one by one by the oracle
+    nz = np.argwhere((k > 0) & (k < used[None, None, :]))
+    pick = nz[rng.choice(len(nz), size=min(n_samples, len(nz)), replace=False)]
+    for q, t, c in pick:
+        D, P = b.configs[c]
+        hi, hm = oracle.eval_unit(int(D), int(P), int(b.avail[q, t + 1]), int(b.seed[q]), int(b.stream_id[q]),
+                                  int(t * C + c), 0, S)
+        sl = slice(b.thr_off[c], b.thr_off[c + 1])
+        assert np.array_equal(hi_all[q, t, sl], hi), (q, t, c)
+        assert np.array_equal(hm_all[q, t, sl], hm), (q, t, c)
+    return len(pick)
+
+
+def _plan_check_from_gpu_histograms(pk, b, q, ev, pl):
+    """DP parity at full size: the oracle's tables and plan from the (already verified) integer histograms."""
+    S = b.n_scenarios
+    hi = _np(ev.hist_int[q], np.uint32)
+    hm = _np(ev.hist_min[q], np.uint32)
+    tab = oracle.finalise(b.configs, b.thr_off, b.avail[q], b.thr[q], b.cost[q], b.interval_sec, S, hi, hm)
+    assert np.array_equal(_np(ev.liveput[q]), tab.liveput_f)
+    assert np.array_equal(_np(ev.teff[q]), tab.teff_f) and np.array_equal(_np(ev.gain[q]), tab.gain_f)
+    assert np.all(np.abs(_np(ev.gain[q]) - tab.gain_d) <= REL * np.abs(tab.gain_d))
+    W_d, W_f = oracle.transition(b.configs, b.thr_off, b.avail[q], b.thr[q], b.cost[q], b.interval_sec, S, b.p_min,
+                                 int(b.cur_config[q]), hi, hm)
+    ref = oracle.dp_f32(W_f)
+    assert np.array_equal(_np(pl.bp[q]), ref.bp) and np.array_equal(_np(pl.F[q]), ref.F)
+    assert np.array_equal(_np(pl.plan[q]), ref.plan) and int(pl.start[q]) == ref.start
+    assert float(pl.objective[q]) == ref.objective
+    assert abs(ref.objective - oracle.dp_f64(W_d)) <= REL * abs(ref.objective)
+
+
+@pytest.mark.parametrize("name", ["medium", "large"])
+def test_full_size_single_query_sampled(pk, name):
+    b = pi.workload(name)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    n = _sampled_unit_check(pk, b, ev, np.random.default_rng(5), 24 if name == "large" else 60, b.n_scenarios)
+    assert n > 0
+    _plan_check_from_gpu_histograms(pk, b, 0, ev, pl)
+
+
+def test_full_size_sweep_sampled(pk):
+    """The 1024-query what-if sweep in the launch configuration the benchmark times."""
+    b = pi.workload("sweep")
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    rng = np.random.default_rng(11)
+    n = _sampled_unit_check(pk, b, ev, rng, 300, b.n_scenarios)
+    assert n == 300
+    assert np.all(_np(pl.status) == 0)
+    for q in rng.choice(b.n_queries, size=24, replace=False):
+        _plan_check_from_gpu_histograms(pk, b, int(q), ev, pl)
+    for q in (0, 1023):
+        _check_query_against_oracle(pk, b, q, ev, pl, b.n_scenarios)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_degenerate_shapes(pk):
+    # one instance, one candidate, one interval, one scenario
+    b = pi.custom_batch(1, [[1, 1]], [[1, 0]], thr_per_pipeline=[3.0], n_scenarios=1, cur_config=0)
+    ev, pl = pk.parcae_liveput_plan(pk.upload(b))
+    _sync()
+    _check_query_against_oracle(pk, b, 0, ev, pl, 1)
+    # the largest pool: 256 instances in every shape, half of them preempted
+    cfg = pi.candidate_list(256, (1, 2, 4, 8, 16, 32, 64, 128, 256), 1)
+    cfg = cfg[cfg[:, 0] * cfg[:, 1] == 256]
+    b = pi.custom_batch(256, cfg, [[256, 128, 255, 1, 0, 256]], thr_per_pipeline=[1.0] * len(cfg), n_scenarios=300)
+    ev, pl = pk.parcae_liveput_plan(pk.upload(b))
+    _sync()
+    _check_query_against_oracle(pk, b, 0, ev, pl, 300)
+
+
+def test_depths_that_are_not_powers_of_two(pk):
+    cfg = pi.candidate_list(60, (3, 5, 7, 12, 13, 23), 3)
+    b = pi.custom_batch(60, cfg, [[60, 41, 52, 33, 60, 20]], thr_per_pipeline=[float(p) ** 0.5 for _, p in cfg],
+                        n_scenarios=500, p_min=3, seed=9)
+    ev, pl = pk.parcae_liveput_plan(pk.upload(b))
+    _sync()
+    _check_query_against_oracle(pk, b, 0, ev, pl, 500)
+
+
+def test_infeasible_and_invalid_queries_are_flagged_per_query(pk):
+    cfg = pi.candidate_list(8, (2, 4), 2)
+    av = [[8, 6, 7, 5], [8, 1, 7, 5], [8, 6, 7, 5], [8, 6, 9, 5]]   # q1: below the memory floor; q3: above N
+    b = pi.custom_batch(8, cfg, av, thr_per_pipeline=[1.0] * len(cfg), n_scenarios=200, p_min=2)
+    b.thr[2, 0] = 1.0                                                 # q2: thr[.][0] != 0
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    st = _np(pl.status)
+    assert st.tolist() == [pk.PARCAE_OK, pk.PARCAE_EINFEASIBLE, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL]
+    _check_query_against_oracle(pk, b, 0, ev, pl, 200)
+    _check_query_against_oracle(pk, b, 1, ev, pl, 200)
+    assert np.all(_np(pl.plan[1]) == -1) and float(pl.objective[1]) == -np.inf and int(pl.start[1]) == -1
+    ev2 = pk.parcae_liveput_eval(p)
+    _sync()
+    assert _np(ev2.status).tolist() == [0, 0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL]
+
+
+def test_optional_outputs_may_be_null(pk):
+    b = pi.workload("tiny")
+    p = pk.upload(b)
+    ev = pk.alloc_eval_out(p, tables=False)
+    ev.status = None
+    pl = pk.alloc_plan_out(p, full=False)
+    pl.start = None
+    pl.objective = None
+    pl.status = None
+    pk.parcae_liveput_plan(p, ev, pl)
+    _sync()
+    r = oracle.run_query(b, 0)
+    assert np.array_equal(_np(ev.hist_int[0], np.uint32), r.hist_int)
+    assert np.array_equal(_np(pl.plan[0]), r.plan.plan)
+
+
+def test_runs_on_a_side_stream_and_repeats_identically(pk):
+    import torch
+    b = pi.workload("small")
+    p = pk.upload(b)
+    ev0, pl0 = pk.parcae_liveput_plan(p)
+    _sync()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ev1, pl1 = pk.parcae_liveput_plan(p)
+    side.synchronize()
+    for f in ("hist_int", "hist_min", "liveput", "teff", "gain"):
+        assert np.array_equal(_np(getattr(ev0, f)), _np(getattr(ev1, f)))
+    for f in ("F", "bp", "plan", "start", "objective"):
+        assert np.array_equal(_np(getattr(pl0, f)), _np(getattr(pl1, f)))

@@ -1,0 +1,107 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header declares,
+and turns bad shapes into error codes before anything is launched."""
+import ctypes as ct
+import os
+import re
+
+import pytest
+
+import paper_2403_14097_amd as pk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "parcae.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(parcae_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = pk.load_library()
+    declared = _declared_symbols()
+    assert set(declared) == set(pk.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror():
+    assert pk.parcae_version() >= 100
+    assert pk.strerror(0) == "ok"
+    for code in (pk.PARCAE_EINVAL, pk.PARCAE_EWORKSPACE, pk.PARCAE_EHIP, pk.PARCAE_EINFEASIBLE, -99):
+        assert isinstance(pk.strerror(code), str) and pk.strerror(code)
+
+
+def test_hist_len():
+    assert pk.parcae_hist_len([(1, 2), (2, 2), (3, 2)]) == 9
+    assert pk.parcae_hist_len([(256, 1)]) == 257
+    assert pk.load_library().parcae_hist_len(None, 3) == pk.PARCAE_EINVAL
+
+
+def _problem(configs, nq=1, N=8, T=4, S=16, tau=60.0, p_min=1, flags=0, fake_ptr=0x1000):
+    arr = (pk.parcae_config * len(configs))()
+    for i, (d, p) in enumerate(configs):
+        arr[i].D, arr[i].P = d, p
+    prob = pk.parcae_problem(nq, N, T, len(configs), S, p_min, tau, flags, ct.cast(arr, ct.POINTER(pk.parcae_config)),
+                             fake_ptr, fake_ptr, fake_ptr, fake_ptr, None, None, None, None)
+    return prob, arr
+
+
+def test_workspace_bytes_and_shape_errors():
+    lib = pk.load_library()
+    out = ct.c_size_t(0)
+    good, keep = _problem([(1, 1), (2, 1), (1, 2), (2, 4)])
+    assert lib.parcae_workspace_bytes(ct.byref(good), ct.byref(out)) == pk.PARCAE_OK
+    assert out.value >= 4 * 16 + 4 + 4 * 4 * 4 and out.value % 256 == 0
+    assert lib.parcae_workspace_bytes(ct.byref(good), None) == pk.PARCAE_EINVAL
+    assert lib.parcae_workspace_bytes(None, ct.byref(out)) == pk.PARCAE_EINVAL
+    bad_cases = [
+        _problem([(2, 1), (1, 1)]),              # not sorted
+        _problem([(1, 1), (1, 1)]),              # duplicate
+        _problem([(1, 2), (1, 1)]),              # P descending
+        _problem([(3, 4)]),                      # D * P > N
+        _problem([(0, 1)]), _problem([(1, 0)]),
+        _problem([(1, 1)], N=257), _problem([(1, 1)], N=0),
+        _problem([(1, 1)], T=0), _problem([(1, 1)], nq=0),
+        _problem([(1, 1)], S=0), _problem([(1, 1)], S=(1 << 24) + 1),
+        _problem([(1, 1)], tau=0.0), _problem([(1, 1)], tau=float("inf")), _problem([(1, 1)], tau=float("nan")),
+        _problem([(1, 1)], flags=1),
+        _problem([(1, 1)], fake_ptr=None),       # NULL device tables
+    ]
+    for prob, _keep in bad_cases:
+        assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    """NULL outputs, a missing or misaligned or short workspace: an error code and nothing is enqueued."""
+    lib = pk.load_library()
+    prob, keep = _problem([(1, 1), (2, 1), (1, 2)])
+    need = ct.c_size_t(0)
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(need)) == 0
+    fake = 0x10000
+    # required outputs missing
+    assert lib.parcae_liveput_eval(ct.byref(prob), None, fake, None, None, None, None, fake, need.value, None) == pk.PARCAE_EINVAL
+    assert lib.parcae_plan_from_hist(ct.byref(prob), fake, fake, None, None, None, None, None, None, fake, need.value,
+                                     None) == pk.PARCAE_EINVAL
+    assert lib.parcae_transition_weights(ct.byref(prob), fake, fake, None, fake, need.value, None) == pk.PARCAE_EINVAL
+    assert lib.parcae_dp_plan(None, 1, 1, 1, None, fake, fake, None, None, None, None) == pk.PARCAE_EINVAL
+    assert lib.parcae_dp_plan(fake, 1, 1, 5000, None, fake, fake, None, None, None, None) == pk.PARCAE_EINVAL
+    # workspace problems
+    for ws, nbytes in ((None, need.value), (fake + 4, need.value), (fake, need.value - 1)):
+        assert lib.parcae_liveput_eval(ct.byref(prob), fake, fake, None, None, None, None, ws, nbytes, None) == pk.PARCAE_EWORKSPACE
+        assert lib.parcae_liveput_plan(ct.byref(prob), fake, fake, None, None, None, None, None, fake, None, None, None,
+                                       ws, nbytes, None) == pk.PARCAE_EWORKSPACE
+    # unit indices out of range
+    assert lib.parcae_debug_sample(ct.byref(prob), 0, 4, 0, 0, 8, fake, fake, fake, fake, need.value, None) == pk.PARCAE_EINVAL
+    assert lib.parcae_debug_sample(ct.byref(prob), 0, 0, 3, 0, 8, fake, fake, fake, fake, need.value, None) == pk.PARCAE_EINVAL
+    assert lib.parcae_debug_sample(ct.byref(prob), 1, 0, 0, 0, 8, fake, fake, fake, fake, need.value, None) == pk.PARCAE_EINVAL
+
+
+def test_product_has_no_cpu_path():
+    """Without a GPU the binding raises instead of computing anything."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    import parcae_inputs as pi
+    with pytest.raises(RuntimeError):
+        pk.upload(pi.workload("tiny"))
