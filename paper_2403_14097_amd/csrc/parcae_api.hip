@@ -19,13 +19,14 @@ using parcae::CfgRec;
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxConfigsDp = 4096;
-constexpr size_t kMaxPlanLds = 64 * 1024;
+constexpr size_t kMaxPlanLds = 60 * 1024;  // dynamic LDS per block, leaves room for the static part within 64 KB
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
     size_t cfg_off, valid_off, bp_off, total;
     int64_t L;
+    int max_row;  // bins of the widest candidate, max over c of D_c + 1
 };
 
 // Host-visible shape checks; fills the packed candidate table.
@@ -39,6 +40,7 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
     if (!(p->interval_sec > 0.0f) || !std::isfinite(p->interval_sec)) return PARCAE_EINVAL;
     if ((int64_t)p->n_configs * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     int64_t L = 0;
+    int max_row = 0;
     if (table) table->resize((size_t)p->n_configs);
     for (int c = 0; c < p->n_configs; ++c) {
         const parcae_config g = p->configs[c];
@@ -56,10 +58,12 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
             (*table)[(size_t)c] = CfgRec{g.D, g.P, (int32_t)L, lg};
         }
         L += g.D + 1;
+        max_row = g.D + 1 > max_row ? g.D + 1 : max_row;
     }
     if ((int64_t)p->n_queries * p->n_intervals * L >= (int64_t)1 << 40) return PARCAE_EINVAL;
     if (lay) {
         lay->L = L;
+        lay->max_row = max_row;
         lay->cfg_off = 0;
         lay->valid_off = align_up(sizeof(CfgRec) * (size_t)p->n_configs);
         lay->bp_off = lay->valid_off + align_up(sizeof(int32_t) * (size_t)p->n_queries);
@@ -121,6 +125,17 @@ int32_t* valid_ptr(const Layout& lay, void* ws)
     return reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
 }
 
+// Histogram bins the planning kernels keep in LDS at a time: all of them if they fit, else as many as
+// the LDS budget allows; -1 if not even the widest row fits next to the per-candidate tables.
+int pick_plan_cap(int C, const Layout& lay)
+{
+    const size_t fixed = parcae::plan_lds_bytes(C, 0);
+    if (fixed >= kMaxPlanLds) return -1;
+    int64_t cap = (int64_t)((kMaxPlanLds - fixed) / 8);
+    if (cap > lay.L) cap = lay.L;
+    return cap >= lay.max_row ? (int)cap : -1;
+}
+
 // Scenarios per block of the sampling kernel.
 int pick_chunk_len(int S) { return S < 2048 ? S : 2048; }
 
@@ -165,11 +180,12 @@ int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* his
                 float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
                 hipStream_t st)
 {
-    const size_t lds = parcae::plan_lds_bytes(b.C, b.L);
-    if (lds > kMaxPlanLds) return PARCAE_EINVAL;
+    const int cap = pick_plan_cap(b.C, lay);
+    if (cap < 0) return PARCAE_EINVAL;
+    const size_t lds = parcae::plan_lds_bytes(b.C, cap);
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.bp_off);
     parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(256), lds, st>>>(
-        b, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status, PARCAE_EINVAL,
+        b, cap, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status, PARCAE_EINVAL,
         PARCAE_EINFEASIBLE);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
@@ -254,7 +270,7 @@ int parcae_liveput_plan(const parcae_problem* p, uint32_t* hist_int, uint32_t* h
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
-    if (parcae::plan_lds_bytes(p->n_configs, (int)lay.L) > kMaxPlanLds) return PARCAE_EINVAL;
+    if (pick_plan_cap(p->n_configs, lay) < 0) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
@@ -272,13 +288,14 @@ int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int,
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !W) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
-    const size_t lds = parcae::plan_lds_bytes(p->n_configs, (int)lay.L);
-    if (lds > kMaxPlanLds) return PARCAE_EINVAL;
+    const int cap = pick_plan_cap(p->n_configs, lay);
+    if (cap < 0) return PARCAE_EINVAL;
+    const size_t lds = parcae::plan_lds_bytes(p->n_configs, cap);
     if ((int64_t)p->n_queries * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
-    parcae::transition_kernel<<<dim3((unsigned)(b.nq * b.T)), dim3(256), lds, st>>>(b, hist_int, hist_min, W);
+    parcae::transition_kernel<<<dim3((unsigned)(b.nq * b.T)), dim3(256), lds, st>>>(b, cap, hist_int, hist_min, W);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
 

@@ -129,118 +129,159 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
 
 // ------------------------------------------------------------------ transition weights from histogram tails
 
-// Per-(q, t) tables held in LDS while a step is processed.
-struct StepTables {
-    uint32_t* tail_int;  // [L] suffix sums of hist_int inside each candidate's row
-    uint32_t* tail_min;  // [L]
+// Tables of one query kept in LDS by the planning kernels.  The histogram rows of a step are brought in
+// a chunk of consecutive source candidates at a time (a chunk holds at most `cap` bins), so the LDS
+// footprint does not grow with the total number of bins.
+struct PlanShared {
+    CfgRec* cfg;         // [C]
     float* full;         // [C] thr[c][D_c]
     float* e;            // [C][3] max(0, tau - cost)
-    int* from_ok;        // [C]
-    int* to_ok;          // [C]
+    int* from_ok;        // [C] may be left at this step
+    int* to_ok;          // [C] may be entered at this step
+    int* chunk_start;    // [n_chunks + 1] first candidate of each chunk
+    float* F0;           // [C]
+    float* F1;           // [C]
+    int* arg;            // [C]
+    uint32_t* tail_int;  // [cap] suffix sums of hist_int inside each row of the current chunk
+    uint32_t* tail_min;  // [cap] same for hist_min, except that slot 0 of a row keeps the raw bin 0
+    int n_chunks;
 };
 
-// Loads the histograms of (q, t), turns each candidate's row into suffix sums, sets feasibility flags.
-__device__ __forceinline__ void load_step(const Batch& b, const CfgRec* cfg_s, int q, int t,
-                                          const uint32_t* __restrict__ hist_int,
-                                          const uint32_t* __restrict__ hist_min, const StepTables& st)
+inline size_t plan_lds_bytes(int C, int cap) { return 56 * (size_t)C + 16 + 8 * (size_t)cap; }
+
+__device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, PlanShared& sh)
 {
-    const int64_t base = ((int64_t)q * b.T + t) * b.L;
-    for (int i = threadIdx.x; i < b.L; i += blockDim.x) {
-        st.tail_int[i] = hist_int[base + i];
-        st.tail_min[i] = hist_min[base + i];
+    size_t o = 0;
+    sh.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
+    sh.full = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    sh.e = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
+    sh.from_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    sh.to_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    sh.chunk_start = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)(C + 1);
+    sh.F0 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    sh.F1 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+    sh.arg = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    o = (o + 15) & ~(size_t)15;
+    sh.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)cap;
+    sh.tail_min = reinterpret_cast<uint32_t*>(smem + o);
+}
+
+// Per-query tables and the chunking of the candidate list (the same for every step).
+__device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap, PlanShared& sh)
+{
+    __shared__ int n_chunks_s;
+    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+        const CfgRec cr = b.cfg[c];
+        sh.cfg[c] = cr;
+        sh.full[c] = b.thr[(int64_t)q * b.L + cr.off + cr.D];
+        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+        sh.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
+        sh.e[3 * c + 1] = max0(__fsub_rn(b.tau, co[1]));
+        sh.e[3 * c + 2] = max0(__fsub_rn(b.tau, co[2]));
     }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n = 0, c = 0;
+        while (c < b.C) {
+            sh.chunk_start[n++] = c;
+            const int first = sh.cfg[c].off;
+            int end = c + 1;  // a row never exceeds cap (checked on the host)
+            while (end < b.C && sh.cfg[end].off + sh.cfg[end].D + 1 - first <= cap) ++end;
+            c = end;
+        }
+        sh.chunk_start[n] = b.C;
+        n_chunks_s = n;
+    }
+    __syncthreads();
+    sh.n_chunks = n_chunks_s;
+}
+
+// Feasibility of leaving / entering each candidate at step t (constraint D * P <= N of Eq. 6, memory floor,
+// and the current configuration at t = 0).  Ends with a barrier.
+__device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, const PlanShared& sh)
+{
     const int a_prev = clampi(b.avail[(int64_t)q * (b.T + 1) + t], 0, b.N);
     const int a_next = clampi(b.avail[(int64_t)q * (b.T + 1) + t + 1], 0, b.N);
     const int cur = b.cur_config ? b.cur_config[q] : -1;
-    __syncthreads();
     for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
-        const CfgRec cr = cfg_s[c];
-        uint32_t ri = 0u, rm = 0u;
-        for (int j = cr.D; j >= 0; --j) {
-            ri += st.tail_int[cr.off + j];
-            rm += st.tail_min[cr.off + j];
-            st.tail_int[cr.off + j] = ri;
-            st.tail_min[cr.off + j] = (j == 0) ? st.tail_min[cr.off] : rm;  // slot 0 keeps the raw bin 0
-        }
+        const CfgRec cr = sh.cfg[c];
         const int used = cr.D * cr.P;
         const bool deep = cr.P >= b.p_min;
-        st.from_ok[c] = (used <= a_prev) && deep && (t > 0 || cur < 0 || c == cur);
-        st.to_ok[c] = (used <= a_next) && deep;
+        sh.from_ok[c] = (used <= a_prev) && deep && (t > 0 || cur < 0 || c == cur);
+        sh.to_ok[c] = (used <= a_next) && deep;
     }
     __syncthreads();
 }
 
-// W_t[c][c'] from the step tables (cfg_s = candidate table in LDS).
-__device__ __forceinline__ float transition_weight(const Batch& b, const CfgRec* cfg_s, const StepTables& st, int c,
-                                                   int c2)
+// Histogram rows of candidates [c_lo, c_hi) of step (q, t) into LDS as suffix sums.  Starts and ends with a barrier.
+__device__ __forceinline__ void load_chunk(const Batch& b, int q, int t, int c_lo, int c_hi,
+                                           const uint32_t* __restrict__ hist_int,
+                                           const uint32_t* __restrict__ hist_min, const PlanShared& sh)
 {
-    if (!st.from_ok[c] || !st.to_ok[c2]) return kNegInf;
-    const CfgRec a = cfg_s[c], z = cfg_s[c2];
-    const float full = st.full[c2];
-    if (a.P != z.P) return __fmul_rn(full, st.e[3 * c2 + 2]);
-    uint32_t n0 = 0u, n01 = 0u;
-    if (z.D <= a.D) {
-        n0 = st.tail_int[a.off + z.D];
-        n01 = st.tail_min[a.off + z.D];
+    __syncthreads();  // the previous chunk is no longer read
+    const int first = sh.cfg[c_lo].off;
+    const int last = sh.cfg[c_hi - 1].off + sh.cfg[c_hi - 1].D + 1;
+    const int64_t base = ((int64_t)q * b.T + t) * b.L + first;
+    for (int i = threadIdx.x; i < last - first; i += blockDim.x) {
+        sh.tail_int[i] = hist_int[base + i];
+        sh.tail_min[i] = hist_min[base + i];
     }
-    const uint32_t h0 = st.tail_min[a.off];
-    const float te = teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, st.e[3 * c2], st.e[3 * c2 + 1],
-                                      st.e[3 * c2 + 2]);
+    __syncthreads();
+    for (int c = c_lo + threadIdx.x; c < c_hi; c += blockDim.x) {
+        const CfgRec cr = sh.cfg[c];
+        const int o = cr.off - first;
+        uint32_t ri = 0u, rm = 0u;
+        for (int j = cr.D; j >= 1; --j) {
+            ri += sh.tail_int[o + j];
+            rm += sh.tail_min[o + j];
+            sh.tail_int[o + j] = ri;
+            sh.tail_min[o + j] = rm;
+        }
+    }
+    __syncthreads();
+}
+
+// W_t[c][c'] for a source c inside the chunk that starts at bin `first`.
+__device__ __forceinline__ float transition_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2)
+{
+    if (!sh.from_ok[c] || !sh.to_ok[c2]) return kNegInf;
+    const CfgRec a = sh.cfg[c], z = sh.cfg[c2];
+    const float full = sh.full[c2];
+    if (a.P != z.P) return __fmul_rn(full, sh.e[3 * c2 + 2]);
+    const int o = a.off - first;
+    uint32_t n0 = 0u, n01 = 0u;
+    if (z.D <= a.D) {  // z.D >= 1, so the raw slot 0 is never read as a suffix sum
+        n0 = sh.tail_int[o + z.D];
+        n01 = sh.tail_min[o + z.D];
+    }
+    const uint32_t h0 = sh.tail_min[o];
+    const float te = teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, sh.e[3 * c2], sh.e[3 * c2 + 1],
+                                      sh.e[3 * c2 + 2]);
     return __fmul_rn(full, te);
 }
 
-// LDS carve-up shared by the two kernels below.  Returns the number of bytes used.
-__device__ __forceinline__ size_t carve(unsigned char* smem, int C, int L, CfgRec*& cfg_s, StepTables& st, float*& F0,
-                                        float*& F1)
-{
-    size_t o = 0;
-    cfg_s = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
-    st.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)L;
-    st.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)L;
-    st.full = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
-    st.e = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
-    st.from_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
-    st.to_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
-    F0 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
-    F1 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
-    return o;
-}
-
-inline size_t plan_lds_bytes(int C, int L) { return sizeof(CfgRec) * (size_t)C + 8 * (size_t)L + 32 * (size_t)C; }
-
-__device__ __forceinline__ void load_query_tables(const Batch& b, int q, CfgRec* cfg_s, const StepTables& st)
-{
-    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
-        const CfgRec cr = b.cfg[c];
-        cfg_s[c] = cr;
-        st.full[c] = b.thr[(int64_t)q * b.L + cr.off + cr.D];
-        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
-        st.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
-        st.e[3 * c + 1] = max0(__fsub_rn(b.tau, co[1]));
-        st.e[3 * c + 2] = max0(__fsub_rn(b.tau, co[2]));
-    }
-    __syncthreads();
-}
-
 // Writes W[q][t][c][c'] (one block per (q, t)).
-__global__ void __launch_bounds__(256) transition_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+__global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const uint32_t* __restrict__ hist_int,
                                                          const uint32_t* __restrict__ hist_min, float* __restrict__ W)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    CfgRec* cfg_s;
-    StepTables st;
-    float *F0, *F1;
-    carve(smem, b.C, b.L, cfg_s, st, F0, F1);
+    PlanShared sh;
+    carve(smem, b.C, cap, sh);
     const int q = blockIdx.x / b.T;
     const int t = blockIdx.x - q * b.T;
-    load_query_tables(b, q, cfg_s, st);
-    load_step(b, cfg_s, q, t, hist_int, hist_min, st);
+    load_query_tables(b, q, cap, sh);
+    load_step_flags(b, q, t, sh);
     float* Wt = W + ((int64_t)q * b.T + t) * b.C * b.C;
-    const int cells = b.C * b.C;
-    for (int i = threadIdx.x; i < cells; i += blockDim.x) {
-        const int c = i / b.C;
-        const int c2 = i - c * b.C;
-        Wt[i] = transition_weight(b, cfg_s, st, c, c2);
+    for (int ch = 0; ch < sh.n_chunks; ++ch) {
+        const int c_lo = sh.chunk_start[ch], c_hi = sh.chunk_start[ch + 1];
+        load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);
+        const int first = sh.cfg[c_lo].off;
+        const int cells = (c_hi - c_lo) * b.C;
+        for (int i = threadIdx.x; i < cells; i += blockDim.x) {
+            const int c = c_lo + i / b.C;
+            const int c2 = i % b.C;
+            Wt[(int64_t)c * b.C + c2] = transition_weight(b, sh, first, c, c2);
+        }
     }
 }
 
@@ -278,7 +319,7 @@ __device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_
 
 // One block per query: T dependent max-plus steps with the weights computed on the fly from the
 // histogram tails (the weights never touch HBM), then the walk back.
-__global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+__global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, int cap, const uint32_t* __restrict__ hist_int,
                                                          const uint32_t* __restrict__ hist_min,
                                                          const int32_t* __restrict__ valid, float* __restrict__ F,
                                                          int32_t* __restrict__ bp, int32_t* __restrict__ plan,
@@ -286,36 +327,49 @@ __global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, const uint32_t
                                                          int32_t* __restrict__ status, int einval, int einfeasible)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    CfgRec* cfg_s;
-    StepTables st;
-    float *Fc, *Fn;
-    carve(smem, b.C, b.L, cfg_s, st, Fc, Fn);
+    PlanShared sh;
+    carve(smem, b.C, cap, sh);
     const int q = blockIdx.x;
     const int C = b.C;
-    load_query_tables(b, q, cfg_s, st);
+    load_query_tables(b, q, cap, sh);
     float* Fq = F ? F + (int64_t)q * (b.T + 1) * C : nullptr;
     int32_t* bpq = bp + (int64_t)q * b.T * C;
+    float* Fc = sh.F0;
+    float* Fn = sh.F1;
     for (int c = threadIdx.x; c < C; c += blockDim.x) {
         Fc[c] = 0.0f;
         if (Fq) Fq[c] = 0.0f;
     }
     for (int t = 0; t < b.T; ++t) {
-        load_step(b, cfg_s, q, t, hist_int, hist_min, st);  // ends with a barrier (also orders Fc writes)
+        load_step_flags(b, q, t, sh);  // ends with a barrier (also orders the writes of Fc)
         for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            float best = kNegInf;
-            int arg = -1;
-            if (st.to_ok[c2]) {
-                for (int c = 0; c < C; ++c) {
-                    const float v = __fadd_rn(Fc[c], transition_weight(b, cfg_s, st, c, c2));
+            Fn[c2] = kNegInf;
+            sh.arg[c2] = -1;
+        }
+        for (int ch = 0; ch < sh.n_chunks; ++ch) {
+            const int c_lo = sh.chunk_start[ch], c_hi = sh.chunk_start[ch + 1];
+            load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);
+            const int first = sh.cfg[c_lo].off;
+            // each thread owns its columns; sources are visited in ascending order, so the strict
+            // comparison keeps the smallest arg-max
+            for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
+                if (!sh.to_ok[c2]) continue;
+                float best = Fn[c2];
+                int arg = sh.arg[c2];
+                for (int c = c_lo; c < c_hi; ++c) {
+                    const float v = __fadd_rn(Fc[c], transition_weight(b, sh, first, c, c2));
                     if (v > best) {
                         best = v;
                         arg = c;
                     }
                 }
+                Fn[c2] = best;
+                sh.arg[c2] = arg;
             }
-            Fn[c2] = best;
-            bpq[(int64_t)t * C + c2] = arg;
-            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = best;
+        }
+        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
+            bpq[(int64_t)t * C + c2] = sh.arg[c2];
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = Fn[c2];
         }
         __syncthreads();
         float* tmp = Fc; Fc = Fn; Fn = tmp;
