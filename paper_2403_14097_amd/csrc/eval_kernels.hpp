@@ -19,22 +19,52 @@ struct Philox4 {
     uint32_t x[4];
 };
 
-// Counter (c0..c3), key (k0, k1); constants of Salmon et al., SC'11.
-__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                                 uint32_t k1)
+// The ten round keys of a query (key bumped by the Weyl constants of Salmon et al., SC'11), held in
+// vector registers: on gfx950 a bitwise VALU instruction with a scalar-register operand issues at half
+// the rate of one whose operands are all vector registers, and the round keys are used by every block.
+struct PhiloxKeys {
+    uint32_t a[10];
+    uint32_t b[10];
+};
+
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t uniform_value)
+{
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(uniform_value));
+    return v;
+}
+
+__device__ __forceinline__ PhiloxKeys philox_keys(uint32_t k0, uint32_t k1)
+{
+    PhiloxKeys ks;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        ks.a[r] = in_vgpr(k0 + (uint32_t)r * 0x9E3779B9u);
+        ks.b[r] = in_vgpr(k1 + (uint32_t)r * 0xBB67AE85u);
+    }
+    return ks;
+}
+
+// a ^ b ^ c in one instruction
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+// One block: counter (c0..c3), ten rounds with multipliers 0xD2511F53 and 0xCD9E8D57.
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 const PhiloxKeys& ks)
 {
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
         const uint64_t pa = (uint64_t)0xD2511F53u * (uint64_t)c0;
         const uint64_t pb = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
-        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, ks.a[round]);
+        const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, ks.b[round]);
         c1 = (uint32_t)pb;
         c3 = (uint32_t)pa;
         c0 = n0;
         c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
     }
     Philox4 r;
     r.x[0] = c0; r.x[1] = c1; r.x[2] = c2; r.x[3] = c3;
@@ -95,24 +125,86 @@ struct Mask {
 
 // ------------------------------------------------------------------ sampler
 
-// Preempted set of scenario s of a unit: Floyd's sampling of the smaller side with Philox words.
-template <int NW>
-__device__ __forceinline__ void sample_mask(Mask<NW>& mask, int M, int k, uint32_t s, uint32_t unit,
-                                            uint32_t stream_id, uint32_t key0, uint32_t key1)
+// Floyd's step on a set held in registers, written without selects: setting bit r always happens; if r
+// was already present the step also sets bit j (never present before: j exceeds every earlier draw).
+// `hit` is all-ones or zero, the bit of j is the same in every lane.
+
+// Preempted set of scenario s of a unit with M <= 32 (one word).
+__device__ __forceinline__ void sample_mask(Mask<1>& mask, int M, int k, uint32_t s, uint32_t unit,
+                                            uint32_t stream_id, const PhiloxKeys& ks)
 {
     const int m = (k < M - k) ? k : (M - k);
-    mask.clear();
+    uint32_t w = 0u;
     for (int i0 = 0; i0 < m; i0 += 4) {
-        const Philox4 blk = philox4x32_10(s, (uint32_t)(i0 >> 2), unit, stream_id, key0, key1);
+        const Philox4 blk = philox4x32_10(s, (uint32_t)(i0 >> 2), unit, stream_id, ks);
         static_for<4>([&](auto x) {
             const int i = i0 + x.value;
             if (i < m) {
                 const uint32_t j = (uint32_t)(M - m + i);
                 const uint32_t r = __umulhi(blk.x[x.value], j + 1u);
-                mask.set(mask.test(r) ? j : r);
+                const uint32_t hit = (uint32_t)__builtin_amdgcn_sbfe((int)w, r, 1u);  // all ones if bit r is set
+                w |= 1u << r;
+                w |= hit & (1u << j);
             }
         });
     }
+    mask.w[0] = w;
+    if (k > M - k) mask.complement(M);
+}
+
+// M <= 64 (two words, handled as one 64-bit value).
+__device__ __forceinline__ void sample_mask(Mask<2>& mask, int M, int k, uint32_t s, uint32_t unit,
+                                            uint32_t stream_id, const PhiloxKeys& ks)
+{
+    const int m = (k < M - k) ? k : (M - k);
+    uint64_t w = 0ull;
+    for (int i0 = 0; i0 < m; i0 += 4) {
+        const Philox4 blk = philox4x32_10(s, (uint32_t)(i0 >> 2), unit, stream_id, ks);
+        static_for<4>([&](auto x) {
+            const int i = i0 + x.value;
+            if (i < m) {
+                const uint32_t j = (uint32_t)(M - m + i);
+                const uint32_t r = __umulhi(blk.x[x.value], j + 1u);
+                const uint32_t hit = 0u - ((uint32_t)(w >> r) & 1u);
+                const uint64_t bj = 1ull << j;  // uniform
+                const uint64_t br = 1ull << r;
+                const uint32_t lo = (uint32_t)w | (uint32_t)br | (hit & (uint32_t)bj);
+                const uint32_t hi = (uint32_t)(w >> 32) | (uint32_t)(br >> 32) | (hit & (uint32_t)(bj >> 32));
+                w = ((uint64_t)hi << 32) | lo;
+            }
+        });
+    }
+    mask.w[0] = (uint32_t)w;
+    mask.w[1] = (uint32_t)(w >> 32);
+    if (k > M - k) mask.complement(M);
+}
+
+// M > 64: the set lives in LDS while it is drawn, word x of this lane at lds[x * stride + lane slot]
+// (conflict-free: the bank depends on the lane only).  One LDS read and two LDS ORs per step whatever the
+// mask width; the finished words are then loaded into registers for the reducer.
+template <int NW>
+__device__ __forceinline__ void sample_mask_lds(Mask<NW>& mask, uint32_t* lds_col, int stride, int M, int k,
+                                                uint32_t s, uint32_t unit, uint32_t stream_id, const PhiloxKeys& ks)
+{
+    const int m = (k < M - k) ? k : (M - k);
+    static_for<NW>([&](auto i) { lds_col[i.value * stride] = 0u; });
+    for (int i0 = 0; i0 < m; i0 += 4) {
+        const Philox4 blk = philox4x32_10(s, (uint32_t)(i0 >> 2), unit, stream_id, ks);
+        static_for<4>([&](auto x) {
+            const int i = i0 + x.value;
+            if (i < m) {
+                const uint32_t j = (uint32_t)(M - m + i);
+                const uint32_t r = __umulhi(blk.x[x.value], j + 1u);
+                uint32_t* pr = lds_col + (r >> 5) * (uint32_t)stride;
+                const uint32_t old = *pr;
+                const uint32_t hit = (uint32_t)__builtin_amdgcn_sbfe((int)old, r & 31u, 1u);  // all ones if bit r is set
+                *pr = old | (1u << (r & 31u));
+                uint32_t* pj = lds_col + (j >> 5) * (uint32_t)stride;  // the same word in every lane
+                atomicOr(pj, hit & (1u << (j & 31u)));                  // LDS operations of a wave stay in order
+            }
+        });
+    }
+    static_for<NW>([&](auto i) { mask.w[i.value] = lds_col[i.value * stride]; });
     if (k > M - k) mask.complement(M);
 }
 
@@ -246,18 +338,11 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
 
 // ------------------------------------------------------------------ histogram update
 
-// Every active lane adds one to bins[val]; lanes with equal values are merged with ballot + popcount
-// so that one lane per distinct value issues the LDS atomic.
-__device__ __forceinline__ void wave_hist_add(uint32_t* bins, int val, bool active)
+// One LDS atomic per lane.  Lanes that hit the same bin are serialised by the LDS bank, not by the
+// vector ALU, which is the unit this kernel is bound by.
+__device__ __forceinline__ void hist_add(uint32_t* bins, int val, bool active)
 {
-    unsigned long long todo = __ballot(active);
-    while (todo != 0ull) {
-        const int leader = __ffsll(todo) - 1;
-        const int v = __builtin_amdgcn_readlane(val, leader);
-        const unsigned long long same = __ballot(active && val == v);
-        if (lane_id() == leader) atomicAdd(&bins[v], (uint32_t)__popcll(same));
-        todo &= ~same;
-    }
+    if (active) atomicAdd(&bins[val], 1u);
 }
 
 // ------------------------------------------------------------------ kernels
@@ -293,24 +378,31 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, uint32_t* __res
     }
 }
 
+// Draws scenario s of a unit into registers, by the path that fits the unit's size.
+template <int NW>
+__device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col, int M, int k, uint32_t s,
+                                              uint32_t unit, uint32_t stream_id, const PhiloxKeys& ks)
+{
+    if constexpr (NW <= 2) {
+        sample_mask(mask, M, k, s, unit, stream_id, ks);
+    } else {
+        sample_mask_lds<NW>(mask, lds_col, kEvalThreads, M, k, s, unit, stream_id, ks);
+    }
+}
+
 template <int NW>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int M, int k, uint32_t unit, uint32_t stream_id,
-                                                uint32_t key0, uint32_t key1, uint32_t s_begin, uint32_t s_end,
-                                                uint32_t* bins_int, uint32_t* bins_min)
+                                                const PhiloxKeys& ks, uint32_t s_begin, uint32_t s_end,
+                                                uint32_t* lds_col, uint32_t* bins_int, uint32_t* bins_min)
 {
-    // the loop bound is rounded up to whole waves so that every lane reaches the ballots
     const uint32_t span = s_end - s_begin;
-    const uint32_t rounded = (span + (uint32_t)blockDim.x - 1u) / (uint32_t)blockDim.x * (uint32_t)blockDim.x;
-    for (uint32_t x = threadIdx.x; x < rounded; x += blockDim.x) {
-        const bool active = x < span;
-        int n_int = 0, d_min = 0;
-        if (active) {
-            Mask<NW> mask;
-            sample_mask<NW>(mask, M, k, s_begin + x, unit, stream_id, key0, key1);
-            reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
-        }
-        wave_hist_add(bins_int, n_int, active);
-        wave_hist_add(bins_min, d_min, active);
+    for (uint32_t x = threadIdx.x; x < span; x += blockDim.x) {
+        int n_int, d_min;
+        Mask<NW> mask;
+        draw_scenario<NW>(mask, lds_col, M, k, s_begin + x, unit, stream_id, ks);
+        reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
+        hist_add(bins_int, n_int, true);
+        hist_add(bins_min, d_min, true);
     }
 }
 
@@ -320,6 +412,7 @@ __global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, int n_
                                                                  uint32_t* __restrict__ hist_min)
 {
     __shared__ uint32_t bins[2 * (kMaxInstances + 1)];
+    __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
     const uint32_t unit_global = blockIdx.x / (uint32_t)n_chunks;  // q * T * C + t * C + c
     const int chunk = (int)(blockIdx.x % (uint32_t)n_chunks);
     const int tc = (int)(unit_global % (uint32_t)(b.T * b.C));
@@ -338,16 +431,17 @@ __global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, int n_
     __syncthreads();
 
     const uint64_t seed = b.seed[q];
-    const uint32_t key0 = (uint32_t)(seed & 0xffffffffull), key1 = (uint32_t)(seed >> 32);
+    const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
     const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
     const uint32_t s_begin = (uint32_t)chunk * (uint32_t)chunk_len;
     uint32_t s_end = s_begin + (uint32_t)chunk_len;
     s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
+    uint32_t* lds_col = lmask + threadIdx.x;
 
-    if (M <= 32) eval_unit_chunk<1>(cr, M, k, (uint32_t)tc, stream_id, key0, key1, s_begin, s_end, bins_int, bins_min);
-    else if (M <= 64) eval_unit_chunk<2>(cr, M, k, (uint32_t)tc, stream_id, key0, key1, s_begin, s_end, bins_int, bins_min);
-    else if (M <= 128) eval_unit_chunk<4>(cr, M, k, (uint32_t)tc, stream_id, key0, key1, s_begin, s_end, bins_int, bins_min);
-    else eval_unit_chunk<8>(cr, M, k, (uint32_t)tc, stream_id, key0, key1, s_begin, s_end, bins_int, bins_min);
+    if (M <= 32) eval_unit_chunk<1>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+    else if (M <= 64) eval_unit_chunk<2>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+    else if (M <= 128) eval_unit_chunk<4>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+    else eval_unit_chunk<8>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
     __syncthreads();
 
     const int64_t base = ((int64_t)q * b.T + t) * b.L + cr.off;
@@ -363,24 +457,44 @@ __global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, int n_
     }
 }
 
-// Scenarios one by one, for inspection: masks [ns][8], n_int [ns], d_min [ns].
-__global__ void __launch_bounds__(256) debug_sample_kernel(Batch b, int q, int t, int c, uint32_t s0, uint32_t ns,
-                                                           uint32_t* __restrict__ masks, int32_t* __restrict__ n_int_out,
-                                                           int32_t* __restrict__ d_min_out)
+// One scenario through the same code path the histogram kernel takes for a unit of this size.
+template <int NW>
+__device__ __forceinline__ void debug_one(const CfgRec cr, uint32_t* lds_col, int M, int k, uint32_t s, uint32_t unit,
+                                          uint32_t stream_id, const PhiloxKeys& ks, uint32_t* mask_out, int& n_int,
+                                          int& d_min)
 {
+    Mask<NW> mask;
+    draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
+    reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
+    static_for<8>([&](auto i) {
+        if constexpr (i.value < NW) mask_out[i.value] = mask.w[i.value];
+        else mask_out[i.value] = 0u;
+    });
+}
+
+// Scenarios one by one, for inspection: masks [ns][8], n_int [ns], d_min [ns].
+__global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int q, int t, int c, uint32_t s0,
+                                                                    uint32_t ns, uint32_t* __restrict__ masks,
+                                                                    int32_t* __restrict__ n_int_out,
+                                                                    int32_t* __restrict__ d_min_out)
+{
+    __shared__ uint32_t lmask[8 * kEvalThreads];
     const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
     if (x >= ns) return;
     const CfgRec cr = b.cfg[c];
     int M, k;
     unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
     const uint64_t seed = b.seed[q];
+    const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
     const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
-    Mask<8> mask;
-    sample_mask<8>(mask, M, k, s0 + x, (uint32_t)(t * b.C + c), stream_id, (uint32_t)(seed & 0xffffffffull),
-                   (uint32_t)(seed >> 32));
+    const uint32_t unit = (uint32_t)(t * b.C + c);
+    uint32_t* lds_col = lmask + threadIdx.x;
+    uint32_t* out = masks + (size_t)x * 8;
     int n_int, d_min;
-    reduce_mask<8>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
-    static_for<8>([&](auto i) { masks[(size_t)x * 8 + i.value] = mask.w[i.value]; });
+    if (M <= 32) debug_one<1>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else if (M <= 64) debug_one<2>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else if (M <= 128) debug_one<4>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else debug_one<8>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
     n_int_out[x] = n_int;
     d_min_out[x] = d_min;
 }

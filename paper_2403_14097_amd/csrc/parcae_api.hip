@@ -327,7 +327,7 @@ int parcae_debug_sample(const parcae_problem* p, int32_t q, int32_t t, int32_t c
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
-    parcae::debug_sample_kernel<<<dim3((ns + 255u) / 256u), dim3(256), 0, st>>>(b, q, t, c, s0, ns, masks, n_int,
+    parcae::debug_sample_kernel<<<dim3((ns + 255u) / 256u), dim3(parcae::kEvalThreads), 0, st>>>(b, q, t, c, s0, ns, masks, n_int,
                                                                                   d_min);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
