@@ -31,7 +31,8 @@ def algorithmic_lane_ops(configs, avail, n_scenarios):
     A(M, k, P) = 33 m + 2 P W + P + W (log2 P + 2) + 10 with m = min(k, M - k) random words (25 operations for a
     quarter of a Philox4x32-10 block plus 8 for one step of the subset draw), W = ceil(M / 32) mask words (an
     and + popcount per stage and word, a min per stage, an OR-fold per word for the untouched pipelines) and 10
-    for the two histogram updates.  Units with k = 0 or k = M have a closed form and count as zero.
+    for the two histogram updates.  Units whose scenarios all land in one bin (k = 0, k = M, a single stage, or a
+    single pipeline) have a closed form and count as zero.
     Returns (total lane-ops, scenarios of non-trivial units).
     """
     import numpy as np
@@ -43,8 +44,9 @@ def algorithmic_lane_ops(configs, avail, n_scenarios):
     W = (M + 31) // 32
     lg = np.ceil(np.log2(np.maximum(P, 1))).astype(np.int64)
     fixed = 2 * P * W + P + W * (lg + 2) + 10
-    A = np.where(m > 0, 33 * m + fixed[None, None, :], 0)
-    return float(A.sum()) * n_scenarios, int((m > 0).sum()) * n_scenarios
+    sampled = (m > 0) & (P > 1)[None, None, :] & (D > 1)[None, None, :]
+    A = np.where(sampled, 33 * m + fixed[None, None, :], 0)
+    return float(A.sum()) * n_scenarios, int(sampled.sum()) * n_scenarios
 
 
 class HipEvents:

@@ -41,6 +41,18 @@ __device__ __forceinline__ void unit_pool(int D, int P, int a, int N, int& M, in
     k = k < 0 ? 0 : k;
 }
 
+// Units whose scenarios all fall into one histogram bin (the same bin in both histograms), so that no
+// sampling is needed: nothing preempted (bin D), everything preempted (bin 0), a single stage (every
+// preemption removes exactly one pipeline: bin D - k) or a single pipeline that is hit (bin 0).
+__device__ __forceinline__ bool unit_closed_form(int D, int P, int M, int k, int& bin)
+{
+    if (k == 0) { bin = D; return true; }
+    if (k == M) { bin = 0; return true; }
+    if (P == 1) { bin = D - k; return true; }
+    if (D == 1) { bin = 0; return true; }
+    return false;
+}
+
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 
 }  // namespace parcae

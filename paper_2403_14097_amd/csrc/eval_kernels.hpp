@@ -224,7 +224,7 @@ __device__ __forceinline__ uint32_t comb32(int log2P)
     }
 }
 
-// Vertical (bit-sliced) counters: plane p holds bit p of one counter per bit position.
+// Vertical (bit-sliced) counters: plane i holds bit i of one counter per bit position.
 template <int NP>
 struct Planes {
     uint32_t p[NP];
@@ -232,20 +232,41 @@ struct Planes {
     {
         static_for<NP>([&](auto i) { p[i.value] = 0u; });
     }
-    // add one to the counter of every position whose bit is set in x
+    // add one to the counter of every position whose bit is set in x; the carry ripples through the
+    // lowest N planes (the caller knows the counters stay below 2^N)
+    template <int N = NP>
     __device__ __forceinline__ void add(uint32_t x)
     {
         uint32_t carry = x;
-        static_for<NP>([&](auto i) {
+        static_for<N>([&](auto i) {
             const uint32_t t = p[i.value] & carry;
             p[i.value] ^= carry;
             carry = t;
         });
     }
-    // largest counter over all positions
-    __device__ __forceinline__ int max() const
+    // counters of position b += counters of position b + sh, for N-plane inputs; the result has N + 1 planes
+    template <int N>
+    __device__ __forceinline__ void fold(int sh)
     {
-        uint32_t cand = 0xffffffffu;
+        static_assert(N + 1 <= NP, "no room for the carry plane");
+        uint32_t carry = 0u;
+        static_for<N>([&](auto i) {
+            const uint32_t a = p[i.value];
+            const uint32_t b = a >> sh;
+            if constexpr (i.value == 0) {
+                p[0] = a ^ b;
+                carry = a & b;
+            } else {
+                p[i.value] = __builtin_amdgcn_bitop3_b32(a, b, carry, 0x96);   // a ^ b ^ carry
+                carry = __builtin_amdgcn_bitop3_b32(a, b, carry, 0xE8);        // majority
+            }
+        });
+        p[N] = carry;
+    }
+    // largest counter over the positions selected by keep
+    __device__ __forceinline__ int max(uint32_t keep = 0xffffffffu) const
+    {
+        uint32_t cand = keep;
         int result = 0;
         static_for<NP>([&](auto i) {
             constexpr int bit = NP - 1 - i.value;
@@ -258,6 +279,22 @@ struct Planes {
         return result;
     }
 };
+
+// Largest number of preempted instances in any stage, P a power of two in [8, 32]: the words are added
+// as vertical counters (rows of different words are aligned because P divides 32), then the rows inside
+// the word are folded onto the lowest row.
+template <int NW>
+__device__ __forceinline__ int worst_stage_tree(const Mask<NW>& mask, int P)
+{
+    constexpr int NP0 = (NW == 1) ? 1 : (NW == 2) ? 2 : (NW == 4) ? 3 : 4;  // planes that hold a count of NW
+    Planes<NP0 + 2> pl;
+    pl.clear();
+    static_for<NW>([&](auto i) { pl.template add<NP0>(mask.w[i.value]); });
+    if (P <= 16) pl.template fold<NP0>(16);
+    if (P <= 8) pl.template fold<NP0 + 1>(8);
+    const uint32_t keep = (P >= 32) ? 0xffffffffu : ((1u << P) - 1u);
+    return pl.max(keep);
+}
 
 // n_int (pipelines without a preempted instance) and d_min (fewest survivors in any stage)
 // of a D x P grid whose preempted instances are the set bits of mask; instance j = d * P + s.
@@ -274,7 +311,7 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
             broken += __popc(y & comb);
         });
         n_int = D - broken;
-        if (P <= 16) {
+        if (P <= 4) {
             // stages: popcount of the stride-P comb shifted to the stage
             int worst = 0;
             for (int s = 0; s < P; ++s) {
@@ -285,11 +322,7 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
             }
             d_min = D - worst;
         } else {
-            // P == 32: one word per pipeline (D <= 8), add the words as vertical counters
-            Planes<4> pl;
-            pl.clear();
-            static_for<NW>([&](auto i) { pl.add(mask.w[i.value]); });
-            d_min = D - pl.max();
+            d_min = D - worst_stage_tree<NW>(mask, P);
         }
     } else if (log2P >= 6) {
         // P in {64, 128, 256}: a pipeline is P/32 whole words, D <= 4
@@ -349,11 +382,25 @@ __device__ __forceinline__ void hist_add(uint32_t* bins, int val, bool active)
 
 constexpr int kEvalThreads = 256;
 
-// Clears the histograms and writes the closed-form bins of units that need no sampling:
-// k == 0 puts all S scenarios in bin D, k == M in bin 0 (of both histograms).
-__global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, uint32_t* __restrict__ hist_int,
+// Work queue of the sampling kernel, in the workspace.  The items are split into kQueueShards contiguous
+// ranges, each with its own claim counter: atomics on ONE address complete at a fixed, low rate (about 86
+// per microsecond on this chip), which a single counter would turn into the bottleneck of small launches.
+constexpr int kQueueShards = 32;
+constexpr int kShardStride = 64;  // counters sit 256 bytes apart: atomics on one cache line serialise too
+struct WorkQueue {
+    uint32_t* list;   // [n_units] global unit indices (q * T * C + t * C + c) that need sampling, any order
+    uint32_t* count;  // number of entries of list
+    uint32_t* next;   // [kQueueShards * kShardStride] items handed out so far in shard i at next[i * kShardStride]
+};
+
+// Clears the histograms, writes the single bin of the units that need no sampling, resets the work queue.
+__global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, WorkQueue wq, uint32_t* __restrict__ hist_int,
                                                         uint32_t* __restrict__ hist_min)
 {
+    if (blockIdx.x == 0 && threadIdx.x < kQueueShards) {
+        if (threadIdx.x == 0) *wq.count = 0u;
+        wq.next[threadIdx.x * kShardStride] = 0u;
+    }
     const int64_t total = (int64_t)b.nq * b.T * b.L;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         const int pos = (int)(e % b.L);
@@ -370,12 +417,35 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, uint32_t* __res
         const int j = pos - cr.off;
         int M, k;
         unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
-        uint32_t v = 0u;
-        if (k == 0) v = (j == cr.D) ? (uint32_t)b.S : 0u;
-        else if (k == M) v = (j == 0) ? (uint32_t)b.S : 0u;
+        int bin;
+        const uint32_t v = (unit_closed_form(cr.D, cr.P, M, k, bin) && j == bin) ? (uint32_t)b.S : 0u;
         hist_int[e] = v;
         hist_min[e] = v;
     }
+}
+
+// Appends every unit that needs sampling to the work list (one thread per unit, one atomic per wave).
+__global__ void __launch_bounds__(256) build_work_kernel(Batch b, WorkQueue wq)
+{
+    const int64_t n_units = (int64_t)b.nq * b.T * b.C;
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool need = false;
+    if (u < n_units) {
+        const int tc = (int)(u % ((int64_t)b.T * b.C));
+        const int q = (int)(u / ((int64_t)b.T * b.C));
+        const int t = tc / b.C;
+        const CfgRec cr = b.cfg[tc - t * b.C];
+        int M, k, bin;
+        unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+        need = !unit_closed_form(cr.D, cr.P, M, k, bin);
+    }
+    const unsigned long long votes = __ballot(need);
+    if (votes == 0ull) return;
+    const int lane = lane_id();
+    uint32_t base = 0u;
+    if (lane == __ffsll(votes) - 1) base = atomicAdd(wq.count, (uint32_t)__popcll(votes));
+    base = __builtin_amdgcn_readlane(base, __ffsll(votes) - 1);
+    if (need) wq.list[base + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = (uint32_t)u;
 }
 
 // Draws scenario s of a unit into registers, by the path that fits the unit's size.
@@ -390,70 +460,113 @@ __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col,
     }
 }
 
+// One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.
 template <int NW>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int M, int k, uint32_t unit, uint32_t stream_id,
                                                 const PhiloxKeys& ks, uint32_t s_begin, uint32_t s_end,
                                                 uint32_t* lds_col, uint32_t* bins_int, uint32_t* bins_min)
 {
-    const uint32_t span = s_end - s_begin;
-    for (uint32_t x = threadIdx.x; x < span; x += blockDim.x) {
+    for (uint32_t s = s_begin + (uint32_t)lane_id(); s < s_end; s += kWave) {
         int n_int, d_min;
         Mask<NW> mask;
-        draw_scenario<NW>(mask, lds_col, M, k, s_begin + x, unit, stream_id, ks);
+        draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
         reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int, true);
         hist_add(bins_min, d_min, true);
     }
 }
 
-// Block b handles scenarios [chunk * chunk_len, ...) of unit b / n_chunks.
-__global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, int n_chunks, int chunk_len,
+// Persistent kernel: every wave pulls (unit, chunk) items from the work queue until it is empty, so waves never
+// wait for each other and units without sampling cost nothing here.  Item i is chunk i % n_chunks of
+// list[i / n_chunks]; a chunk is chunk_len consecutive scenarios.  Each wave owns a slice of the LDS bins.
+__global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {
-    __shared__ uint32_t bins[2 * (kMaxInstances + 1)];
+    constexpr int kWaves = kEvalThreads / kWave;
+    __shared__ uint32_t bins_all[kWaves][2 * (kMaxInstances + 1)];
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
-    const uint32_t unit_global = blockIdx.x / (uint32_t)n_chunks;  // q * T * C + t * C + c
-    const int chunk = (int)(blockIdx.x % (uint32_t)n_chunks);
-    const int tc = (int)(unit_global % (uint32_t)(b.T * b.C));
-    const int q = (int)(unit_global / (uint32_t)(b.T * b.C));
-    const int t = tc / b.C;
-    const int c = tc - t * b.C;
-    const CfgRec cr = b.cfg[c];
-    int M, k;
-    unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
-    if (k == 0 || k == M) return;  // closed form, written by prep_hist_kernel
-
-    const int nb = cr.D + 1;
-    uint32_t* bins_int = bins;
-    uint32_t* bins_min = bins + nb;
-    for (int i = threadIdx.x; i < 2 * nb; i += blockDim.x) bins[i] = 0u;
-    __syncthreads();
-
-    const uint64_t seed = b.seed[q];
-    const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
-    const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
-    const uint32_t s_begin = (uint32_t)chunk * (uint32_t)chunk_len;
-    uint32_t s_end = s_begin + (uint32_t)chunk_len;
-    s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
+    const int lane = lane_id();
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
+    uint32_t* bins = bins_all[wave];
     uint32_t* lds_col = lmask + threadIdx.x;
+    const uint32_t total = *wq.count * (uint32_t)n_chunks;
+    // A wave claims `batch` consecutive items at a time (about eight claims per wave over the launch), first
+    // from its home shard, then from the following shards; a shard is probed with a plain load before the
+    // atomic, so exhausted shards cost no serialised traffic.  Every wave leaves after at most
+    // kQueueShards failed probes.
+    const uint32_t per_shard = (total + kQueueShards - 1u) / kQueueShards;
+    uint32_t batch = total / ((uint32_t)gridDim.x * kWaves * 8u);
+    batch = batch < 1u ? 1u : (batch > 64u ? 64u : batch);
+    const uint32_t home = ((uint32_t)blockIdx.x * kWaves + wave) % kQueueShards;
+    uint32_t visited = 0u;
+    uint32_t item = 0u, item_end = 0u;
 
-    if (M <= 32) eval_unit_chunk<1>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-    else if (M <= 64) eval_unit_chunk<2>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-    else if (M <= 128) eval_unit_chunk<4>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-    else eval_unit_chunk<8>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-    __syncthreads();
-
-    const int64_t base = ((int64_t)q * b.T + t) * b.L + cr.off;
-    for (int i = threadIdx.x; i < nb; i += blockDim.x) {
-        const uint32_t vi = bins_int[i], vm = bins_min[i];
-        if (n_chunks == 1) {
-            hist_int[base + i] = vi;
-            hist_min[base + i] = vm;
-        } else {
-            if (vi) atomicAdd(&hist_int[base + i], vi);
-            if (vm) atomicAdd(&hist_min[base + i], vm);
+    for (;;) {
+        while (item == item_end && visited < (uint32_t)kQueueShards) {
+            const uint32_t shard = (home + visited) % kQueueShards;
+            const uint32_t lo = shard * per_shard;
+            uint32_t hi = lo + per_shard;
+            hi = hi > total ? total : hi;
+            uint32_t first = hi;
+            if (lo < hi && __hip_atomic_load(&wq.next[shard * kShardStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < hi - lo) {
+                uint32_t got = 0u;
+                if (lane == 0) got = atomicAdd(&wq.next[shard * kShardStride], batch);
+                first = lo + __builtin_amdgcn_readfirstlane(got);
+            }
+            if (first < hi) {
+                item = first;
+                item_end = first + batch < hi ? first + batch : hi;
+            } else {
+                ++visited;
+            }
         }
+        if (item == item_end) break;
+        const uint32_t unit_global = wq.list[item / (uint32_t)n_chunks];
+        const int chunk = (int)(item % (uint32_t)n_chunks);
+        ++item;
+        const int tc = (int)(unit_global % (uint32_t)(b.T * b.C));
+        const int q = (int)(unit_global / (uint32_t)(b.T * b.C));
+        const int t = tc / b.C;
+        const int c = tc - t * b.C;
+        const CfgRec cr = b.cfg[c];
+        int M, k;
+        unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+
+        const int nb = cr.D + 1;
+        uint32_t* bins_int = bins;
+        uint32_t* bins_min = bins + nb;
+        for (int i = lane; i < 2 * nb; i += kWave) bins[i] = 0u;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        const uint64_t seed = b.seed[q];
+        const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
+        const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
+        const uint32_t s_begin = (uint32_t)chunk * (uint32_t)chunk_len;
+        uint32_t s_end = s_begin + (uint32_t)chunk_len;
+        s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
+
+        if (M <= 32) eval_unit_chunk<1>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else if (M <= 64) eval_unit_chunk<2>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else if (M <= 128) eval_unit_chunk<4>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else eval_unit_chunk<8>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        const int64_t base = ((int64_t)q * b.T + t) * b.L + cr.off;
+        for (int i = lane; i < nb; i += kWave) {
+            const uint32_t vi = bins_int[i], vm = bins_min[i];
+            if (n_chunks == 1) {
+                hist_int[base + i] = vi;
+                hist_min[base + i] = vm;
+            } else {
+                if (vi) atomicAdd(&hist_int[base + i], vi);
+                if (vm) atomicAdd(&hist_min[base + i], vm);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

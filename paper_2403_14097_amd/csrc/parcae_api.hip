@@ -24,7 +24,7 @@ constexpr size_t kMaxPlanLds = 60 * 1024;  // dynamic LDS per block, leaves room
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t cfg_off, valid_off, bp_off, total;
+    size_t cfg_off, valid_off, bp_off, queue_off, list_off, total;
     int64_t L;
     int max_row;  // bins of the widest candidate, max over c of D_c + 1
 };
@@ -67,8 +67,10 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
         lay->cfg_off = 0;
         lay->valid_off = align_up(sizeof(CfgRec) * (size_t)p->n_configs);
         lay->bp_off = lay->valid_off + align_up(sizeof(int32_t) * (size_t)p->n_queries);
-        lay->total = lay->bp_off +
-                     align_up(sizeof(int32_t) * (size_t)p->n_queries * (size_t)p->n_intervals * (size_t)p->n_configs);
+        const size_t n_units = (size_t)p->n_queries * (size_t)p->n_intervals * (size_t)p->n_configs;
+        lay->queue_off = lay->bp_off + align_up(sizeof(int32_t) * n_units);
+        lay->list_off = lay->queue_off + kAlign * (1 + parcae::kQueueShards);  // item count, then one line per shard counter
+        lay->total = lay->list_off + align_up(sizeof(uint32_t) * n_units);
     }
     return PARCAE_OK;
 }
@@ -136,28 +138,57 @@ int pick_plan_cap(int C, const Layout& lay)
     return cap >= lay.max_row ? (int)cap : -1;
 }
 
-// Scenarios per block of the sampling kernel.
-int pick_chunk_len(int S) { return S < 2048 ? S : 2048; }
+// Scenarios per work item of the sampling kernel (one wave processes an item, 64 scenarios at a time):
+// 1024 when there is plenty of work, down to 256 when there is little, so that every wave still gets
+// several items and a late heavy item cannot dominate the launch.
+int pick_chunk_len(int64_t n_units, int S, int64_t n_waves)
+{
+    int64_t want = n_units * (int64_t)S / (n_waves * 64);
+    int chunk = 1024;
+    while (chunk > 256 && chunk > want) chunk >>= 1;
+    return S < chunk ? S : chunk;
+}
+
+parcae::WorkQueue make_queue(const Layout& lay, void* ws)
+{
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    parcae::WorkQueue wq;
+    wq.count = reinterpret_cast<uint32_t*>(base + lay.queue_off);
+    wq.next = wq.count + kAlign / sizeof(uint32_t);
+    wq.list = reinterpret_cast<uint32_t*>(base + lay.list_off);
+    return wq;
+}
 
 int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void* ws, uint32_t* hist_int,
                 uint32_t* hist_min, float* liveput, float* teff, float* gain, int32_t* status, hipStream_t st)
 {
     const int64_t n_units = (int64_t)b.nq * b.T * b.C;
-    const int chunk_len = pick_chunk_len(b.S);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return PARCAE_EHIP;
+    const int chunk_len = pick_chunk_len(n_units, b.S, (int64_t)cus * 32);
     const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
-    if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counter to overshoot
+    const parcae::WorkQueue wq = make_queue(lay, ws);
 
     const int64_t elems = (int64_t)b.nq * b.T * b.L;
     int64_t prep_blocks = (elems + 255) / 256;
     if (prep_blocks > 65536) prep_blocks = 65536;
-    parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, hist_int, hist_min);
+    parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, wq, hist_int, hist_min);
+    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    parcae::build_work_kernel<<<dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, st>>>(b, wq);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
 
+    // persistent waves: enough blocks to fill every compute unit, never more than there are items
+    int64_t eval_blocks = (int64_t)cus * 8;
+    const int64_t max_useful = (n_units * n_chunks + 3) / 4;
+    if (eval_blocks > max_useful) eval_blocks = max_useful;
     if (p->event_before_sampling &&
         hipEventRecord(static_cast<hipEvent_t>(p->event_before_sampling), st) != hipSuccess)
         return PARCAE_EHIP;
-    parcae::eval_hist_kernel<<<dim3((unsigned)(n_units * n_chunks)), dim3(parcae::kEvalThreads), 0, st>>>(
-        b, n_chunks, chunk_len, hist_int, hist_min);
+    parcae::eval_hist_kernel<<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
+        b, wq, n_chunks, chunk_len, hist_int, hist_min);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     if (p->event_after_sampling &&
         hipEventRecord(static_cast<hipEvent_t>(p->event_after_sampling), st) != hipSuccess)
