@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 namespace parcae {
 
 constexpr int kWave = 64;
@@ -51,6 +53,21 @@ __device__ __forceinline__ bool unit_closed_form(int D, int P, int M, int k, int
     if (P == 1) { bin = D - k; return true; }
     if (D == 1) { bin = 0; return true; }
     return false;
+}
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>).  Register arrays are
+// only ever indexed with these constants, so they are split into scalar registers before any other
+// optimisation sees them (a run-time loop, even one unrolled later, lets the optimiser turn a chain of
+// selects into one indexed load from scratch memory).
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }

@@ -7,8 +7,6 @@
 // vector registers per lane (NW = 1, 2, 4 or 8 by the unit's size).
 #pragma once
 
-#include <utility>
-
 #include "device_common.hpp"
 
 namespace parcae {
@@ -72,21 +70,6 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 // ------------------------------------------------------------------ bit set in registers
-
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>).  Register arrays are
-// only ever indexed with these constants, so they are split into scalar registers before any other
-// optimisation sees them (a run-time loop, even one unrolled later, lets the optimiser turn a chain of
-// selects into one indexed load from scratch memory).
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
-}
 
 template <int NW>
 struct Mask {
@@ -424,9 +407,14 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, WorkQueue wq, u
     }
 }
 
-// Appends every unit that needs sampling to the work list (one thread per unit, one atomic per wave).
-__global__ void __launch_bounds__(256) build_work_kernel(Batch b, WorkQueue wq)
+// Appends every unit that needs sampling to the work list: one thread per unit, positions inside the
+// block by ballot + LDS prefix, ONE global atomic per block of 1024 units (atomics on one address are slow).
+constexpr int kBuildThreads = 1024;
+__global__ void __launch_bounds__(kBuildThreads) build_work_kernel(Batch b, WorkQueue wq)
 {
+    constexpr int kWaves = kBuildThreads / kWave;
+    __shared__ uint32_t wave_count[kWaves];
+    __shared__ uint32_t wave_base[kWaves];
     const int64_t n_units = (int64_t)b.nq * b.T * b.C;
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool need = false;
@@ -440,12 +428,21 @@ __global__ void __launch_bounds__(256) build_work_kernel(Batch b, WorkQueue wq)
         need = !unit_closed_form(cr.D, cr.P, M, k, bin);
     }
     const unsigned long long votes = __ballot(need);
-    if (votes == 0ull) return;
     const int lane = lane_id();
-    uint32_t base = 0u;
-    if (lane == __ffsll(votes) - 1) base = atomicAdd(wq.count, (uint32_t)__popcll(votes));
-    base = __builtin_amdgcn_readlane(base, __ffsll(votes) - 1);
-    if (need) wq.list[base + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = (uint32_t)u;
+    const int wave = (int)threadIdx.x / kWave;
+    if (lane == 0) wave_count[wave] = (uint32_t)__popcll(votes);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t sum = 0u;
+        for (int w = 0; w < kWaves; ++w) {
+            wave_base[w] = sum;
+            sum += wave_count[w];
+        }
+        const uint32_t base = sum ? atomicAdd(wq.count, sum) : 0u;
+        for (int w = 0; w < kWaves; ++w) wave_base[w] += base;
+    }
+    __syncthreads();
+    if (need) wq.list[wave_base[wave] + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = (uint32_t)u;
 }
 
 // Draws scenario s of a unit into registers, by the path that fits the unit's size.

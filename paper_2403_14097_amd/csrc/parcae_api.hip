@@ -19,12 +19,16 @@ using parcae::CfgRec;
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxConfigsDp = 4096;
+constexpr int kFusedMinQueries = 32;     // fewer queries than this: weights go to memory, steps are spread over the chip
+constexpr int kSingleBlockMaxConfigs = 128;  // stepwise DP: up to this many candidates one block per query does all steps
+constexpr size_t kMaxBpLds = 16 * 1024;  // back-pointers stay in LDS (16-bit) when they fit in this
 constexpr size_t kMaxPlanLds = 60 * 1024;  // dynamic LDS per block, leaves room for the static part within 64 KB
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t cfg_off, valid_off, bp_off, queue_off, list_off, total;
+    size_t cfg_off, valid_off, bp_off, queue_off, list_off, w_off, f_off, total;
+    bool stepwise;  // few queries: weights are written out and the DP runs on them
     int64_t L;
     int max_row;  // bins of the widest candidate, max over c of D_c + 1
 };
@@ -70,7 +74,13 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
         const size_t n_units = (size_t)p->n_queries * (size_t)p->n_intervals * (size_t)p->n_configs;
         lay->queue_off = lay->bp_off + align_up(sizeof(int32_t) * n_units);
         lay->list_off = lay->queue_off + kAlign * (1 + parcae::kQueueShards);  // item count, then one line per shard counter
-        lay->total = lay->list_off + align_up(sizeof(uint32_t) * n_units);
+        lay->w_off = lay->list_off + align_up(sizeof(uint32_t) * n_units);
+        lay->stepwise = p->n_queries < kFusedMinQueries;
+        const size_t w_bytes = lay->stepwise ? sizeof(float) * n_units * (size_t)p->n_configs : 0;
+        const size_t f_bytes =
+            lay->stepwise ? sizeof(float) * (size_t)p->n_queries * ((size_t)p->n_intervals + 1) * (size_t)p->n_configs : 0;
+        lay->f_off = lay->w_off + align_up(w_bytes);
+        lay->total = lay->f_off + align_up(f_bytes);
     }
     return PARCAE_OK;
 }
@@ -129,13 +139,20 @@ int32_t* valid_ptr(const Layout& lay, void* ws)
 
 // Histogram bins the planning kernels keep in LDS at a time: all of them if they fit, else as many as
 // the LDS budget allows; -1 if not even the widest row fits next to the per-candidate tables.
-int pick_plan_cap(int C, const Layout& lay)
+int pick_plan_cap(int C, const Layout& lay, size_t bp16_bytes)
 {
-    const size_t fixed = parcae::plan_lds_bytes(C, 0);
+    const size_t fixed = parcae::plan_lds_bytes(C, 0, bp16_bytes);
     if (fixed >= kMaxPlanLds) return -1;
     int64_t cap = (int64_t)((kMaxPlanLds - fixed) / 8);
     if (cap > lay.L) cap = lay.L;
     return cap >= lay.max_row ? (int)cap : -1;
+}
+
+// Bytes of a 16-bit copy of the back-pointers of one query if it is small enough to live in LDS, else 0.
+size_t bp16_bytes_for(int T, int C)
+{
+    const size_t need = sizeof(uint16_t) * (size_t)T * (size_t)C;
+    return need <= kMaxBpLds ? need : 0;
 }
 
 // Scenarios per work item of the sampling kernel (one wave processes an item, 64 scenarios at a time):
@@ -177,7 +194,8 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     if (prep_blocks > 65536) prep_blocks = 65536;
     parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, wq, hist_int, hist_min);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
-    parcae::build_work_kernel<<<dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, st>>>(b, wq);
+    parcae::build_work_kernel<<<dim3((unsigned)((n_units + parcae::kBuildThreads - 1) / parcae::kBuildThreads)),
+                                dim3(parcae::kBuildThreads), 0, st>>>(b, wq);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
 
     // persistent waves: enough blocks to fill every compute unit, never more than there are items
@@ -207,18 +225,66 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     return PARCAE_OK;
 }
 
+// The DP on weights held in memory.  F_scratch is used when the caller wants no F and the stepwise kernels need one.
+int launch_dp(const float* W, int nq, int T, int C, const int32_t* valid, float* F, float* F_scratch, int32_t* bp,
+              int32_t* plan, int32_t* start, float* objective, int32_t* status, hipStream_t st)
+{
+    const bool spread = C > kSingleBlockMaxConfigs && nq < kFusedMinQueries && (F || F_scratch);
+    if (!spread) {
+        const size_t b16 = bp16_bytes_for(T, C);
+        const size_t lds = parcae::dp_lds_bytes(C, b16);
+        parcae::dp_kernel<<<dim3((unsigned)nq), dim3(parcae::kPlanThreads), lds, st>>>(
+            W, T, C, b16 ? 1 : 0, valid, F, bp, plan, start, objective, status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+        return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+    }
+    float* F_use = F ? F : F_scratch;
+    for (int t = 0; t < T; ++t) {
+        parcae::dp_step_kernel<<<dim3((unsigned)((C + parcae::kStepCols - 1) / parcae::kStepCols), (unsigned)nq),
+                                 dim3(parcae::kPlanThreads), sizeof(float) * (size_t)C, st>>>(W, T, C, t, F_use, bp);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
+    parcae::dp_finish_kernel<<<dim3((unsigned)((nq + 63) / 64)), dim3(64), 0, st>>>(
+        nq, T, C, valid, F_use, bp, plan, start, objective, status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
 int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* hist_int, const uint32_t* hist_min,
                 float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
                 hipStream_t st)
 {
-    const int cap = pick_plan_cap(b.C, lay);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
+    if (lay.stepwise) {
+        // few queries: every (query, step) writes its weights in parallel, then the DP runs on them
+        const int cap = pick_plan_cap(b.C, lay, 0);
+        if (cap < 0 || b.C > kMaxConfigsDp) return PARCAE_EINVAL;
+        float* W = reinterpret_cast<float*>(base + lay.w_off);
+        parcae::transition_kernel<<<dim3((unsigned)(b.nq * b.T)), dim3(parcae::kPlanThreads),
+                                    parcae::plan_lds_bytes(b.C, cap, 0), st>>>(b, cap, hist_int, hist_min, W);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+        return launch_dp(W, b.nq, b.T, b.C, valid_ptr(lay, ws), F, reinterpret_cast<float*>(base + lay.f_off), bp_use,
+                         plan, start, objective, status, st);
+    }
+    const size_t b16 = bp16_bytes_for(b.T, b.C);
+    int cap = pick_plan_cap(b.C, lay, b16);
+    size_t b16_use = b16;
+    if (cap < 0) {  // no room for the LDS copy of the back-pointers: walk back through memory instead
+        b16_use = 0;
+        cap = pick_plan_cap(b.C, lay, 0);
+    }
     if (cap < 0) return PARCAE_EINVAL;
-    const size_t lds = parcae::plan_lds_bytes(b.C, cap);
-    int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.bp_off);
-    parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(256), lds, st>>>(
-        b, cap, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status, PARCAE_EINVAL,
-        PARCAE_EINFEASIBLE);
+    parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(parcae::kPlanThreads),
+                                parcae::plan_lds_bytes(b.C, cap, b16_use), st>>>(
+        b, cap, b16_use ? 1 : 0, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status,
+        PARCAE_EINVAL, PARCAE_EINFEASIBLE);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+// Whether the planning kernels can take this problem (LDS budget, candidate limit of the stepwise path).
+bool plan_fits(const parcae_problem* p, const Layout& lay)
+{
+    if (lay.stepwise && p->n_configs > kMaxConfigsDp) return false;
+    return pick_plan_cap(p->n_configs, lay, 0) >= 0;
 }
 
 }  // namespace
@@ -301,7 +367,7 @@ int parcae_liveput_plan(const parcae_problem* p, uint32_t* hist_int, uint32_t* h
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
-    if (pick_plan_cap(p->n_configs, lay) < 0) return PARCAE_EINVAL;
+    if (!plan_fits(p, lay)) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
@@ -319,9 +385,9 @@ int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int,
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !W) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
-    const int cap = pick_plan_cap(p->n_configs, lay);
+    const int cap = pick_plan_cap(p->n_configs, lay, 0);
     if (cap < 0) return PARCAE_EINVAL;
-    const size_t lds = parcae::plan_lds_bytes(p->n_configs, cap);
+    const size_t lds = parcae::plan_lds_bytes(p->n_configs, cap, 0);
     if ((int64_t)p->n_queries * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
@@ -335,11 +401,9 @@ int parcae_dp_plan(const float* W, int32_t n_queries, int32_t n_intervals, int32
 {
     if (!W || !bp || !plan) return PARCAE_EINVAL;
     if (n_queries < 1 || n_intervals < 1 || n_configs < 1 || n_configs > kMaxConfigsDp) return PARCAE_EINVAL;
+    if ((int64_t)n_queries * n_intervals >= (int64_t)1 << 31 || n_queries > 65535 * 32) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const size_t lds = 2 * sizeof(float) * (size_t)n_configs;
-    parcae::dp_kernel<<<dim3((unsigned)n_queries), dim3(256), lds, st>>>(W, n_intervals, n_configs, F, bp, plan, start,
-                                                                         objective, status, PARCAE_EINFEASIBLE);
-    return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+    return launch_dp(W, n_queries, n_intervals, n_configs, nullptr, F, nullptr, bp, plan, start, objective, status, st);
 }
 
 int parcae_debug_sample(const parcae_problem* p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,

@@ -144,12 +144,19 @@ struct PlanShared {
     int* arg;            // [C]
     uint32_t* tail_int;  // [cap] suffix sums of hist_int inside each row of the current chunk
     uint32_t* tail_min;  // [cap] same for hist_min, except that slot 0 of a row keeps the raw bin 0
+    uint16_t* bp16;      // [T][C] back-pointers (0xffff = none) if they fit in LDS, else null
     int n_chunks;
 };
 
-inline size_t plan_lds_bytes(int C, int cap) { return 56 * (size_t)C + 16 + 8 * (size_t)cap; }
+constexpr int kPlanThreads = 256;
+constexpr uint16_t kNoPred16 = 0xffffu;
 
-__device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, PlanShared& sh)
+inline size_t plan_lds_bytes(int C, int cap, size_t bp16_bytes)
+{
+    return 56 * (size_t)C + 16 + 8 * (size_t)cap + ((bp16_bytes + 15) & ~(size_t)15);
+}
+
+__device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool bp_in_lds, PlanShared& sh)
 {
     size_t o = 0;
     sh.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
@@ -163,7 +170,8 @@ __device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, PlanS
     sh.arg = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
     o = (o + 15) & ~(size_t)15;
     sh.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)cap;
-    sh.tail_min = reinterpret_cast<uint32_t*>(smem + o);
+    sh.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)cap;
+    sh.bp16 = bp_in_lds ? reinterpret_cast<uint16_t*>(smem + o) : nullptr;
 }
 
 // Per-query tables and the chunking of the candidate list (the same for every step).
@@ -266,7 +274,7 @@ __global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const
 {
     extern __shared__ __align__(16) unsigned char smem[];
     PlanShared sh;
-    carve(smem, b.C, cap, sh);
+    carve(smem, b.C, cap, false, sh);
     const int q = blockIdx.x / b.T;
     const int t = blockIdx.x - q * b.T;
     load_query_tables(b, q, cap, sh);
@@ -287,10 +295,54 @@ __global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const
 
 // ------------------------------------------------------------------ dynamic program (Eq. 6)
 
+// The 256 threads of a planning block form a grid of CW target columns x RG groups of source rows
+// (CW * RG = 256, CW a power of two).  Every thread scans its rows in ascending order for its column;
+// the group results are then merged in ascending group order with a strict comparison, so the
+// smallest arg-max wins exactly as in a plain ascending scan.
+struct ColumnGrid {
+    int cw, cw_log2, rg, x, g;
+};
+
+__device__ __forceinline__ ColumnGrid column_grid(int C)
+{
+    ColumnGrid cg;
+    cg.cw_log2 = C > 32 ? 6 : (C > 16 ? 5 : 4);
+    cg.cw = 1 << cg.cw_log2;
+    cg.rg = kPlanThreads >> cg.cw_log2;
+    cg.x = (int)threadIdx.x & (cg.cw - 1);
+    cg.g = (int)threadIdx.x >> cg.cw_log2;
+    return cg;
+}
+
+// Merges the per-group partial maxima of one column pass into (F_next, arg).  Called by every thread;
+// contains two barriers.
+__device__ __forceinline__ void merge_groups(const ColumnGrid& cg, int c2, int C, float best, int arg, float* red_val,
+                                             int* red_arg, float* F_next, int* arg_next)
+{
+    red_val[threadIdx.x] = best;
+    red_arg[threadIdx.x] = arg;
+    __syncthreads();
+    if (cg.g == 0 && c2 < C) {
+        float cur = F_next[c2];
+        int a = arg_next[c2];
+        for (int gg = 0; gg < cg.rg; ++gg) {
+            const float v = red_val[gg * cg.cw + cg.x];
+            if (v > cur) {
+                cur = v;
+                a = red_arg[gg * cg.cw + cg.x];
+            }
+        }
+        F_next[c2] = cur;
+        arg_next[c2] = a;
+    }
+    __syncthreads();
+}
+
 // Final arg-max and walk back along the back-pointers; thread 0 of the block only.
+// bp16 (LDS, 0xffff = none) is used when present, else the back-pointers in memory.
 __device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_last, const int32_t* bp_q,
-                                            int32_t* plan, int32_t* start, float* objective, int32_t* status,
-                                            bool inputs_valid, int einval, int einfeasible)
+                                            const uint16_t* bp16, int32_t* plan, int32_t* start, float* objective,
+                                            int32_t* status, bool inputs_valid, int einval, int einfeasible)
 {
     float top = kNegInf;
     int last = -1;
@@ -307,33 +359,44 @@ __device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_
         st = einfeasible;
     } else {
         pl[T - 1] = last;
-        for (int t = T - 1; t >= 1; --t) {
-            last = bp_q[(int64_t)t * C + last];
-            pl[t - 1] = last;
+        for (int t = T - 1; t >= 0; --t) {
+            int prev;
+            if (bp16) {
+                const uint16_t v = bp16[t * C + last];
+                prev = v == kNoPred16 ? -1 : (int)v;
+            } else {
+                prev = bp_q[(int64_t)t * C + last];
+            }
+            if (prev < 0) prev = 0;  // cannot happen on a finite path; keeps the walk in bounds
+            if (t >= 1) pl[t - 1] = prev;
+            else if (start) start[q] = prev;
+            last = prev;
         }
-        if (start) start[q] = bp_q[last];
     }
     if (objective) objective[q] = top;
     if (status) status[q] = inputs_valid ? st : einval;
 }
 
 // One block per query: T dependent max-plus steps with the weights computed on the fly from the
-// histogram tails (the weights never touch HBM), then the walk back.
-__global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, int cap, const uint32_t* __restrict__ hist_int,
-                                                         const uint32_t* __restrict__ hist_min,
-                                                         const int32_t* __restrict__ valid, float* __restrict__ F,
-                                                         int32_t* __restrict__ bp, int32_t* __restrict__ plan,
-                                                         int32_t* __restrict__ start, float* __restrict__ objective,
-                                                         int32_t* __restrict__ status, int einval, int einfeasible)
+// histogram tails (the weights never touch HBM), then the walk back.  Used when there are enough
+// queries to fill the chip.
+__global__ void __launch_bounds__(kPlanThreads) plan_fused_kernel(
+    Batch b, int cap, int bp_in_lds, const uint32_t* __restrict__ hist_int, const uint32_t* __restrict__ hist_min,
+    const int32_t* __restrict__ valid, float* __restrict__ F, int32_t* __restrict__ bp, int32_t* __restrict__ plan,
+    int32_t* __restrict__ start, float* __restrict__ objective, int32_t* __restrict__ status, int einval,
+    int einfeasible)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red_val[kPlanThreads];
+    __shared__ int red_arg[kPlanThreads];
     PlanShared sh;
-    carve(smem, b.C, cap, sh);
+    carve(smem, b.C, cap, bp_in_lds != 0, sh);
     const int q = blockIdx.x;
     const int C = b.C;
+    const ColumnGrid cg = column_grid(C);
     load_query_tables(b, q, cap, sh);
     float* Fq = F ? F + (int64_t)q * (b.T + 1) * C : nullptr;
-    int32_t* bpq = bp + (int64_t)q * b.T * C;
+    int32_t* bpq = bp ? bp + (int64_t)q * b.T * C : nullptr;
     float* Fc = sh.F0;
     float* Fn = sh.F1;
     for (int c = threadIdx.x; c < C; c += blockDim.x) {
@@ -348,75 +411,249 @@ __global__ void __launch_bounds__(256) plan_fused_kernel(Batch b, int cap, const
         }
         for (int ch = 0; ch < sh.n_chunks; ++ch) {
             const int c_lo = sh.chunk_start[ch], c_hi = sh.chunk_start[ch + 1];
-            load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);
+            load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);  // barriers before and after
             const int first = sh.cfg[c_lo].off;
-            // each thread owns its columns; sources are visited in ascending order, so the strict
-            // comparison keeps the smallest arg-max
-            for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-                if (!sh.to_ok[c2]) continue;
-                float best = Fn[c2];
-                int arg = sh.arg[c2];
-                for (int c = c_lo; c < c_hi; ++c) {
-                    const float v = __fadd_rn(Fc[c], transition_weight(b, sh, first, c, c2));
-                    if (v > best) {
-                        best = v;
-                        arg = c;
+            const int rpg = (c_hi - c_lo + cg.rg - 1) / cg.rg;
+            const int r0 = c_lo + cg.g * rpg;
+            const int r1 = r0 + rpg < c_hi ? r0 + rpg : c_hi;
+            for (int base = 0; base < C; base += cg.cw) {
+                const int c2 = base + cg.x;
+                float best = kNegInf;
+                int arg = -1;
+                if (c2 < C && sh.to_ok[c2]) {
+                    for (int c = r0; c < r1; ++c) {
+                        const float v = __fadd_rn(Fc[c], transition_weight(b, sh, first, c, c2));
+                        if (v > best) {
+                            best = v;
+                            arg = c;
+                        }
                     }
                 }
-                Fn[c2] = best;
-                sh.arg[c2] = arg;
+                merge_groups(cg, c2, C, best, arg, red_val, red_arg, Fn, sh.arg);
             }
         }
         for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            bpq[(int64_t)t * C + c2] = sh.arg[c2];
+            const int a = sh.arg[c2];
+            if (bpq) bpq[(int64_t)t * C + c2] = a;
+            if (sh.bp16) sh.bp16[t * C + c2] = a < 0 ? kNoPred16 : (uint16_t)a;
             if (Fq) Fq[(int64_t)(t + 1) * C + c2] = Fn[c2];
         }
         __syncthreads();
         float* tmp = Fc; Fc = Fn; Fn = tmp;
     }
-    if (threadIdx.x == 0)
-        finish_plan(q, b.T, C, Fc, bpq, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
+    if (threadIdx.x == 0) {
+        finish_plan(q, b.T, C, Fc, bpq, sh.bp16, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
                     einfeasible);
+    }
+}
+
+// Scans source rows [r0, r1) of column c2 of a weight tile held in memory, eight loads in flight at a
+// time (a one-load-at-a-time loop is bound by memory latency).  f = F of the previous step (LDS).
+__device__ __forceinline__ void scan_rows_memory(const float* __restrict__ Wt, int C, int c2, int r0, int r1,
+                                                 const float* f, float& best, int& arg)
+{
+    for (int c = r0; c < r1; c += 8) {
+        float w[8];
+        static_for<8>([&](auto i) {
+            const int row = c + i.value;
+            w[i.value] = row < r1 ? Wt[(int64_t)row * C + c2] : kNegInf;
+        });
+        static_for<8>([&](auto i) {
+            const int row = c + i.value;
+            if (row < r1) {
+                const float v = __fadd_rn(f[row], w[i.value]);
+                if (v > best) {
+                    best = v;
+                    arg = row;
+                }
+            }
+        });
+    }
+}
+
+constexpr int kStagedMaxConfigs = 64;                                               // tiles up to 64 x 64 are staged in LDS
+constexpr int kStageRegs = kStagedMaxConfigs * kStagedMaxConfigs / kPlanThreads;    // floats per thread per tile
+
+inline size_t dp_lds_bytes(int C, size_t bp16_bytes)
+{
+    const size_t tiles = C <= kStagedMaxConfigs ? 2 * sizeof(float) * (size_t)C * (size_t)C : 0;
+    return 12 * (size_t)C + ((bp16_bytes + 15) & ~(size_t)15) + 16 + tiles;
 }
 
 // One block per query on weights held in memory: W[q][t][c][c'], c' contiguous.
-__global__ void __launch_bounds__(256) dp_kernel(const float* __restrict__ W, int T, int C, float* __restrict__ F,
-                                                 int32_t* __restrict__ bp, int32_t* __restrict__ plan,
-                                                 int32_t* __restrict__ start, float* __restrict__ objective,
-                                                 int32_t* __restrict__ status, int einfeasible)
+// Tiles of up to 64 x 64 candidates travel memory -> registers -> LDS two steps ahead of the step that
+// consumes them, so the T dependent steps never wait for memory; larger tiles are read in place.
+__global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restrict__ W, int T, int C, int bp_in_lds,
+                                                          const int32_t* __restrict__ valid, float* __restrict__ F,
+                                                          int32_t* __restrict__ bp, int32_t* __restrict__ plan,
+                                                          int32_t* __restrict__ start, float* __restrict__ objective,
+                                                          int32_t* __restrict__ status, int einval, int einfeasible)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red_val[kPlanThreads];
+    __shared__ int red_arg[kPlanThreads];
     float* Fc = reinterpret_cast<float*>(smem);
     float* Fn = Fc + C;
+    int* argn = reinterpret_cast<int*>(Fn + C);
+    size_t o = 12 * (size_t)C;
+    uint16_t* bp16 = bp_in_lds ? reinterpret_cast<uint16_t*>(smem + o) : nullptr;
+    if (bp_in_lds) o += (sizeof(uint16_t) * (size_t)T * (size_t)C + 15) & ~(size_t)15;
+    o = (o + 15) & ~(size_t)15;
+    float* tile0 = reinterpret_cast<float*>(smem + o);
+    const bool staged = C <= kStagedMaxConfigs;
+    const int n_w = C * C;
+    float* tile1 = tile0 + n_w;
+
     const int q = blockIdx.x;
+    const ColumnGrid cg = column_grid(C);
     float* Fq = F ? F + (int64_t)q * (T + 1) * C : nullptr;
-    int32_t* bpq = bp + (int64_t)q * T * C;
+    int32_t* bpq = bp ? bp + (int64_t)q * T * C : nullptr;
     const float* Wq = W + (int64_t)q * T * C * C;
     for (int c = threadIdx.x; c < C; c += blockDim.x) {
         Fc[c] = 0.0f;
         if (Fq) Fq[c] = 0.0f;
     }
-    __syncthreads();
-    for (int t = 0; t < T; ++t) {
-        const float* Wt = Wq + (int64_t)t * C * C;
+    const int rpg = (C + cg.rg - 1) / cg.rg;
+    const int r0 = cg.g * rpg;
+    const int r1 = r0 + rpg < C ? r0 + rpg : C;
+
+    float ra[kStageRegs], rb[kStageRegs];
+    auto fetch = [&](int t, float (&r)[kStageRegs]) __attribute__((always_inline)) {
+        const float* src = Wq + (int64_t)t * n_w;
+        static_for<kStageRegs>([&](auto i) {
+            const int idx = (int)threadIdx.x + kPlanThreads * i.value;
+            r[i.value] = (t < T && idx < n_w) ? src[idx] : 0.0f;
+        });
+    };
+    auto stash = [&](const float (&r)[kStageRegs], float* tile) __attribute__((always_inline)) {
+        static_for<kStageRegs>([&](auto i) {
+            const int idx = (int)threadIdx.x + kPlanThreads * i.value;
+            if (idx < n_w) tile[idx] = r[i.value];
+        });
+    };
+    // one step: tile (LDS) or Wt (memory) -> Fn, argn, back-pointers
+    auto step = [&](int t, const float* tile) __attribute__((always_inline)) {
+        const float* Wt = Wq + (int64_t)t * n_w;
         for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            float best = kNegInf;
-            int arg = -1;
-            for (int c = 0; c < C; ++c) {
-                const float v = __fadd_rn(Fc[c], Wt[(int64_t)c * C + c2]);
-                if (v > best) {
-                    best = v;
-                    arg = c;
-                }
-            }
-            Fn[c2] = best;
-            bpq[(int64_t)t * C + c2] = arg;
-            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = best;
+            Fn[c2] = kNegInf;
+            argn[c2] = -1;
         }
         __syncthreads();
-        float* tmp = Fc; Fc = Fn; Fn = tmp;
+        for (int base = 0; base < C; base += cg.cw) {
+            const int c2 = base + cg.x;
+            float best = kNegInf;
+            int arg = -1;
+            if (c2 < C) {
+                if (tile) {
+                    for (int c = r0; c < r1; ++c) {
+                        const float v = __fadd_rn(Fc[c], tile[c * C + c2]);
+                        if (v > best) {
+                            best = v;
+                            arg = c;
+                        }
+                    }
+                } else {
+                    scan_rows_memory(Wt, C, c2, r0, r1, Fc, best, arg);
+                }
+            }
+            merge_groups(cg, c2, C, best, arg, red_val, red_arg, Fn, argn);
+        }
+        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
+            const int a = argn[c2];
+            if (bpq) bpq[(int64_t)t * C + c2] = a;
+            if (bp16) bp16[t * C + c2] = a < 0 ? kNoPred16 : (uint16_t)a;
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = Fn[c2];
+        }
+    };
+
+    if (staged) {
+        fetch(0, ra);
+        fetch(1, rb);
+        stash(ra, tile0);
+        __syncthreads();
+        for (int t = 0; t < T; t += 2) {
+            // even step: tile0 holds W_t, rb holds W_{t+1}; ra is free for W_{t+2}
+            fetch(t + 2, ra);
+            step(t, tile0);
+            stash(rb, tile1);
+            __syncthreads();
+            { float* tmp = Fc; Fc = Fn; Fn = tmp; }
+            if (t + 1 >= T) break;
+            // odd step: tile1 holds W_{t+1}, ra holds W_{t+2}; rb is free for W_{t+3}
+            fetch(t + 3, rb);
+            step(t + 1, tile1);
+            stash(ra, tile0);
+            __syncthreads();
+            { float* tmp = Fc; Fc = Fn; Fn = tmp; }
+        }
+    } else {
+        for (int t = 0; t < T; ++t) {
+            step(t, nullptr);
+            __syncthreads();
+            float* tmp = Fc; Fc = Fn; Fn = tmp;
+        }
     }
-    if (threadIdx.x == 0) finish_plan(q, T, C, Fc, bpq, plan, start, objective, status, true, 0, einfeasible);
+    if (threadIdx.x == 0)
+        finish_plan(q, T, C, Fc, bpq, bp16, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
+                    einfeasible);
+}
+
+// One max-plus step for 16 target columns of one query (grid: column blocks x queries), weights and F in
+// memory.  Launched once per step when a few queries have many candidates, so that a step is spread
+// over many compute units.  F is [nq][T + 1][C] and must be present; bp is [nq][T][C].
+constexpr int kStepCols = 16;
+__global__ void __launch_bounds__(kPlanThreads) dp_step_kernel(const float* __restrict__ W, int T, int C, int t,
+                                                               float* __restrict__ F, int32_t* __restrict__ bp)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red_val[kPlanThreads];
+    __shared__ int red_arg[kPlanThreads];
+    float* f_prev = reinterpret_cast<float*>(smem);  // [C]
+    constexpr int kGroups = kPlanThreads / kStepCols;
+    const int q = blockIdx.y;
+    const int x = (int)threadIdx.x & (kStepCols - 1);
+    const int g = (int)threadIdx.x / kStepCols;
+    const int c2 = (int)blockIdx.x * kStepCols + x;
+    float* Fq = F + (int64_t)q * (T + 1) * C;
+    const float* Wt = W + ((int64_t)q * T + t) * C * C;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) f_prev[c] = (t == 0) ? 0.0f : Fq[(int64_t)t * C + c];
+    if (t == 0 && g == 0 && c2 < C) Fq[c2] = 0.0f;  // F_0 for the caller
+    __syncthreads();
+    const int rpg = (C + kGroups - 1) / kGroups;
+    const int r0 = g * rpg;
+    const int r1 = r0 + rpg < C ? r0 + rpg : C;
+    float best = kNegInf;
+    int arg = -1;
+    if (c2 < C) scan_rows_memory(Wt, C, c2, r0, r1, f_prev, best, arg);
+    red_val[threadIdx.x] = best;
+    red_arg[threadIdx.x] = arg;
+    __syncthreads();
+    if (g == 0 && c2 < C) {
+        float cur = kNegInf;
+        int a = -1;
+        for (int gg = 0; gg < kGroups; ++gg) {
+            const float v = red_val[gg * kStepCols + x];
+            if (v > cur) {
+                cur = v;
+                a = red_arg[gg * kStepCols + x];
+            }
+        }
+        Fq[(int64_t)(t + 1) * C + c2] = cur;
+        bp[((int64_t)q * T + t) * C + c2] = a;
+    }
+}
+
+// Final arg-max and walk back for the stepwise path (one thread per query does the walk).
+__global__ void __launch_bounds__(64) dp_finish_kernel(int nq, int T, int C, const int32_t* __restrict__ valid,
+                                                       const float* __restrict__ F, const int32_t* __restrict__ bp,
+                                                       int32_t* __restrict__ plan, int32_t* __restrict__ start,
+                                                       float* __restrict__ objective, int32_t* __restrict__ status,
+                                                       int einval, int einfeasible)
+{
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    finish_plan(q, T, C, F + ((int64_t)q * (T + 1) + T) * C, bp + (int64_t)q * T * C, nullptr, plan, start, objective,
+                status, valid ? valid[q] != 0 : true, einval, einfeasible);
 }
 
 }  // namespace parcae

@@ -150,6 +150,48 @@ def test_batched_queries_parity(pk):
         _check_query_against_oracle(pk, b, q, ev, pl, 1000, check_W=W)
 
 
+def test_many_queries_take_the_per_query_planning_kernel(pk):
+    """Forty queries: enough for the one-block-per-query planner (weights formed on the fly in LDS)."""
+    b = pi.workload("sweep", n_queries=40, n_scenarios=300)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    for q in (0, 7, 39):
+        _check_query_against_oracle(pk, b, q, ev, pl, 300)
+    # the same plans from weights in memory, with and without the optional outputs
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    pl2 = pk.parcae_dp_plan(W)
+    lean = pk.alloc_plan_out(p, full=False)
+    lean.bp = pl2.bp.clone()
+    pk.parcae_dp_plan(W, lean)
+    _sync()
+    for f in ("F", "bp", "plan", "start", "objective", "status"):
+        assert np.array_equal(_np(getattr(pl2, f)), _np(getattr(pl, f))), f
+    assert np.array_equal(_np(lean.plan), _np(pl.plan)) and np.array_equal(_np(lean.objective), _np(pl.objective))
+
+
+def test_dp_on_stored_weights_all_kernel_variants(pk):
+    """Weights in memory: tiles staged in LDS (C <= 64), read in place (one block), and one launch per step."""
+    for name, dense, S in (("small", False, 200), ("medium", True, 100), ("large", True, 64)):
+        b = pi.workload(name, dense=dense, n_scenarios=S)
+        p = pk.upload(b)
+        ev = pk.parcae_liveput_eval(p)
+        W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+        _sync()
+        r = oracle.run_query(b, 0, n_scenarios=S, n_threads=8)
+        assert np.array_equal(_np(W[0]), r.W_f)
+        full = pk.parcae_dp_plan(W)                       # F wanted: stepwise launches when C is large
+        lean = pk.alloc_plan_out(p, full=False)           # no F: one block per query
+        lean.bp = full.bp.clone().zero_()
+        pk.parcae_dp_plan(W, lean)
+        _sync()
+        assert np.array_equal(_np(full.F[0]), r.plan.F) and np.array_equal(_np(full.bp[0]), r.plan.bp)
+        assert np.array_equal(_np(lean.bp[0]), r.plan.bp)
+        for out in (full, lean):
+            assert np.array_equal(_np(out.plan[0]), r.plan.plan) and int(out.start[0]) == r.plan.start
+            assert float(out.objective[0]) == r.plan.objective
+
+
 def test_multi_chunk_and_ragged_scenario_counts(pk):
     """Scenario counts around the block chunking (2048 per block) and the wave size."""
     base = pi.workload("small")
