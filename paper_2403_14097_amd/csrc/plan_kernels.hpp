@@ -447,8 +447,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_fused_kernel(
     }
 }
 
-// Scans source rows [r0, r1) of column c2 of a weight tile held in memory, eight loads in flight at a
-// time (a one-load-at-a-time loop is bound by memory latency).  f = F of the previous step (LDS).
+// Scans source rows [r0, r1) of column c2 of a weight tile (in memory or in LDS), eight loads in flight
+// at a time (a one-load-at-a-time loop is bound by latency).  f = F of the previous step (LDS).
 __device__ __forceinline__ void scan_rows_memory(const float* __restrict__ Wt, int C, int c2, int r0, int r1,
                                                  const float* f, float& best, int& arg)
 {
@@ -476,7 +476,7 @@ constexpr int kStageRegs = kStagedMaxConfigs * kStagedMaxConfigs / kPlanThreads;
 
 inline size_t dp_lds_bytes(int C, size_t bp16_bytes)
 {
-    const size_t tiles = C <= kStagedMaxConfigs ? 2 * sizeof(float) * (size_t)C * (size_t)C : 0;
+    const size_t tiles = C <= kStagedMaxConfigs ? 2 * sizeof(float) * kStageRegs * kPlanThreads : 0;
     return 12 * (size_t)C + ((bp16_bytes + 15) & ~(size_t)15) + 16 + tiles;
 }
 
@@ -502,7 +502,7 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
     float* tile0 = reinterpret_cast<float*>(smem + o);
     const bool staged = C <= kStagedMaxConfigs;
     const int n_w = C * C;
-    float* tile1 = tile0 + n_w;
+    float* tile1 = tile0 + kStageRegs * kPlanThreads;
 
     const int q = blockIdx.x;
     const ColumnGrid cg = column_grid(C);
@@ -518,18 +518,18 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
     const int r1 = r0 + rpg < C ? r0 + rpg : C;
 
     float ra[kStageRegs], rb[kStageRegs];
+    // Loads and LDS writes are unconditional (indices clamped into the tile, LDS tiles padded to a full
+    // register set): with no branches around them the compiler can wait for exactly the older tile and
+    // leave the newer one in flight.
     auto fetch = [&](int t, float (&r)[kStageRegs]) __attribute__((always_inline)) {
-        const float* src = Wq + (int64_t)t * n_w;
+        const float* src = Wq + (int64_t)(t < T ? t : T - 1) * n_w;
         static_for<kStageRegs>([&](auto i) {
             const int idx = (int)threadIdx.x + kPlanThreads * i.value;
-            r[i.value] = (t < T && idx < n_w) ? src[idx] : 0.0f;
+            r[i.value] = src[idx < n_w ? idx : n_w - 1];
         });
     };
     auto stash = [&](const float (&r)[kStageRegs], float* tile) __attribute__((always_inline)) {
-        static_for<kStageRegs>([&](auto i) {
-            const int idx = (int)threadIdx.x + kPlanThreads * i.value;
-            if (idx < n_w) tile[idx] = r[i.value];
-        });
+        static_for<kStageRegs>([&](auto i) { tile[(int)threadIdx.x + kPlanThreads * i.value] = r[i.value]; });
     };
     // one step: tile (LDS) or Wt (memory) -> Fn, argn, back-pointers
     auto step = [&](int t, const float* tile) __attribute__((always_inline)) {
@@ -544,17 +544,8 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
             float best = kNegInf;
             int arg = -1;
             if (c2 < C) {
-                if (tile) {
-                    for (int c = r0; c < r1; ++c) {
-                        const float v = __fadd_rn(Fc[c], tile[c * C + c2]);
-                        if (v > best) {
-                            best = v;
-                            arg = c;
-                        }
-                    }
-                } else {
-                    scan_rows_memory(Wt, C, c2, r0, r1, Fc, best, arg);
-                }
+                if (tile) scan_rows_memory(tile, C, c2, r0, r1, Fc, best, arg);
+                else scan_rows_memory(Wt, C, c2, r0, r1, Fc, best, arg);
             }
             merge_groups(cg, c2, C, best, arg, red_val, red_arg, Fn, argn);
         }
