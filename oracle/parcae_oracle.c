@@ -125,25 +125,32 @@ void orc_reduce(int D, int P, const uint8_t *preempted, int *n_int, int *d_min, 
     *d_min = least;
 }
 
-/* Pool size and preempted count of unit (t, c): the D*P used instances lose
- * max(0, D*P - a_t) of them when availability drops to a_t (section 4.2). */
-static void unit_pool(int D, int P, int a_next, int *M, int *k)
+/* Pool size and preempted count of unit (t, c).
+ * Used-instance pool (a_prev < 0): the D*P used instances lose max(0, D*P - a_next) of them when
+ * availability drops to a_next (section 4.2).
+ * Whole-cluster pool (a_prev >= 0, section 6.3: N- preemptions among all N_i available instances, idle
+ * ones included): the pool is the a_prev available instances, of which the first D*P run the grid and the
+ * rest are idle, and it loses N- = max(0, a_prev - a_next).  A configuration that does not even fit
+ * a_prev (never a source in the dynamic program) falls back to a pool of its own D*P instances. */
+static void unit_pool(int D, int P, int a_prev, int a_next, int *M, int *k)
 {
     *M = D * P;
+    if (a_prev > *M) *M = a_prev;
     *k = (*M - a_next > 0) ? (*M - a_next) : 0;
 }
 
 /*
  * Debug view of scenarios [s0, s0 + ns) of one unit: packed masks
- * (bit j of word j/32 = instance j preempted, 8 words per scenario) and the
- * two per-scenario integers.
+ * (bit j of word j/32 = instance j of the pool preempted, 8 words per scenario;
+ * instances D*P and up are idle ones) and the two per-scenario integers.
+ * a_prev < 0 selects the used-instance pool.
  */
-void orc_debug_sample(int D, int P, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_debug_sample(int D, int P, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
                       uint32_t s0, uint32_t ns, uint32_t *masks, int32_t *n_int, int32_t *d_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
     int M, k;
-    unit_pool(D, P, a_next, &M, &k);
+    unit_pool(D, P, a_prev, a_next, &M, &k);
     for (uint32_t x = 0; x < ns; ++x) {
         int ni, dm;
         orc_sample_preempted(M, k, seed, stream_id, unit, s0 + x, pre);
@@ -158,14 +165,15 @@ void orc_debug_sample(int D, int P, int a_next, uint64_t seed, uint32_t stream_i
 
 /*
  * Histograms of a single unit over scenarios [s_begin, s_end): bins [D + 1] each, overwritten.
+ * a_prev < 0 selects the used-instance pool.
  * unit = t * C + c is the value that enters the random-word counter.
  */
-void orc_eval_unit(int D, int P, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_eval_unit(int D, int P, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
                    uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
     int M, k;
-    unit_pool(D, P, a_next, &M, &k);
+    unit_pool(D, P, a_prev, a_next, &M, &k);
     for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; }
     for (uint32_t s = s_begin; s < s_end; ++s) {
         int ni, dm;
@@ -181,11 +189,12 @@ void orc_eval_unit(int D, int P, int a_next, uint64_t seed, uint32_t stream_id, 
  *   hist_int[t][off[c] + n_int] += 1, hist_min[t][off[c] + d_min] += 1.
  * configs = (D, P) pairs; avail[0] = availability now, avail[1 + t] = a_t.
  * Buffers are [T][off[C]] and are overwritten.  n_threads > 1 splits the
- * independent units over OpenMP threads (no effect on the integers).
+ * independent units over OpenMP threads (no effect on the integers).  pool_all != 0
+ * draws the preemptions among all avail[t] instances instead of the used ones.
  */
 void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                    uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
-                   uint32_t *hist_int, uint32_t *hist_min, int n_threads)
+                   uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all)
 {
     const int L = thr_off[C];
     memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
@@ -199,7 +208,7 @@ void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off,
         int D = configs[2 * c], P = configs[2 * c + 1];
         int M, k;
         uint8_t pre[ORC_MAX_INSTANCES];
-        unit_pool(D, P, avail[t + 1], &M, &k);
+        unit_pool(D, P, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
         uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
         uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
         for (uint32_t s = s_begin; s < s_end; ++s) {
@@ -247,7 +256,7 @@ static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int widt
  * and in the fixed float order (*_f).
  */
 void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
-                  const float *thr, const float *cost, float tau, uint32_t S,
+                  const float *thr, const float *cost, float tau, uint32_t S, int pool_all,
                   const uint32_t *hist_int, const uint32_t *hist_min,
                   double *liveput_d, double *teff_d, double *gain_d,
                   float *liveput_f, float *teff_f, float *gain_f)
@@ -257,7 +266,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
         for (int c = 0; c < C; ++c) {
             int D = configs[2 * c], P = configs[2 * c + 1];
             int M, k;
-            unit_pool(D, P, avail[t + 1], &M, &k);
+            unit_pool(D, P, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
             const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
             const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
             const float *th = thr + thr_off[c];

@@ -97,3 +97,16 @@ def brute_force_plans(W):
         elif tot == best:
             arg.append(seq)
     return best, arg
+
+
+def exact_histograms_pool(D, P, pool, k):
+    """Exact counts of n_int and d_min when k of `pool` instances are preempted and only the first D*P run the grid."""
+    hi = np.zeros(D + 1, dtype=np.int64)
+    hm = np.zeros(D + 1, dtype=np.int64)
+    n = 0
+    for _, v in all_subsets(pool, k):
+        a, b = survivors(D, P, v[: D * P])
+        hi[a] += 1
+        hm[b] += 1
+        n += 1
+    return hi, hm, n
