@@ -11,7 +11,8 @@
  * ------------------------------------------------------------------------
  * Conventions common to all calls
  * ------------------------------------------------------------------------
- * Memory.  A pointer is marked HOST or DEVICE.  The caller owns every buffer;
+ * Memory.  A pointer is marked HOST or DEVICE.  The caller owns every buffer
+ * (calls that may overlap in time need separate workspaces);
  * the library allocates nothing, frees nothing and keeps no state between
  * calls.  DEVICE buffers must be ordinary device allocations of the current
  * HIP device and must not overlap each other.  HOST data is read before the
@@ -71,6 +72,10 @@ extern "C" {
 #define PARCAE_MAX_SCENARIOS 16777216   /* S limit: counts stay exact in float      */
 #define PARCAE_MASK_WORDS 8
 
+/* parcae_problem.flags */
+#define PARCAE_POOL_USED 0u /* preemptions fall on the D * P instances the configuration uses (default) */
+#define PARCAE_POOL_ALL 1u  /* preemptions fall on any of the available instances, idle ones included  */
+
 #define PARCAE_OK 0
 #define PARCAE_EINVAL (-1)       /* bad argument or bad input data                       */
 #define PARCAE_EWORKSPACE (-2)   /* workspace NULL, misaligned (256 B) or too small      */
@@ -90,7 +95,7 @@ typedef struct parcae_problem {
     int32_t n_scenarios; /* S, 1..PARCAE_MAX_SCENARIOS Monte-Carlo scenarios per (t, c) */
     int32_t p_min;       /* smallest pipeline depth that fits device memory             */
     float interval_sec;  /* interval length in seconds (the paper's T), > 0, finite     */
-    uint32_t flags;      /* must be 0                                                   */
+    uint32_t flags;      /* PARCAE_POOL_USED or PARCAE_POOL_ALL                         */
     const parcae_config *configs; /* HOST   [C]                                         */
     const int32_t *avail;         /* DEVICE [nq][T + 1]                                 */
     const float *thr;             /* DEVICE [nq][L]                                     */
@@ -109,10 +114,15 @@ typedef struct parcae_problem {
  * What is computed (the definitions every entry point refers to)
  * ------------------------------------------------------------------------
  * Unit (q, t, c): configuration c, running in interval t - 1 (now, for
- * t = 0), meets the boundary into interval t.  Its M = D * P instances lose
- * k = max(0, M - avail[q][1 + t]) of them (section 4.2: N- = max(0, N_{i-1} -
- * N_i), here for the instances the job uses).  Logical instance j = d * P + s
- * is stage s of pipeline d.
+ * t = 0), meets the boundary into interval t.  A pool of M instances loses k
+ * of them; logical instance j = d * P + s < D * P is stage s of pipeline d,
+ * instances D * P .. M - 1 are idle.
+ *   PARCAE_POOL_USED: M = D * P, k = max(0, M - avail[q][1 + t]) (section 4.2:
+ *     N- = max(0, N_{i-1} - N_i), here for the instances the job uses).
+ *   PARCAE_POOL_ALL:  M = max(avail[q][t], D * P), k = max(0, M - avail[q][1 + t])
+ *     (section 6.3: the N- preemptions are drawn among all N_i available
+ *     instances; a configuration that does not fit avail[q][t] is never a source
+ *     in the plan and keeps the pool of its own instances).
  *
  * Scenario s of a unit (section 6.3, section 5.1: every instance equally
  * likely) is a k-subset of [0, M) drawn as follows.  Random word i is output
@@ -149,6 +159,7 @@ typedef struct parcae_problem {
  *   liveput[q][0][t][c] = (sum_j hist_int[j] * thr[c][j]) / S   no migration
  *   liveput[q][1][t][c] = (sum_j hist_min[j] * thr[c][j]) / S   intra-stage only
  *   liveput[q][2][t][c] = thr[c][D*], D* = min(D, (M - k) / P)  all live migrations
+ *     (M - k survivors of the pool: idle instances may fill in at inter-stage cost)
  *   teff[q][t][c] = teff(D*, cost[q][c]);  gain[q][t][c] = thr[c][D*] * teff[q][t][c]
  *
  * Transition weight (Eq. 4 with the rule of section 6.2), c -> c' at step t:
@@ -232,7 +243,7 @@ int parcae_dp_plan(const float *W, int32_t n_queries, int32_t n_intervals, int32
 /*
  * Scenarios [s0, s0 + ns) of unit (q, t, c), one by one (section 6.3).
  *   masks  DEVICE out [ns][8] uint32: bit (j mod 32) of word (j / 32) is set
- *          iff logical instance j is preempted
+ *          iff instance j of the pool is preempted
  *   n_int, d_min  DEVICE out [ns] int32
  */
 int parcae_debug_sample(const parcae_problem *p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,

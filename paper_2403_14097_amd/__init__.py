@@ -23,6 +23,8 @@ PARCAE_EWORKSPACE = -2
 PARCAE_EHIP = -3
 PARCAE_EINFEASIBLE = -4
 PARCAE_MAX_INSTANCES = 256
+PARCAE_POOL_USED = 0
+PARCAE_POOL_ALL = 1
 
 EXPORTED_SYMBOLS = (
     "parcae_workspace_bytes", "parcae_hist_len", "parcae_liveput_eval", "parcae_plan_from_hist",
@@ -126,6 +128,7 @@ class Problem:
     seed: "object"                # int64 view of uint64 [nq] device
     stream_id: "object" = None    # int32 view of uint32 [nq] device, or None
     cur_config: "object" = None   # int32 [nq] device, or None
+    flags: int = 0                # PARCAE_POOL_USED or PARCAE_POOL_ALL
     event_before_sampling: Optional[int] = None   # raw hipEvent_t handles, recorded around the sampling kernel
     event_after_sampling: Optional[int] = None
     _cfg_arr: object = field(default=None, repr=False)
@@ -151,7 +154,7 @@ class Problem:
             self._cfg_arr = arr
         return parcae_problem(
             self.n_queries, self.n_instances, self.n_intervals, self.n_configs, self.n_scenarios, self.p_min,
-            self.interval_sec, 0, ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
+            self.interval_sec, int(self.flags), ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
             _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling)
 

@@ -22,6 +22,7 @@ struct CfgRec {
 // Everything a kernel needs to know about the batch; passed by value.
 struct Batch {
     int32_t nq, N, T, C, S, p_min, L;
+    int32_t pool_all;           // 0: preemptions fall on the used instances, 1: on all available ones
     float tau;
     const CfgRec* cfg;          // [C]
     const int32_t* avail;       // [nq][T+1]
@@ -34,24 +35,34 @@ struct Batch {
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-// Instances used (M) and preempted (k) when configuration (D, P) meets availability a (section 4.2).
-__device__ __forceinline__ void unit_pool(int D, int P, int a, int N, int& M, int& k)
+// Pool (M instances, the first D * P of them run the grid) and preempted count k of unit (q, t, c).
+// Used-instance pool: M = D * P, k = max(0, M - a_t) (section 4.2).  Whole-cluster pool (section 6.3: the
+// N- preemptions fall on any of the N_i available instances, idle ones included): M = max(a_{t-1}, D * P),
+// k = max(0, M - a_t); a configuration that does not fit a_{t-1} keeps the pool of its own instances.
+__device__ __forceinline__ void unit_pool(const Batch& b, int q, int t, int D, int P, int& M, int& k)
 {
+    const int32_t* av = b.avail + (int64_t)q * (b.T + 1) + t;
     M = D * P;
-    a = clampi(a, 0, N);
-    k = M - a;
+    if (b.pool_all) {
+        const int a_prev = clampi(av[0], 0, b.N);
+        M = a_prev > M ? a_prev : M;
+    }
+    k = M - clampi(av[1], 0, b.N);
     k = k < 0 ? 0 : k;
 }
 
 // Units whose scenarios all fall into one histogram bin (the same bin in both histograms), so that no
-// sampling is needed: nothing preempted (bin D), everything preempted (bin 0), a single stage (every
-// preemption removes exactly one pipeline: bin D - k) or a single pipeline that is hit (bin 0).
+// sampling is needed: nothing preempted (bin D), everything preempted (bin 0) and, when the pool is the
+// grid itself, a single stage (every preemption removes exactly one pipeline: bin D - k) or a single
+// pipeline that is hit (bin 0).
 __device__ __forceinline__ bool unit_closed_form(int D, int P, int M, int k, int& bin)
 {
     if (k == 0) { bin = D; return true; }
     if (k == M) { bin = 0; return true; }
-    if (P == 1) { bin = D - k; return true; }
-    if (D == 1) { bin = 0; return true; }
+    if (M == D * P) {
+        if (P == 1) { bin = D - k; return true; }
+        if (D == 1) { bin = 0; return true; }
+    }
     return false;
 }
 

@@ -95,6 +95,15 @@ struct Mask {
         const uint32_t bit = 1u << (b & 31u);
         static_for<NW>([&](auto i) { w[i.value] |= (sel == (uint32_t)i.value) ? bit : 0u; });
     }
+    // drop bits at and above M
+    __device__ __forceinline__ void keep_below(int M)
+    {
+        static_for<NW>([&](auto i) {
+            constexpr int lo = i.value * 32;
+            const uint32_t valid = (M >= lo + 32) ? 0xffffffffu : (M <= lo ? 0u : ((1u << (M - lo)) - 1u));
+            w[i.value] &= valid;
+        });
+    }
     // keep bits [0, M) of the complement
     __device__ __forceinline__ void complement(int M)
     {
@@ -399,7 +408,7 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, WorkQueue wq, u
         const CfgRec cr = b.cfg[lo];
         const int j = pos - cr.off;
         int M, k;
-        unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+        unit_pool(b, q, t, cr.D, cr.P, M, k);
         int bin;
         const uint32_t v = (unit_closed_form(cr.D, cr.P, M, k, bin) && j == bin) ? (uint32_t)b.S : 0u;
         hist_int[e] = v;
@@ -424,7 +433,7 @@ __global__ void __launch_bounds__(kBuildThreads) build_work_kernel(Batch b, Work
         const int t = tc / b.C;
         const CfgRec cr = b.cfg[tc - t * b.C];
         int M, k, bin;
-        unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+        unit_pool(b, q, t, cr.D, cr.P, M, k);
         need = !unit_closed_form(cr.D, cr.P, M, k, bin);
     }
     const unsigned long long votes = __ballot(need);
@@ -467,6 +476,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int M, int k, u
         int n_int, d_min;
         Mask<NW> mask;
         draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
+        if (M > cr.D * cr.P) mask.keep_below(cr.D * cr.P);  // idle instances of the pool are not on the grid
         reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int, true);
         hist_add(bins_min, d_min, true);
@@ -528,7 +538,7 @@ __global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, WorkQu
         const int c = tc - t * b.C;
         const CfgRec cr = b.cfg[c];
         int M, k;
-        unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+        unit_pool(b, q, t, cr.D, cr.P, M, k);
 
         const int nb = cr.D + 1;
         uint32_t* bins_int = bins;
@@ -575,11 +585,12 @@ __device__ __forceinline__ void debug_one(const CfgRec cr, uint32_t* lds_col, in
 {
     Mask<NW> mask;
     draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
-    reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
     static_for<8>([&](auto i) {
         if constexpr (i.value < NW) mask_out[i.value] = mask.w[i.value];
         else mask_out[i.value] = 0u;
     });
+    if (M > cr.D * cr.P) mask.keep_below(cr.D * cr.P);
+    reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
 }
 
 // Scenarios one by one, for inspection: masks [ns][8], n_int [ns], d_min [ns].
@@ -593,7 +604,7 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     if (x >= ns) return;
     const CfgRec cr = b.cfg[c];
     int M, k;
-    unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+    unit_pool(b, q, t, cr.D, cr.P, M, k);
     const uint64_t seed = b.seed[q];
     const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
     const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;

@@ -40,7 +40,7 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
     if (p->n_queries < 1 || p->n_intervals < 1 || p->n_configs < 1) return PARCAE_EINVAL;
     if (p->n_instances < 1 || p->n_instances > PARCAE_MAX_INSTANCES) return PARCAE_EINVAL;
     if (p->n_scenarios < 1 || p->n_scenarios > PARCAE_MAX_SCENARIOS) return PARCAE_EINVAL;
-    if (p->flags != 0u) return PARCAE_EINVAL;
+    if ((p->flags & ~(uint32_t)PARCAE_POOL_ALL) != 0u) return PARCAE_EINVAL;
     if (!(p->interval_sec > 0.0f) || !std::isfinite(p->interval_sec)) return PARCAE_EINVAL;
     if ((int64_t)p->n_configs * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     int64_t L = 0;
@@ -96,6 +96,7 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     Batch b;
     b.nq = p->n_queries; b.N = p->n_instances; b.T = p->n_intervals; b.C = p->n_configs; b.S = p->n_scenarios;
     b.p_min = p->p_min; b.L = (int32_t)lay.L; b.tau = p->interval_sec;
+    b.pool_all = (p->flags & PARCAE_POOL_ALL) ? 1 : 0;
     b.cfg = reinterpret_cast<const CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
     b.cur_config = p->cur_config;

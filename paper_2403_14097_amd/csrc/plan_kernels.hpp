@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
     const int q = (int)(qt / b.T);
     const CfgRec cr = b.cfg[c];
     int M, k;
-    unit_pool(cr.D, cr.P, b.avail[(int64_t)q * (b.T + 1) + t + 1], b.N, M, k);
+    unit_pool(b, q, t, cr.D, cr.P, M, k);
     const uint32_t* hi = hist_int + qt * b.L + cr.off;
     const uint32_t* hm = hist_min + qt * b.L + cr.off;
     const float* th = b.thr + (int64_t)q * b.L + cr.off;

@@ -277,6 +277,51 @@ def test_full_size_sweep_sampled(pk):
         _check_query_against_oracle(pk, b, q, ev, pl, b.n_scenarios)
 
 
+# ------------------------------------------------------------------ whole-cluster preemption pool
+
+def test_pool_all_scenarios_one_by_one(pk):
+    """Preemptions drawn among all available instances: masks cover the pool, the grid is its first D * P bits."""
+    cases = [  # D, P, a_prev, a_next
+        (3, 4, 20, 13), (2, 8, 30, 25), (4, 8, 64, 40), (2, 16, 64, 10), (1, 32, 50, 33), (16, 4, 100, 70),
+        (8, 16, 200, 120), (2, 64, 256, 130), (32, 1, 40, 22), (1, 8, 20, 9), (5, 7, 60, 31), (4, 4, 16, 9), (4, 4, 12, 9),
+        (3, 32, 256, 1), (6, 2, 12, 12), (6, 2, 40, 0),
+    ]
+    configs = sorted({(d, p) for d, p, _, _ in cases}, key=lambda x: (x[1], x[0]))
+    cfg = np.asarray(configs, np.int32)
+    b = pi.custom_batch(256, cfg, [[256, 256]], thr_per_pipeline=[1.0] * len(cfg), n_scenarios=64, seed=99)
+    ns, s0 = 160, 7
+    for D, P, a_prev, a_next in cases:
+        b.avail[0, :] = (a_prev, a_next)
+        p = pk.upload(b)
+        p.flags = pk.PARCAE_POOL_ALL
+        c = configs.index((D, P))
+        masks, n_int, d_min = pk.parcae_debug_sample(p, 0, 0, c, s0, ns)
+        _sync()
+        om, oi, od = oracle.debug_sample(D, P, a_next, int(b.seed[0]), 0, c, s0, ns, a_prev=a_prev)
+        assert np.array_equal(_np(masks, np.uint32), om), (D, P, a_prev, a_next)
+        assert np.array_equal(_np(n_int), oi) and np.array_equal(_np(d_min), od), (D, P, a_prev, a_next)
+
+
+@pytest.mark.parametrize("name,S,nq", [("tiny", 256, 1), ("small", 1000, 1), ("large", 300, 1), ("sweep", 500, 40)])
+def test_pool_all_full_parity(pk, name, S, nq):
+    b = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None)
+    p = pk.upload(b)
+    p.flags = pk.PARCAE_POOL_ALL
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in sorted({0, nq - 1}):
+        r = oracle.run_query(b, q, n_scenarios=S, n_threads=8, pool_all=True)
+        assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int)
+        assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min)
+        assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f)
+        assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f)
+        assert np.all(np.abs(_np(ev.gain[q]) - r.tables.gain_d) <= REL * np.abs(r.tables.gain_d))
+        assert np.array_equal(_np(W[q]), r.W_f)
+        assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F)
+        assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_degenerate_shapes(pk):

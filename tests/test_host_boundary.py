@@ -65,7 +65,7 @@ def test_workspace_bytes_and_shape_errors():
         _problem([(1, 1)], T=0), _problem([(1, 1)], nq=0),
         _problem([(1, 1)], S=0), _problem([(1, 1)], S=(1 << 24) + 1),
         _problem([(1, 1)], tau=0.0), _problem([(1, 1)], tau=float("inf")), _problem([(1, 1)], tau=float("nan")),
-        _problem([(1, 1)], flags=1),
+        _problem([(1, 1)], flags=2), _problem([(1, 1)], flags=0x80000001),
         _problem([(1, 1)], fake_ptr=None),       # NULL device tables
     ]
     for prob, _keep in bad_cases:
