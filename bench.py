@@ -25,10 +25,10 @@ if ROOT not in sys.path:
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
-def algorithmic_lane_ops(configs, avail, n_scenarios):
+def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False):
     """Sum over units of S * A(M, k, P): the 32-bit lane operations the method itself needs.
 
-    A(M, k, P) = 33 m + 2 P W + P + W (log2 P + 2) + 10 with m = min(k, M - k) random words (25 operations for a
+    A(M, k, P) = 33 m + 2 P W + P + W (log2 P + 2) + 10 with M the pool, m = min(k, M - k) random words (25 operations for a
     quarter of a Philox4x32-10 block plus 8 for one step of the subset draw), W = ceil(M / 32) mask words (an
     and + popcount per stage and word, a min per stage, an OR-fold per word for the untouched pipelines) and 10
     for the two histogram updates.  Units whose scenarios all land in one bin (k = 0, k = M, a single stage, or a
@@ -38,14 +38,21 @@ def algorithmic_lane_ops(configs, avail, n_scenarios):
     import numpy as np
     D = configs[:, 0].astype(np.int64)
     P = configs[:, 1].astype(np.int64)
-    M = D * P
-    k = np.maximum(0, M[None, None, :] - avail[:, 1:, None].astype(np.int64))          # [nq, T, C]
-    m = np.minimum(k, M[None, None, :] - k)
+    used = D * P
+    a_prev = avail[:, :-1, None].astype(np.int64)
+    a_next = avail[:, 1:, None].astype(np.int64)
+    M = np.broadcast_to(used[None, None, :], a_next.shape[:2] + used.shape)                 # [nq, T, C]
+    if pool_all:
+        M = np.maximum(M, a_prev)
+    k = np.maximum(0, M - a_next)
+    m = np.minimum(k, M - k)
     W = (M + 31) // 32
-    lg = np.ceil(np.log2(np.maximum(P, 1))).astype(np.int64)
-    fixed = 2 * P * W + P + W * (lg + 2) + 10
-    sampled = (m > 0) & (P > 1)[None, None, :] & (D > 1)[None, None, :]
-    A = np.where(sampled, 33 * m + fixed[None, None, :], 0)
+    lg = np.ceil(np.log2(np.maximum(P, 1))).astype(np.int64)[None, None, :]
+    Pb = P[None, None, :]
+    fixed = 2 * Pb * W + Pb + W * (lg + 2) + 10
+    grid_is_pool = M == used[None, None, :]
+    sampled = (m > 0) & ~(grid_is_pool & ((P == 1) | (D == 1))[None, None, :])
+    A = np.where(sampled, 33 * m + fixed, 0)
     return float(A.sum()) * n_scenarios, int(sampled.sum()) * n_scenarios
 
 
@@ -85,7 +92,7 @@ def _soname_loaded(name: str) -> bool:
         return False
 
 
-def cpu_baseline(batch, budget_queries: int):
+def cpu_baseline(batch, budget_queries: int, pool_all: bool = False):
     """The oracle, as it stands, on a bounded sample of the same workload (first queries, all scenarios)."""
     import oracle
     threads = min(oracle.num_threads(), os.cpu_count() or 1)
@@ -94,7 +101,7 @@ def cpu_baseline(batch, budget_queries: int):
     s_cpu = min(batch.n_scenarios, max(256, int(2.5e8 // (units * nq))))   # scenario prefix if one query is too big
     t0 = time.perf_counter()
     for q in range(nq):
-        oracle.run_query(batch, q, n_scenarios=s_cpu, n_threads=threads)
+        oracle.run_query(batch, q, n_scenarios=s_cpu, n_threads=threads, pool_all=pool_all)
     dt = time.perf_counter() - t0
     scen = nq * units * s_cpu
     return {"value": scen / dt, "unit": "evals/s", "cores": threads, "kind": "oracle",
@@ -110,6 +117,8 @@ def main():
     ap.add_argument("--workload", default="sweep", choices=["tiny", "small", "medium", "large", "sweep"])
     ap.add_argument("--dense", action="store_true", help="keep candidate depths below the memory floor")
     ap.add_argument("--queries", type=int, default=None, help="override the number of queries in the batch")
+    ap.add_argument("--pool-all", action="store_true",
+                    help="draw preemptions among all available instances (idle ones included) instead of the used ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -135,12 +144,14 @@ def main():
 
     batch = pi.workload(args.workload, dense=args.dense, n_queries=args.queries)
     prob = pk.upload(batch, device="cuda:0")
+    if args.pool_all:
+        prob.flags = pk.PARCAE_POOL_ALL
     ev_out = pk.alloc_eval_out(prob)
     pl_out = pk.alloc_plan_out(prob)
     nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
     scenarios = nq * T * C * S
     cells = nq * T * C * C
-    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S)
+    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S, args.pool_all)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
@@ -196,7 +207,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u32+f32",
         "data": "synthetic",
-        "config": {"workload": batch.name, "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
+        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
                    "n_configs": C, "n_scenarios": S, "scenarios_per_step": scenarios,
                    "nontrivial_scenarios_per_step": nontrivial, "dp_cells_per_step": cells,
                    "infeasible_queries": int((status != 0).sum())},
@@ -215,7 +226,7 @@ def main():
     if not args.no_cpu_baseline:
         per_query = T * C * S
         budget = args.cpu_queries or max(1, min(nq, int(2.5e8 // max(per_query, 1)) or 1))
-        out["cpu_baseline"] = cpu_baseline(batch, budget)
+        out["cpu_baseline"] = cpu_baseline(batch, budget, args.pool_all)
     print(json.dumps(out), flush=True)
 
 

@@ -396,3 +396,36 @@ def test_runs_on_a_side_stream_and_repeats_identically(pk):
         assert np.array_equal(_np(getattr(ev0, f)), _np(getattr(ev1, f)))
     for f in ("F", "bp", "plan", "start", "objective"):
         assert np.array_equal(_np(getattr(pl0, f)), _np(getattr(pl1, f)))
+
+
+def test_whole_call_can_be_captured_in_a_hip_graph_and_replayed(pk):
+    """The calls enqueue kernels only (no memset or memcpy nodes), so a captured graph replays correctly; every
+    replay is checked against the eager result, with eager work and synchronisations between replays."""
+    import torch
+    b = pi.workload("small", n_scenarios=2000)
+    p = pk.upload(b)
+    ev0, pl0 = pk.parcae_liveput_plan(p)
+    _sync()
+    ev, pl = pk.alloc_eval_out(p), pk.alloc_plan_out(p)
+    p.workspace()                                   # allocate before capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pk.parcae_liveput_plan(p, ev, pl)           # warm-up on the capture stream
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pk.parcae_liveput_plan(p, ev, pl)
+    for rep in range(4):
+        for t in (ev.hist_int, ev.hist_min, ev.liveput, pl.F, pl.bp, pl.plan, pl.objective):
+            t.fill_(-1 if t.dtype != torch.float32 else float("nan"))
+        _sync()
+        graph.replay()
+        _sync()
+        for f in ("hist_int", "hist_min", "liveput", "teff", "gain"):
+            assert np.array_equal(_np(getattr(ev, f)), _np(getattr(ev0, f))), (rep, f)
+        for f in ("F", "bp", "plan", "start", "objective", "status"):
+            assert np.array_equal(_np(getattr(pl, f)), _np(getattr(pl0, f))), (rep, f)
+        ev1 = pk.parcae_liveput_eval(p)             # eager work between the replays
+        _sync()
+        assert np.array_equal(_np(ev1.hist_int), _np(ev0.hist_int))
