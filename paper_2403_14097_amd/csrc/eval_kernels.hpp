@@ -288,6 +288,136 @@ __device__ __forceinline__ int worst_stage_tree(const Mask<NW>& mask, int P)
     return pl.max(keep);
 }
 
+// ---- depths that are not powers of two: pipeline rows do not line up with the 32-bit words ----
+
+// Bits at multiples of P below 32.
+__device__ __forceinline__ uint32_t period_comb(int P)
+{
+    uint32_t q = 0u;
+    for (int b = 0; b < 32; b += P) q |= 1u << b;
+    return q;
+}
+
+// Bits b of word i with (32 i + b) mod P == s, given q = period_comb(P).
+__device__ __forceinline__ uint32_t stage_comb(uint32_t q, int P, int s, int i)
+{
+    int r = (s - 32 * i) % P;
+    r = r < 0 ? r + P : r;
+    return q << r;
+}
+
+// 2 <= P <= 8, not a power of two (3, 5, 6, 7): windows and combs.
+// Intact pipelines: OR of every window of P consecutive bits (built by doubling, shifts cross word
+// boundaries), sampled at the positions where a pipeline starts.  Stage occupancy: popcount of the
+// period-P comb of every stage.
+template <int NW>
+__device__ __forceinline__ void reduce_small_depth(const Mask<NW>& mask, int D, int P, int& n_int, int& d_min)
+{
+    const uint32_t q = period_comb(P);
+    uint32_t y[NW];
+    static_for<NW>([&](auto i) { y[i.value] = mask.w[i.value]; });
+    for (int cover = 1; cover < P;) {
+        const int sh = cover < P - cover ? cover : P - cover;
+        static_for<NW>([&](auto i) {  // ascending: word i + 1 still holds its old value
+            uint32_t next = 0u;
+            if constexpr (i.value + 1 < NW) next = y[i.value + 1];
+            y[i.value] |= __builtin_amdgcn_alignbit(next, y[i.value], (uint32_t)sh);
+        });
+        cover += sh;
+    }
+    int broken = 0;
+    static_for<NW>([&](auto i) { broken += __popc(y[i.value] & stage_comb(q, P, 0, i.value)); });
+    n_int = D - broken;
+    int worst = 0;
+    for (int s = 0; s < P; ++s) {
+        int cnt = 0;
+        static_for<NW>([&](auto i) { cnt += __popc(mask.w[i.value] & stage_comb(q, P, s, i.value)); });
+        worst = cnt > worst ? cnt : worst;
+    }
+    d_min = D - worst;
+}
+
+// 8 < P < 32, not a power of two: every pipeline row is cut out of the two words it touches (the word
+// index is a compile-time constant, the shift is the same in every lane) and added to vertical counters.
+template <int NW, int NP>
+__device__ __forceinline__ void reduce_medium_depth(const Mask<NW>& mask, int D, int P, int& n_int, int& d_min)
+{
+    const uint32_t pmask = (1u << P) - 1u;
+    Planes<NP> pl;
+    pl.clear();
+    int broken = 0;
+    static_for<NW>([&](auto i) {
+        uint32_t hi = 0u;
+        if constexpr (i.value + 1 < NW) hi = mask.w[i.value + 1];
+        const uint32_t lo = mask.w[i.value];
+        // pipelines whose first bit lies in word i
+        int d = (32 * i.value + P - 1) / P;
+        for (; d < D && d * P < 32 * (i.value + 1); ++d) {
+            const uint32_t row = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(d * P - 32 * i.value)) & pmask;
+            pl.add(row);
+            broken += row != 0u ? 1 : 0;
+        }
+    });
+    n_int = D - broken;
+    d_min = D - pl.max();
+}
+
+// P > 32, not a power of two (D <= 7): a pipeline row spans several words; word c of every row is added to
+// its own set of vertical counters.
+template <int NW>
+__device__ __forceinline__ void reduce_large_depth(const Mask<NW>& mask, int D, int P, int& n_int, int& d_min)
+{
+    const int rw = (P + 31) >> 5;                                         // words per row
+    const uint32_t last = (P & 31) ? ((1u << (P & 31)) - 1u) : 0xffffffffu;  // valid bits of a row's last word
+    Planes<3> pl[NW];
+    static_for<NW>([&](auto c) { pl[c.value].clear(); });
+    int broken = 0;
+    static_for<NW>([&](auto i) {
+        // at most one pipeline starts in word i
+        const int d = (32 * i.value + P - 1) / P;
+        if (d < D && d * P < 32 * (i.value + 1)) {
+            const uint32_t sh = (uint32_t)(d * P - 32 * i.value);
+            uint32_t any = 0u;
+            static_for<NW>([&](auto c) {
+                if constexpr (i.value + c.value < NW) {
+                    if (c.value < rw) {
+                        uint32_t hi = 0u;
+                        if constexpr (i.value + c.value + 1 < NW) hi = mask.w[i.value + c.value + 1];
+                        uint32_t x = __builtin_amdgcn_alignbit(hi, mask.w[i.value + c.value], sh);
+                        if (c.value == rw - 1) x &= last;
+                        pl[c.value].add(x);
+                        any |= x;
+                    }
+                }
+            });
+            broken += any != 0u ? 1 : 0;
+        }
+    });
+    int worst = 0;
+    static_for<NW>([&](auto c) {
+        if (c.value < rw) {
+            const int m = pl[c.value].max();
+            worst = m > worst ? m : worst;
+        }
+    });
+    n_int = D - broken;
+    d_min = D - worst;
+}
+
+template <int NW>
+__device__ __forceinline__ void reduce_mask_any_depth(const Mask<NW>& mask, int D, int P, int& n_int, int& d_min)
+{
+    if (P <= 8) {
+        reduce_small_depth<NW>(mask, D, P, n_int, d_min);
+    } else if (P < 32) {
+        if (D <= 7) reduce_medium_depth<NW, 3>(mask, D, P, n_int, d_min);
+        else reduce_medium_depth<NW, 5>(mask, D, P, n_int, d_min);
+    } else {
+        if constexpr (NW >= 2) reduce_large_depth<NW>(mask, D, P, n_int, d_min);
+        else { n_int = D; d_min = D; }  // unreachable: more than 32 stages need more than one word
+    }
+}
+
 // n_int (pipelines without a preempted instance) and d_min (fewest survivors in any stage)
 // of a D x P grid whose preempted instances are the set bits of mask; instance j = d * P + s.
 template <int NW>
@@ -343,21 +473,7 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
         n_int = D - broken;
         d_min = D - worst;
     } else {
-        // any other depth: walk the grid bit by bit (the bit index is the same in every lane)
-        int intact = 0;
-        for (int d = 0; d < D; ++d) {
-            bool hit = false;
-            for (int s = 0; s < P; ++s) hit = hit || mask.test((uint32_t)(d * P + s));
-            intact += hit ? 0 : 1;
-        }
-        int least = D;
-        for (int s = 0; s < P; ++s) {
-            int alive = 0;
-            for (int d = 0; d < D; ++d) alive += mask.test((uint32_t)(d * P + s)) ? 0 : 1;
-            least = alive < least ? alive : least;
-        }
-        n_int = intact;
-        d_min = least;
+        reduce_mask_any_depth<NW>(mask, D, P, n_int, d_min);
     }
 }
 
@@ -486,7 +602,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int M, int k, u
 // Persistent kernel: every wave pulls (unit, chunk) items from the work queue until it is empty, so waves never
 // wait for each other and units without sampling cost nothing here.  Item i is chunk i % n_chunks of
 // list[i / n_chunks]; a chunk is chunk_len consecutive scenarios.  Each wave owns a slice of the LDS bins.
-__global__ void __launch_bounds__(kEvalThreads) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
+__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {

@@ -74,6 +74,14 @@ UNITS = [
     (8, 16, 97), (4, 32, 96), (2, 64, 100), (1, 128, 77), (256, 1, 130), (128, 2, 3), (64, 4, 250),
     (32, 8, 128), (16, 16, 255), (8, 32, 129), (4, 64, 192), (2, 128, 128), (1, 256, 255), (1, 256, 0),
     (3, 64, 100), (1, 64, 40), (2, 96, 150), (7, 32, 100), (5, 40, 120), (12, 20, 100),
+    # depths that are not powers of two, every mask width: 3..7, 9..31, above 32
+    (10, 3, 20), (21, 3, 40), (42, 3, 100), (85, 3, 200), (6, 5, 21), (12, 5, 33), (25, 5, 90), (51, 5, 140),
+    (5, 6, 19), (10, 6, 41), (21, 6, 100), (42, 6, 131), (4, 7, 20), (9, 7, 50), (18, 7, 77), (36, 7, 200),
+    (3, 9, 20), (7, 9, 40), (14, 9, 100), (28, 9, 130), (2, 12, 15), (5, 12, 31), (10, 12, 75), (21, 12, 200),
+    (2, 15, 22), (4, 15, 40), (8, 15, 70), (1, 23, 11), (2, 23, 30), (5, 23, 80), (11, 23, 150),
+    (1, 31, 20), (2, 31, 40), (4, 31, 65), (8, 31, 200), (1, 33, 20), (3, 33, 60), (7, 33, 100),
+    (1, 48, 30), (2, 48, 50), (5, 48, 129), (1, 63, 40), (4, 63, 150), (1, 65, 33), (3, 65, 111),
+    (2, 100, 120), (1, 129, 100), (1, 200, 99), (1, 255, 128), (2, 127, 130),
 ]
 
 
