@@ -77,23 +77,23 @@ def reduce(D: int, P: int, preempted: np.ndarray):
 
 
 def debug_sample(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s0: int, ns: int,
-                 a_prev: int = -1):
+                 a_prev: int = -1, group: int = 1):
     """a_prev >= 0: preemptions drawn among all a_prev available instances (the first D * P run the grid)."""
     masks = np.zeros((ns, 8), dtype=np.uint32)
     n_int = np.zeros(ns, dtype=np.int32)
     d_min = np.zeros(ns, dtype=np.int32)
-    lib().orc_debug_sample(ct.c_int(D), ct.c_int(P), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
+    lib().orc_debug_sample(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
                            ct.c_uint32(stream_id), ct.c_uint32(unit), ct.c_uint32(s0), ct.c_uint32(ns),
                            _p(masks, ct.c_uint32), _p(n_int, ct.c_int32), _p(d_min, ct.c_int32))
     return masks, n_int, d_min
 
 
 def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s_begin: int, s_end: int,
-              a_prev: int = -1):
+              a_prev: int = -1, group: int = 1):
     """Histograms [D + 1] of one unit (unit = t * C + c) over scenarios [s_begin, s_end)."""
     hi = np.zeros(D + 1, dtype=np.uint32)
     hm = np.zeros(D + 1, dtype=np.uint32)
-    lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
+    lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
                         ct.c_uint32(stream_id),
                         ct.c_uint32(unit), ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32),
                         _p(hm, ct.c_uint32))
@@ -101,7 +101,7 @@ def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int,
 
 
 def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1,
-              pool_all: bool = False):
+              pool_all: bool = False, group: int = 1):
     """Histograms [T][L] of one query over scenarios [s_begin, s_end)."""
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -112,7 +112,7 @@ def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, 
     lib().orc_eval_hist(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                         _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
                         ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
-                        ct.c_int(n_threads), ct.c_int(1 if pool_all else 0))
+                        ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group))
     return hi, hm
 
 
@@ -127,7 +127,7 @@ class Tables:
 
 
 def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, hist_min,
-             pool_all: bool = False) -> Tables:
+             pool_all: bool = False, group: int = 1) -> Tables:
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
     avail = np.ascontiguousarray(avail, dtype=np.int32)
@@ -140,14 +140,14 @@ def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, h
                  np.zeros((3, T, C), np.float32), np.zeros((T, C), np.float32), np.zeros((T, C), np.float32))
     lib().orc_finalise(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                        _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
-                       ct.c_uint32(S), ct.c_int(1 if pool_all else 0), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
-                       _p(out.liveput_d, ct.c_double), _p(out.teff_d, ct.c_double), _p(out.gain_d, ct.c_double),
+                       ct.c_uint32(S), ct.c_int(1 if pool_all else 0), ct.c_int(group), _p(hi, ct.c_uint32),
+                       _p(hm, ct.c_uint32), _p(out.liveput_d, ct.c_double), _p(out.teff_d, ct.c_double), _p(out.gain_d, ct.c_double),
                        _p(out.liveput_f, ct.c_float), _p(out.teff_f, ct.c_float), _p(out.gain_f, ct.c_float))
     return out
 
 
 def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: int, cur_config: int,
-               hist_int, hist_min):
+               hist_int, hist_min, group: int = 1):
     """W[T][C][C] in double and in fixed-order float."""
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -161,7 +161,7 @@ def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: in
     W_f = np.zeros((T, C, C), dtype=np.float32)
     lib().orc_transition(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                          _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
-                         ct.c_uint32(S), ct.c_int(p_min), ct.c_int(cur_config),
+                         ct.c_uint32(S), ct.c_int(p_min), ct.c_int(cur_config), ct.c_int(group),
                          _p(hi, ct.c_uint32), _p(hm, ct.c_uint32), _p(W_d, ct.c_double), _p(W_f, ct.c_float))
     return W_d, W_f
 
@@ -214,13 +214,14 @@ class QueryResult:
 def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int = 1, want_plan: bool = True,
               pool_all: bool = False) -> QueryResult:
     """Whole path for query q of a batch object that carries the input arrays."""
+    group = int(getattr(batch, "group_size", 1))
     S = batch.n_scenarios if n_scenarios is None else int(n_scenarios)
     hi, hm = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
-                       0, S, n_threads, pool_all)
+                       0, S, n_threads, pool_all, group)
     tab = finalise(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                   batch.interval_sec, S, hi, hm, pool_all)
+                   batch.interval_sec, S, hi, hm, pool_all, group)
     if not want_plan:
         return QueryResult(hi, hm, tab, None, None, None, float("nan"))
     W_d, W_f = transition(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm)
+                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm, group)
     return QueryResult(hi, hm, tab, W_d, W_f, dp_f32(W_f), dp_f64(W_d))

@@ -132,29 +132,60 @@ void orc_reduce(int D, int P, const uint8_t *preempted, int *n_int, int *d_min, 
  * ones included): the pool is the a_prev available instances, of which the first D*P run the grid and the
  * rest are idle, and it loses N- = max(0, a_prev - a_next).  A configuration that does not even fit
  * a_prev (never a source in the dynamic program) falls back to a pool of its own D*P instances. */
-static void unit_pool(int D, int P, int a_prev, int a_next, int *M, int *k)
+static void unit_pool(int D, int P, int group, int a_prev, int a_next, int *M, int *k)
 {
-    *M = D * P;
+    *M = D * P / (group > 1 ? group : 1); /* instances the configuration occupies */
     if (a_prev > *M) *M = a_prev;
     *k = (*M - a_next > 0) ? (*M - a_next) : 0;
+}
+
+/*
+ * Multi-GPU instances (section 9.2, "Multi-GPU instances"): an instance holds `group` GPUs that are
+ * preempted together, and pipeline parallelism is used across instances only, so the GPUs of one instance
+ * hold the same stage of `group` neighbouring pipelines: instance G of the grid (G < D*P/group) is stage
+ * G mod P of pipelines group*(G div P) .. group*(G div P) + group - 1.  Availability then counts
+ * instances.  gpu[d*P + s] = 1 if the GPU at stage s of pipeline d goes.  D must be a multiple of group.
+ */
+void orc_expand_groups(int D, int P, int group, const uint8_t *instance_preempted, uint8_t *gpu)
+{
+    memset(gpu, 0, (size_t)(D * P));
+    for (int G = 0; G < D * P / group; ++G) {
+        if (!instance_preempted[G]) continue;
+        int block = G / P, stage = G % P;
+        for (int i = 0; i < group; ++i) gpu[(block * group + i) * P + stage] = 1;
+    }
+}
+
+/* One scenario of a unit: which instances of the pool go (pool_pre[M]) and what is left of the D x P grid. */
+static void scenario(int D, int P, int group, int M, int k, uint64_t seed, uint32_t stream_id, uint32_t unit,
+                     uint32_t s, uint8_t *pool_pre, int *n_int, int *d_min)
+{
+    orc_sample_preempted(M, k, seed, stream_id, unit, s, pool_pre);
+    if (group <= 1) {
+        orc_reduce(D, P, pool_pre, n_int, d_min, NULL);
+    } else {
+        uint8_t gpu[ORC_MAX_INSTANCES];
+        orc_expand_groups(D, P, group, pool_pre, gpu);
+        orc_reduce(D, P, gpu, n_int, d_min, NULL);
+    }
 }
 
 /*
  * Debug view of scenarios [s0, s0 + ns) of one unit: packed masks
  * (bit j of word j/32 = instance j of the pool preempted, 8 words per scenario;
  * instances D*P and up are idle ones) and the two per-scenario integers.
- * a_prev < 0 selects the used-instance pool.
+ * a_prev < 0 selects the used-instance pool.  With group > 1 the mask is over instances
+ * of `group` GPUs each, n_int and d_min count GPU pipelines.
  */
-void orc_debug_sample(int D, int P, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
                       uint32_t s0, uint32_t ns, uint32_t *masks, int32_t *n_int, int32_t *d_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
     int M, k;
-    unit_pool(D, P, a_prev, a_next, &M, &k);
+    unit_pool(D, P, group, a_prev, a_next, &M, &k);
     for (uint32_t x = 0; x < ns; ++x) {
         int ni, dm;
-        orc_sample_preempted(M, k, seed, stream_id, unit, s0 + x, pre);
-        orc_reduce(D, P, pre, &ni, &dm, NULL);
+        scenario(D, P, group, M, k, seed, stream_id, unit, s0 + x, pre, &ni, &dm);
         for (int w = 0; w < 8; ++w) masks[x * 8u + (uint32_t)w] = 0u;
         for (int j = 0; j < M; ++j)
             if (pre[j]) masks[x * 8u + (uint32_t)(j / 32)] |= (1u << (j % 32));
@@ -168,17 +199,16 @@ void orc_debug_sample(int D, int P, int a_prev, int a_next, uint64_t seed, uint3
  * a_prev < 0 selects the used-instance pool.
  * unit = t * C + c is the value that enters the random-word counter.
  */
-void orc_eval_unit(int D, int P, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
                    uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
     int M, k;
-    unit_pool(D, P, a_prev, a_next, &M, &k);
+    unit_pool(D, P, group, a_prev, a_next, &M, &k);
     for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; }
     for (uint32_t s = s_begin; s < s_end; ++s) {
         int ni, dm;
-        orc_sample_preempted(M, k, seed, stream_id, unit, s, pre);
-        orc_reduce(D, P, pre, &ni, &dm, NULL);
+        scenario(D, P, group, M, k, seed, stream_id, unit, s, pre, &ni, &dm);
         bins_int[ni] += 1u;
         bins_min[dm] += 1u;
     }
@@ -194,7 +224,7 @@ void orc_eval_unit(int D, int P, int a_prev, int a_next, uint64_t seed, uint32_t
  */
 void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                    uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
-                   uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all)
+                   uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group)
 {
     const int L = thr_off[C];
     memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
@@ -208,13 +238,12 @@ void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off,
         int D = configs[2 * c], P = configs[2 * c + 1];
         int M, k;
         uint8_t pre[ORC_MAX_INSTANCES];
-        unit_pool(D, P, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
+        unit_pool(D, P, group, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
         uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
         uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
         for (uint32_t s = s_begin; s < s_end; ++s) {
             int ni, dm;
-            orc_sample_preempted(M, k, seed, stream_id, (uint32_t)u, s, pre);
-            orc_reduce(D, P, pre, &ni, &dm, NULL);
+            scenario(D, P, group, M, k, seed, stream_id, (uint32_t)u, s, pre, &ni, &dm);
             hi[ni] += 1u;
             hm[dm] += 1u;
         }
@@ -256,7 +285,7 @@ static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int widt
  * and in the fixed float order (*_f).
  */
 void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
-                  const float *thr, const float *cost, float tau, uint32_t S, int pool_all,
+                  const float *thr, const float *cost, float tau, uint32_t S, int pool_all, int group,
                   const uint32_t *hist_int, const uint32_t *hist_min,
                   double *liveput_d, double *teff_d, double *gain_d,
                   float *liveput_f, float *teff_f, float *gain_f)
@@ -266,7 +295,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
         for (int c = 0; c < C; ++c) {
             int D = configs[2 * c], P = configs[2 * c + 1];
             int M, k;
-            unit_pool(D, P, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
+            unit_pool(D, P, group, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
             const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
             const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
             const float *th = thr + thr_off[c];
@@ -282,7 +311,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
                 a_f = a_f + pa;
                 b_f = b_f + pb;
             }
-            int d_cap = (M - k) / P;
+            int d_cap = (group > 1 ? group : 1) * ((M - k) / P); /* surviving instances fill whole blocks of pipelines */
             int d_star = D < d_cap ? D : d_cap;
             size_t o = (size_t)t * C + c, lvl = (size_t)T * C;
             liveput_d[0 * lvl + o] = a_d / (double)S;
@@ -329,19 +358,20 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
  * Both outputs are [T][C][C], row c, column c' contiguous.
  */
 void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
-                    const float *thr, const float *cost, float tau, uint32_t S, int p_min, int cur_config,
+                    const float *thr, const float *cost, float tau, uint32_t S, int p_min, int cur_config, int group,
                     const uint32_t *hist_int, const uint32_t *hist_min, double *W_d, float *W_f)
 {
     const int L = thr_off[C];
     for (int t = 0; t < T; ++t) {
         for (int c = 0; c < C; ++c) {
             int D = configs[2 * c], P = configs[2 * c + 1];
-            int from_ok = (D * P <= avail[t]) && (P >= p_min) && (t > 0 || cur_config < 0 || c == cur_config);
+            const int gpus = group > 1 ? group : 1; /* GPUs per instance: availability counts instances */
+            int from_ok = (D * P <= gpus * avail[t]) && (P >= p_min) && (t > 0 || cur_config < 0 || c == cur_config);
             const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
             const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
             for (int c2 = 0; c2 < C; ++c2) {
                 int D2 = configs[2 * c2], P2 = configs[2 * c2 + 1];
-                int to_ok = (D2 * P2 <= avail[t + 1]) && (P2 >= p_min);
+                int to_ok = (D2 * P2 <= gpus * avail[t + 1]) && (P2 >= p_min);
                 size_t o = ((size_t)t * C + c) * C + c2;
                 if (!from_ok || !to_ok) {
                     W_d[o] = -INFINITY;

@@ -96,6 +96,7 @@ class ProblemBatch:
       seed        uint64 [nq]
       stream_id   uint32 [nq]
       cur_config  int32  [nq]        index of the configuration running now, or -1
+    group_size > 1: instances of that many GPUs; n_instances and avail then count instances, D * P counts GPUs.
     """
 
     name: str
@@ -113,6 +114,7 @@ class ProblemBatch:
     stream_id: np.ndarray
     cur_config: np.ndarray
     meta: dict = field(default_factory=dict)
+    group_size: int = 1        # GPUs per instance (preempted together); availability counts instances
 
     @property
     def n_queries(self) -> int:
@@ -135,7 +137,7 @@ class ProblemBatch:
             np.ascontiguousarray(self.avail[idx]), np.ascontiguousarray(self.thr[idx]),
             np.ascontiguousarray(self.cost[idx]), np.ascontiguousarray(self.seed[idx]),
             np.ascontiguousarray(self.stream_id[idx]), np.ascontiguousarray(self.cur_config[idx]),
-            dict(self.meta))
+            dict(self.meta), self.group_size)
 
     def with_scenarios(self, n_scenarios: int) -> "ProblemBatch":
         """Same inputs with another scenario count (scenario s never depends on the count)."""
@@ -248,7 +250,8 @@ def workload(name: str, **kw) -> ProblemBatch:
 def custom_batch(n_instances: int, configs: Sequence[Sequence[int]], avail: Sequence[Sequence[int]],
                  thr_per_pipeline: Sequence[float] | None = None, cost: Sequence[Sequence[float]] | None = None,
                  *, interval_sec: float = 60.0, p_min: int = 1, n_scenarios: int = 256,
-                 seed: int = 1, cur_config: int = -1, thr: np.ndarray | None = None) -> ProblemBatch:
+                 seed: int = 1, cur_config: int = -1, thr: np.ndarray | None = None,
+                 group_size: int = 1) -> ProblemBatch:
     """Hand-built batch for small worked examples.
 
     thr_per_pipeline[c] gives a linear table thr[c][d] = d * thr_per_pipeline[c]
@@ -277,4 +280,4 @@ def custom_batch(n_instances: int, configs: Sequence[Sequence[int]], avail: Sequ
         interval_sec=float(interval_sec), p_min=int(p_min), n_scenarios=int(n_scenarios),
         configs=cfg, thr_off=off, avail=np.ascontiguousarray(av), thr=np.ascontiguousarray(thr_arr),
         cost=np.ascontiguousarray(cost_arr), seed=seeds, stream_id=np.zeros(nq, dtype=np.uint32),
-        cur_config=np.full(nq, cur_config, dtype=np.int32))
+        cur_config=np.full(nq, cur_config, dtype=np.int32), group_size=int(group_size))
