@@ -38,7 +38,8 @@
  * and the scenario count; each query has its own availability sequence,
  * throughput table, cost table, seed and current configuration.
  *
- * Candidate c = (D_c, P_c): D_c >= 1, P_c >= 1, D_c * P_c <= N <= 256.  The
+ * Candidate c = (D_c, P_c): D_c >= 1, P_c >= 1, D_c * P_c <= N <= 256 (D_c <= 256
+ * and D_c * P_c <= g * N with multi-GPU instances, see below).  The
  * list is strictly increasing in (P, D) lexicographic order (so index order
  * prefers shallower, then narrower configurations when the planner breaks
  * ties).  off[c] = sum over c' < c of (D_c' + 1); L = off[C].
@@ -107,6 +108,8 @@ typedef struct parcae_problem {
     void *event_before_sampling;  /* hipEvent_t or NULL: recorded on the stream right
                                      before the scenario sampling kernel is launched   */
     void *event_after_sampling;   /* hipEvent_t or NULL: recorded right after it       */
+    int32_t group_size;           /* g, GPUs per instance, 0 or 1 = single-GPU instances,
+                                     at most 64; see "Multi-GPU instances" below         */
 } parcae_problem;
 
 /*
@@ -123,6 +126,16 @@ typedef struct parcae_problem {
  *     (section 6.3: the N- preemptions are drawn among all N_i available
  *     instances; a configuration that does not fit avail[q][t] is never a source
  *     in the plan and keeps the pool of its own instances).
+ *
+ * Multi-GPU instances (section 9.2): with g = group_size > 1 an instance holds g
+ * GPUs that are preempted together; pipeline parallelism runs across instances
+ * only, so instance G of the grid (G < D * P / g) is stage G mod P of pipelines
+ * g * (G div P) .. g * (G div P) + g - 1.  n_instances and avail then count
+ * instances while D * P counts GPUs: every D must be a multiple of g, a
+ * candidate needs D * P / g <= N, the plan needs D * P <= g * avail, pools and k
+ * above are in instances (D * P / g in place of D * P), the drawn set is a set
+ * of instances, and n_int, d_min and D* = min(D, g * ((M - k) / P)) count GPU
+ * pipelines (multiples of g).
  *
  * Scenario s of a unit (section 6.3, section 5.1: every instance equally
  * likely) is a k-subset of [0, M) drawn as follows.  Random word i is output

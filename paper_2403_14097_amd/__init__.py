@@ -52,6 +52,7 @@ class parcae_problem(ct.Structure):
         ("avail", ct.c_void_p), ("thr", ct.c_void_p), ("cost", ct.c_void_p), ("seed", ct.c_void_p),
         ("stream_id", ct.c_void_p), ("cur_config", ct.c_void_p),
         ("event_before_sampling", ct.c_void_p), ("event_after_sampling", ct.c_void_p),
+        ("group_size", ct.c_int32),
     ]
 
 
@@ -129,6 +130,7 @@ class Problem:
     stream_id: "object" = None    # int32 view of uint32 [nq] device, or None
     cur_config: "object" = None   # int32 [nq] device, or None
     flags: int = 0                # PARCAE_POOL_USED or PARCAE_POOL_ALL
+    group_size: int = 1           # GPUs per instance (preempted together)
     event_before_sampling: Optional[int] = None   # raw hipEvent_t handles, recorded around the sampling kernel
     event_after_sampling: Optional[int] = None
     _cfg_arr: object = field(default=None, repr=False)
@@ -156,7 +158,7 @@ class Problem:
             self.n_queries, self.n_instances, self.n_intervals, self.n_configs, self.n_scenarios, self.p_min,
             self.interval_sec, int(self.flags), ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
-            _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling)
+            _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling, int(self.group_size))
 
     def workspace(self):
         """Device workspace of the size the library asks for (allocated once per Problem)."""
@@ -188,9 +190,11 @@ def problem_from_arrays(n_instances, n_intervals, interval_sec, p_min, n_scenari
 
 def upload(batch, device="cuda:0", n_scenarios: Optional[int] = None) -> Problem:
     """Problem from any object with the attribute names of the C structure (numpy arrays)."""
-    return problem_from_arrays(batch.n_instances, batch.n_intervals, batch.interval_sec, batch.p_min,
+    prob = problem_from_arrays(batch.n_instances, batch.n_intervals, batch.interval_sec, batch.p_min,
                                batch.n_scenarios if n_scenarios is None else n_scenarios, batch.configs, batch.avail,
                                batch.thr, batch.cost, batch.seed, batch.stream_id, batch.cur_config, device)
+    prob.group_size = int(getattr(batch, "group_size", 1))
+    return prob
 
 
 def _check(rc: int, where: str):

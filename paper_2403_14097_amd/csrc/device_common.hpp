@@ -23,6 +23,7 @@ struct CfgRec {
 struct Batch {
     int32_t nq, N, T, C, S, p_min, L;
     int32_t pool_all;           // 0: preemptions fall on the used instances, 1: on all available ones
+    int32_t group;              // GPUs per instance (>= 1); availability counts instances, D * P counts GPUs
     float tau;
     const CfgRec* cfg;          // [C]
     const int32_t* avail;       // [nq][T+1]
@@ -35,14 +36,18 @@ struct Batch {
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-// Pool (M instances, the first D * P of them run the grid) and preempted count k of unit (q, t, c).
-// Used-instance pool: M = D * P, k = max(0, M - a_t) (section 4.2).  Whole-cluster pool (section 6.3: the
-// N- preemptions fall on any of the N_i available instances, idle ones included): M = max(a_{t-1}, D * P),
-// k = max(0, M - a_t); a configuration that does not fit a_{t-1} keeps the pool of its own instances.
+// Pool (M instances, the first D * P / group of them run the grid) and preempted count k of unit (q, t, c).
+// Used-instance pool: M = instances used, k = max(0, M - a_t) (section 4.2).  Whole-cluster pool
+// (section 6.3: the N- preemptions fall on any of the N_i available instances, idle ones included):
+// M = max(a_{t-1}, instances used), k = max(0, M - a_t); a configuration that does not fit a_{t-1} keeps
+// the pool of its own instances.
+// With multi-GPU instances (section 9.2) an instance holds one stage of `group` neighbouring pipelines, so
+// the instances form a (D / group) x P grid and every count on the GPU grid is `group` times the count on
+// the instance grid; the kernels sample and reduce on the instance grid.
 __device__ __forceinline__ void unit_pool(const Batch& b, int q, int t, int D, int P, int& M, int& k)
 {
     const int32_t* av = b.avail + (int64_t)q * (b.T + 1) + t;
-    M = D * P;
+    M = (D / b.group) * P;
     if (b.pool_all) {
         const int a_prev = clampi(av[0], 0, b.N);
         M = a_prev > M ? a_prev : M;

@@ -526,7 +526,8 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, WorkQueue wq, u
         int M, k;
         unit_pool(b, q, t, cr.D, cr.P, M, k);
         int bin;
-        const uint32_t v = (unit_closed_form(cr.D, cr.P, M, k, bin) && j == bin) ? (uint32_t)b.S : 0u;
+        const uint32_t v =
+            (unit_closed_form(cr.D / b.group, cr.P, M, k, bin) && j == bin * b.group) ? (uint32_t)b.S : 0u;
         hist_int[e] = v;
         hist_min[e] = v;
     }
@@ -550,7 +551,7 @@ __global__ void __launch_bounds__(kBuildThreads) build_work_kernel(Batch b, Work
         const CfgRec cr = b.cfg[tc - t * b.C];
         int M, k, bin;
         unit_pool(b, q, t, cr.D, cr.P, M, k);
-        need = !unit_closed_form(cr.D, cr.P, M, k, bin);
+        need = !unit_closed_form(cr.D / b.group, cr.P, M, k, bin);
     }
     const unsigned long long votes = __ballot(need);
     const int lane = lane_id();
@@ -584,18 +585,20 @@ __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col,
 
 // One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.
 template <int NW>
-__device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int M, int k, uint32_t unit, uint32_t stream_id,
-                                                const PhiloxKeys& ks, uint32_t s_begin, uint32_t s_end,
-                                                uint32_t* lds_col, uint32_t* bins_int, uint32_t* bins_min)
+__device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int M, int k, uint32_t unit,
+                                                uint32_t stream_id, const PhiloxKeys& ks, uint32_t s_begin,
+                                                uint32_t s_end, uint32_t* lds_col, uint32_t* bins_int,
+                                                uint32_t* bins_min)
 {
+    const int rows = cr.D / group;  // pipelines of the instance grid
     for (uint32_t s = s_begin + (uint32_t)lane_id(); s < s_end; s += kWave) {
         int n_int, d_min;
         Mask<NW> mask;
         draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
-        if (M > cr.D * cr.P) mask.keep_below(cr.D * cr.P);  // idle instances of the pool are not on the grid
-        reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
-        hist_add(bins_int, n_int, true);
-        hist_add(bins_min, d_min, true);
+        if (M > rows * cr.P) mask.keep_below(rows * cr.P);  // idle instances of the pool are not on the grid
+        reduce_mask<NW>(mask, rows, cr.P, cr.log2P, n_int, d_min);
+        hist_add(bins_int, n_int * group, true);
+        hist_add(bins_min, d_min * group, true);
     }
 }
 
@@ -670,10 +673,10 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
         uint32_t s_end = s_begin + (uint32_t)chunk_len;
         s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
 
-        if (M <= 32) eval_unit_chunk<1>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else if (M <= 64) eval_unit_chunk<2>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else if (M <= 128) eval_unit_chunk<4>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else eval_unit_chunk<8>(cr, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        if (M <= 32) eval_unit_chunk<1>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else if (M <= 64) eval_unit_chunk<2>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else if (M <= 128) eval_unit_chunk<4>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        else eval_unit_chunk<8>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -695,7 +698,7 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
 
 // One scenario through the same code path the histogram kernel takes for a unit of this size.
 template <int NW>
-__device__ __forceinline__ void debug_one(const CfgRec cr, uint32_t* lds_col, int M, int k, uint32_t s, uint32_t unit,
+__device__ __forceinline__ void debug_one(const CfgRec cr, int group, uint32_t* lds_col, int M, int k, uint32_t s, uint32_t unit,
                                           uint32_t stream_id, const PhiloxKeys& ks, uint32_t* mask_out, int& n_int,
                                           int& d_min)
 {
@@ -705,8 +708,11 @@ __device__ __forceinline__ void debug_one(const CfgRec cr, uint32_t* lds_col, in
         if constexpr (i.value < NW) mask_out[i.value] = mask.w[i.value];
         else mask_out[i.value] = 0u;
     });
-    if (M > cr.D * cr.P) mask.keep_below(cr.D * cr.P);
-    reduce_mask<NW>(mask, cr.D, cr.P, cr.log2P, n_int, d_min);
+    const int rows = cr.D / group;
+    if (M > rows * cr.P) mask.keep_below(rows * cr.P);
+    reduce_mask<NW>(mask, rows, cr.P, cr.log2P, n_int, d_min);
+    n_int *= group;
+    d_min *= group;
 }
 
 // Scenarios one by one, for inspection: masks [ns][8], n_int [ns], d_min [ns].
@@ -728,10 +734,10 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     uint32_t* lds_col = lmask + threadIdx.x;
     uint32_t* out = masks + (size_t)x * 8;
     int n_int, d_min;
-    if (M <= 32) debug_one<1>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else if (M <= 64) debug_one<2>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else if (M <= 128) debug_one<4>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else debug_one<8>(cr, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    if (M <= 32) debug_one<1>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else if (M <= 64) debug_one<2>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else if (M <= 128) debug_one<4>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    else debug_one<8>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
     n_int_out[x] = n_int;
     d_min_out[x] = d_min;
 }

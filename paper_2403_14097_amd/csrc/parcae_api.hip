@@ -43,12 +43,15 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
     if ((p->flags & ~(uint32_t)PARCAE_POOL_ALL) != 0u) return PARCAE_EINVAL;
     if (!(p->interval_sec > 0.0f) || !std::isfinite(p->interval_sec)) return PARCAE_EINVAL;
     if ((int64_t)p->n_configs * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    if (p->group_size < 0 || p->group_size > 64) return PARCAE_EINVAL;
+    const int group = p->group_size > 1 ? p->group_size : 1;
     int64_t L = 0;
     int max_row = 0;
     if (table) table->resize((size_t)p->n_configs);
     for (int c = 0; c < p->n_configs; ++c) {
         const parcae_config g = p->configs[c];
-        if (g.D < 1 || g.P < 1 || (int64_t)g.D * g.P > p->n_instances) return PARCAE_EINVAL;
+        if (g.D < 1 || g.P < 1 || g.D > PARCAE_MAX_INSTANCES || g.D % group != 0) return PARCAE_EINVAL;
+        if ((int64_t)(g.D / group) * g.P > p->n_instances) return PARCAE_EINVAL;
         if (c > 0) {
             const parcae_config h = p->configs[c - 1];
             if (!(h.P < g.P || (h.P == g.P && h.D < g.D))) return PARCAE_EINVAL;  // strictly increasing (P, D)
@@ -97,6 +100,7 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     b.nq = p->n_queries; b.N = p->n_instances; b.T = p->n_intervals; b.C = p->n_configs; b.S = p->n_scenarios;
     b.p_min = p->p_min; b.L = (int32_t)lay.L; b.tau = p->interval_sec;
     b.pool_all = (p->flags & PARCAE_POOL_ALL) ? 1 : 0;
+    b.group = p->group_size > 1 ? p->group_size : 1;
     b.cfg = reinterpret_cast<const CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
     b.cur_config = p->cur_config;

@@ -95,7 +95,7 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
     const uint32_t* hm = hist_min + qt * b.L + cr.off;
     const float* th = b.thr + (int64_t)q * b.L + cr.off;
     const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
-    const int d_cap = (M - k) / cr.P;
+    const int d_cap = b.group * ((M - k) / cr.P);  // surviving instances fill whole blocks of pipelines
     const int d_star = cr.D < d_cap ? cr.D : d_cap;
     const uint32_t S = (uint32_t)b.S;
 
@@ -215,8 +215,8 @@ __device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, co
         const CfgRec cr = sh.cfg[c];
         const int used = cr.D * cr.P;
         const bool deep = cr.P >= b.p_min;
-        sh.from_ok[c] = (used <= a_prev) && deep && (t > 0 || cur < 0 || c == cur);
-        sh.to_ok[c] = (used <= a_next) && deep;
+        sh.from_ok[c] = (used <= b.group * a_prev) && deep && (t > 0 || cur < 0 || c == cur);
+        sh.to_ok[c] = (used <= b.group * a_next) && deep;
     }
     __syncthreads();
 }

@@ -330,6 +330,57 @@ def test_pool_all_full_parity(pk, name, S, nq):
         assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
 
 
+# ------------------------------------------------------------------ multi-GPU instances
+
+def test_grouped_instances_scenarios_one_by_one(pk):
+    cases = [  # D, P, g, a_prev (-1: used pool), a_next   -- availability in instances
+        (8, 3, 4, -1, 5), (4, 2, 2, -1, 3), (16, 4, 4, -1, 9), (32, 8, 4, -1, 40), (64, 4, 8, -1, 20),
+        (8, 16, 2, -1, 50), (12, 5, 3, -1, 13), (8, 4, 2, 30, 22), (16, 8, 4, 60, 33), (6, 7, 2, 40, 25),
+        (8, 32, 8, -1, 20), (128, 2, 64, -1, 3),
+    ]
+    for D, P, g, a_prev, a_next in cases:
+        cfg = np.asarray([[D, P]], np.int32)
+        b = pi.custom_batch(256, cfg, [[max(a_prev, 0), a_next]], thr_per_pipeline=[1.0], n_scenarios=64, seed=5,
+                            group_size=g)
+        p = pk.upload(b)
+        if a_prev >= 0:
+            p.flags = pk.PARCAE_POOL_ALL
+        masks, n_int, d_min = pk.parcae_debug_sample(p, 0, 0, 0, 3, 128)
+        _sync()
+        om, oi, od = oracle.debug_sample(D, P, a_next, int(b.seed[0]), 0, 0, 3, 128, a_prev=a_prev, group=g)
+        assert np.array_equal(_np(masks, np.uint32), om), (D, P, g)
+        assert np.array_equal(_np(n_int), oi) and np.array_equal(_np(d_min), od), (D, P, g)
+        assert np.all(_np(n_int) % g == 0) and np.all(_np(d_min) % g == 0)
+
+
+@pytest.mark.parametrize("pool_all", [False, True])
+def test_grouped_instances_full_parity(pk, pool_all):
+    """Four-GPU instances: 64 instances, candidates in blocks of four pipelines, 40 queries and 1 query."""
+    for nq in (1, 40):
+        spec = pi.WorkloadSpec("quad", nq, 64, 10, 60.0, (2, 4, 8, 16), 2, 6, 16, 0.1, False, 2, 700)
+        b = pi.make_batch(spec, seed=21)
+        # the walks of the drawn batch (in instances) on candidates counted in GPUs: D * P up to 4 * 64
+        cfg = pi.candidate_list(256, (2, 4, 8, 16), 2)
+        cfg = cfg[(cfg[:, 0] % 4 == 0) & (cfg[:, 0] * cfg[:, 1] <= 256) & (cfg[:, 0] <= 64)]
+        g = pi.custom_batch(64, cfg, b.avail, thr_per_pipeline=[1.0 + 0.05 * p for _, p in cfg], n_scenarios=700,
+                            p_min=2, group_size=4, seed=8)
+        p = pk.upload(g)
+        if pool_all:
+            p.flags = pk.PARCAE_POOL_ALL
+        ev, pl = pk.parcae_liveput_plan(p)
+        W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+        _sync()
+        for q in sorted({0, nq - 1}):
+            r = oracle.run_query(g, q, n_threads=8, pool_all=pool_all)
+            assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int)
+            assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min)
+            assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f)
+            assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f)
+            assert np.array_equal(_np(W[q]), r.W_f)
+            assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F)
+            assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_degenerate_shapes(pk):

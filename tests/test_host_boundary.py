@@ -38,12 +38,12 @@ def test_hist_len():
     assert pk.load_library().parcae_hist_len(None, 3) == pk.PARCAE_EINVAL
 
 
-def _problem(configs, nq=1, N=8, T=4, S=16, tau=60.0, p_min=1, flags=0, fake_ptr=0x1000):
+def _problem(configs, nq=1, N=8, T=4, S=16, tau=60.0, p_min=1, flags=0, fake_ptr=0x1000, group=0):
     arr = (pk.parcae_config * len(configs))()
     for i, (d, p) in enumerate(configs):
         arr[i].D, arr[i].P = d, p
     prob = pk.parcae_problem(nq, N, T, len(configs), S, p_min, tau, flags, ct.cast(arr, ct.POINTER(pk.parcae_config)),
-                             fake_ptr, fake_ptr, fake_ptr, fake_ptr, None, None, None, None)
+                             fake_ptr, fake_ptr, fake_ptr, fake_ptr, None, None, None, None, group)
     return prob, arr
 
 
@@ -53,6 +53,8 @@ def test_workspace_bytes_and_shape_errors():
     good, keep = _problem([(1, 1), (2, 1), (1, 2), (2, 4)])
     assert lib.parcae_workspace_bytes(ct.byref(good), ct.byref(out)) == pk.PARCAE_OK
     assert out.value >= 4 * 16 + 4 + 4 * 4 * 4 and out.value % 256 == 0
+    grouped, keep2 = _problem([(4, 4), (8, 4)], group=4)      # 32 GPUs on 8 four-GPU instances
+    assert lib.parcae_workspace_bytes(ct.byref(grouped), ct.byref(out)) == pk.PARCAE_OK
     assert lib.parcae_workspace_bytes(ct.byref(good), None) == pk.PARCAE_EINVAL
     assert lib.parcae_workspace_bytes(None, ct.byref(out)) == pk.PARCAE_EINVAL
     bad_cases = [
@@ -67,6 +69,8 @@ def test_workspace_bytes_and_shape_errors():
         _problem([(1, 1)], tau=0.0), _problem([(1, 1)], tau=float("inf")), _problem([(1, 1)], tau=float("nan")),
         _problem([(1, 1)], flags=2), _problem([(1, 1)], flags=0x80000001),
         _problem([(1, 1)], fake_ptr=None),       # NULL device tables
+        _problem([(3, 2)], group=2), _problem([(2, 2)], group=-1), _problem([(2, 2)], group=65),
+        _problem([(20, 2)], group=4),            # 10 instances needed, 8 exist
     ]
     for prob, _keep in bad_cases:
         assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
