@@ -77,6 +77,8 @@ extern "C" {
 #define PARCAE_POOL_USED 0u /* preemptions fall on the D * P instances the configuration uses (default) */
 #define PARCAE_POOL_ALL 1u  /* preemptions fall on any of the available instances, idle ones included  */
 
+#define PARCAE_COLD_START (-2) /* cur_config value: nothing is running, see the transition weight */
+
 #define PARCAE_OK 0
 #define PARCAE_EINVAL (-1)       /* bad argument or bad input data                       */
 #define PARCAE_EWORKSPACE (-2)   /* workspace NULL, misaligned (256 B) or too small      */
@@ -104,7 +106,8 @@ typedef struct parcae_problem {
     const uint64_t *seed;         /* DEVICE [nq]  Philox key of the query               */
     const uint32_t *stream_id;    /* DEVICE [nq] or NULL (= 0): Philox counter word 3   */
     const int32_t *cur_config;    /* DEVICE [nq] or NULL (= -1): index of the
-                                     configuration running now, -1 = any               */
+                                     configuration running now, -1 = any,
+                                     PARCAE_COLD_START = nothing is running            */
     void *event_before_sampling;  /* hipEvent_t or NULL: recorded on the stream right
                                      before the scenario sampling kernel is launched   */
     void *event_after_sampling;   /* hipEvent_t or NULL: recorded right after it       */
@@ -178,6 +181,9 @@ typedef struct parcae_problem {
  * Transition weight (Eq. 4 with the rule of section 6.2), c -> c' at step t:
  *   -inf if D*P > avail[q][t] or P < p_min or D'*P' > avail[q][1+t] or
  *        P' < p_min, or if t == 0, cur_config[q] >= 0 and c != cur_config[q];
+ *   cold start, cur_config[q] == PARCAE_COLD_START and t == 0 (nothing is running,
+ *        e.g. training was suspended, section 7): -inf unless c == c' and c'
+ *        fits avail[q][1] and p_min, then thr[c'][D'] * max(0, tau - cost[q][c'][2]);
  *   thr[c'][D'] * max(0, tau - cost[q][c'][2])           if P' != P;
  *   thr[c'][D'] * teff(D', cost[q][c']) of unit (q,t,c)  if P' == P.
  *

@@ -351,6 +351,8 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
  *   -inf              if c does not fit avail[t] or c' does not fit avail[t+1],
  *                     if either depth is below p_min, or if t == 0 and a
  *                     current configuration is given and c is not it;
+ *   cold start        cur_config == -2 and t == 0: only c == c' is allowed, at
+ *                     thr(c') * max(0, tau - repartition cost of c');
  *   depth changes     thr(c') * max(0, tau - repartition cost of c')   (section 6.2);
  *   same depth        thr(c') * expected effective seconds, the expectation
  *                     taken over the unit's scenarios by migration class,
@@ -373,13 +375,25 @@ void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off
                 int D2 = configs[2 * c2], P2 = configs[2 * c2 + 1];
                 int to_ok = (D2 * P2 <= gpus * avail[t + 1]) && (P2 >= p_min);
                 size_t o = ((size_t)t * C + c) * C + c2;
+                const float *co = cost + 3 * c2;
+                float full = thr[thr_off[c2] + D2];
+                if (t == 0 && cur_config == -2) {
+                    /* cold start: nothing is running (training was suspended, section 7); the first
+                     * configuration is brought up from the checkpoint at the re-partition cost */
+                    if (c == c2 && to_ok) {
+                        W_d[o] = (double)full * dmax0((double)tau - (double)co[2]);
+                        W_f[o] = full * fmax0(tau - co[2]);
+                    } else {
+                        W_d[o] = -INFINITY;
+                        W_f[o] = -INFINITY;
+                    }
+                    continue;
+                }
                 if (!from_ok || !to_ok) {
                     W_d[o] = -INFINITY;
                     W_f[o] = -INFINITY;
                     continue;
                 }
-                const float *co = cost + 3 * c2;
-                float full = thr[thr_off[c2] + D2];
                 if (P2 != P) {
                     W_d[o] = (double)full * dmax0((double)tau - (double)co[2]);
                     W_f[o] = full * fmax0(tau - co[2]);

@@ -24,6 +24,8 @@ struct Batch {
     int32_t nq, N, T, C, S, p_min, L;
     int32_t pool_all;           // 0: preemptions fall on the used instances, 1: on all available ones
     int32_t group;              // GPUs per instance (>= 1); availability counts instances, D * P counts GPUs
+    int32_t avail_stride;       // ints between the availability rows of consecutive queries (T + 1 if packed)
+    uint32_t stream_offset;     // added to every query's Philox stream id
     float tau;
     const CfgRec* cfg;          // [C]
     const int32_t* avail;       // [nq][T+1]
@@ -46,7 +48,7 @@ __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? l
 // the instance grid; the kernels sample and reduce on the instance grid.
 __device__ __forceinline__ void unit_pool(const Batch& b, int q, int t, int D, int P, int& M, int& k)
 {
-    const int32_t* av = b.avail + (int64_t)q * (b.T + 1) + t;
+    const int32_t* av = b.avail + (int64_t)q * b.avail_stride + t;
     M = (D / b.group) * P;
     if (b.pool_all) {
         const int a_prev = clampi(av[0], 0, b.N);

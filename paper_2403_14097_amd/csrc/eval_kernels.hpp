@@ -668,7 +668,7 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
 
         const uint64_t seed = b.seed[q];
         const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
-        const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
+        const uint32_t stream_id = (b.stream_id ? b.stream_id[q] : 0u) + b.stream_offset;
         const uint32_t s_begin = (uint32_t)chunk * (uint32_t)chunk_len;
         uint32_t s_end = s_begin + (uint32_t)chunk_len;
         s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
@@ -729,7 +729,7 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     unit_pool(b, q, t, cr.D, cr.P, M, k);
     const uint64_t seed = b.seed[q];
     const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
-    const uint32_t stream_id = b.stream_id ? b.stream_id[q] : 0u;
+    const uint32_t stream_id = (b.stream_id ? b.stream_id[q] : 0u) + b.stream_offset;
     const uint32_t unit = (uint32_t)(t * b.C + c);
     uint32_t* lds_col = lmask + threadIdx.x;
     uint32_t* out = masks + (size_t)x * 8;

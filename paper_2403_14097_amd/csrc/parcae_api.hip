@@ -101,6 +101,8 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     b.p_min = p->p_min; b.L = (int32_t)lay.L; b.tau = p->interval_sec;
     b.pool_all = (p->flags & PARCAE_POOL_ALL) ? 1 : 0;
     b.group = p->group_size > 1 ? p->group_size : 1;
+    b.avail_stride = p->n_intervals + 1;
+    b.stream_offset = 0u;
     b.cfg = reinterpret_cast<const CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
     b.cur_config = p->cur_config;

@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restr
     __syncthreads();
     int my_bad = 0;
     for (int i = threadIdx.x; i <= b.T; i += blockDim.x) {
-        const int a = b.avail[(int64_t)q * (b.T + 1) + i];
+        const int a = b.avail[(int64_t)q * b.avail_stride + i];
         if (a < 0 || a > b.N) my_bad = 1;
     }
     for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restr
     }
     if (threadIdx.x == 0 && b.cur_config) {
         const int cur = b.cur_config[q];
-        if (cur < -1 || cur >= b.C) my_bad = 1;
+        if (cur < -2 || cur >= b.C) my_bad = 1;
     }
     if (my_bad) atomicOr(&bad, 1);
     __syncthreads();
@@ -146,6 +146,7 @@ struct PlanShared {
     uint32_t* tail_min;  // [cap] same for hist_min, except that slot 0 of a row keeps the raw bin 0
     uint16_t* bp16;      // [T][C] back-pointers (0xffff = none) if they fit in LDS, else null
     int n_chunks;
+    int cold;            // this step starts from nothing running (t == 0 and cur_config == -2)
 };
 
 constexpr int kPlanThreads = 256;
@@ -206,11 +207,12 @@ __device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap
 
 // Feasibility of leaving / entering each candidate at step t (constraint D * P <= N of Eq. 6, memory floor,
 // and the current configuration at t = 0).  Ends with a barrier.
-__device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, const PlanShared& sh)
+__device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, PlanShared& sh)
 {
-    const int a_prev = clampi(b.avail[(int64_t)q * (b.T + 1) + t], 0, b.N);
-    const int a_next = clampi(b.avail[(int64_t)q * (b.T + 1) + t + 1], 0, b.N);
+    const int a_prev = clampi(b.avail[(int64_t)q * b.avail_stride + t], 0, b.N);
+    const int a_next = clampi(b.avail[(int64_t)q * b.avail_stride + t + 1], 0, b.N);
     const int cur = b.cur_config ? b.cur_config[q] : -1;
+    sh.cold = (t == 0 && cur == -2) ? 1 : 0;
     for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
         const CfgRec cr = sh.cfg[c];
         const int used = cr.D * cr.P;
@@ -252,6 +254,8 @@ __device__ __forceinline__ void load_chunk(const Batch& b, int q, int t, int c_l
 // W_t[c][c'] for a source c inside the chunk that starts at bin `first`.
 __device__ __forceinline__ float transition_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2)
 {
+    if (sh.cold)  // nothing is running: the first configuration comes up at its re-partition cost
+        return (c == c2 && sh.to_ok[c2]) ? __fmul_rn(sh.full[c2], sh.e[3 * c2 + 2]) : kNegInf;
     if (!sh.from_ok[c] || !sh.to_ok[c2]) return kNegInf;
     const CfgRec a = sh.cfg[c], z = sh.cfg[c2];
     const float full = sh.full[c2];

@@ -223,3 +223,23 @@ def test_workload_generator_shapes():
     assert pi.workload("large", dense=True).n_configs == 508
     sw = pi.workload("sweep", n_queries=8)
     assert sw.n_queries == 8 and sw.n_configs == 30 and len(set(sw.seed.tolist())) == 8
+
+
+def test_cold_start_brings_up_the_first_configuration_at_the_repartition_cost():
+    """cur_config = -2: nothing is running (training was suspended, section 7)."""
+    cfg = pi.candidate_list(8, (1, 2, 4), 1)
+    b = pi.custom_batch(8, cfg, [[1, 6, 7]], thr_per_pipeline=[1.0 + 0.5 * p for _, p in cfg], n_scenarios=64,
+                        cur_config=-2, cost=[[1.0, 8.0, 25.0]] * len(cfg), p_min=2)
+    r = _run(b, S=64)
+    used = cfg[:, 0] * cfg[:, 1]
+    full = b.thr[0, b.thr_off[1:] - 1]
+    for c in range(len(cfg)):
+        for c2 in range(len(cfg)):
+            if c == c2 and used[c2] <= 6 and cfg[c2, 1] >= 2:
+                assert r.W_f[0, c, c2] == np.float32(full[c2] * np.float32(35.0))
+            else:
+                assert r.W_f[0, c, c2] == -np.inf
+    assert r.plan.feasible and r.plan.start == r.plan.plan[0]
+    # the availability now (1 instance) does not matter for a cold start; a warm free start would be infeasible
+    b.cur_config[0] = -1
+    assert not _run(b, S=64).plan.feasible
