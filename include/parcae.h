@@ -269,6 +269,38 @@ int parcae_debug_sample(const parcae_problem *p, int32_t q, int32_t t, int32_t c
                         uint32_t *masks, int32_t *n_int, int32_t *d_min, void *workspace,
                         size_t workspace_bytes, void *stream);
 
+/*
+ * Receding-horizon replay of the planner along a true availability walk (algorithm 1's scheduler loop,
+ * the adaptation of section 7, and the reactive baseline of section 9.4), for every query of the batch,
+ * with no host synchronisation between the steps.  State of a query: the configuration running in
+ * interval i, starting from cur_config[q] (a negative value: nothing is running).  Step i = 0 .. n_steps-1:
+ *   1. PARCAE_REPLAY_PROACTIVE: parcae_liveput_plan on window i (availability now + forecast) with the state
+ *      as current configuration (cold start if nothing runs) and Philox stream id + 2 i; target = plan[0],
+ *      or the running configuration if no plan is feasible.
+ *      PARCAE_REPLAY_REACTIVE: target = the candidate with the largest thr[c][D_c] that fits the actual
+ *      availability a = true_avail[q][i + 1] and p_min (smallest index on ties).
+ *   2. adaptation: if a equals the forecast windows[i][q][1] (always, for the reactive mode) and the target
+ *      fits, it stands; otherwise the widest candidate of the target's depth that fits a; if none, the widest
+ *      candidate of the deepest shallower depth (>= p_min) that fits; if none, nothing runs (-1).
+ *   3. reward = transition weight (as defined above) from the state to the new configuration for the one
+ *      interval that actually happened (availability true_avail[q][i] -> a, stream id + 2 i + 1), without the
+ *      feasibility test; re-partition formula if nothing was running; 0 if nothing runs afterwards.
+ *      total[q] accumulates the rewards in float in step order.
+ *   p->avail is ignored.  The pool flag, group_size and all tables of p apply.
+ *   true_avail  DEVICE in  [nq][n_steps + 1]
+ *   windows     DEVICE in  [n_steps][nq][T + 1], windows[i][q][0] = true_avail[q][i]; may be NULL for
+ *               PARCAE_REPLAY_REACTIVE
+ *   chosen      DEVICE out [nq][n_steps] int32: configuration of interval i + 1, -1 = none
+ *   reward      DEVICE out [nq][n_steps] float;  total  DEVICE out [nq] float
+ *   workspace   DEVICE, 256-byte aligned, >= parcae_replay_workspace_bytes()
+ */
+#define PARCAE_REPLAY_PROACTIVE 0
+#define PARCAE_REPLAY_REACTIVE 1
+int parcae_replay_workspace_bytes(const parcae_problem *p, int32_t n_steps, size_t *bytes);
+int parcae_replay(const parcae_problem *p, int32_t n_steps, const int32_t *true_avail, const int32_t *windows,
+                  int32_t mode, int32_t *chosen, float *reward, float *total, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
 /* Static, NUL-terminated description of a return code (HOST). */
 const char *parcae_strerror(int code);
 

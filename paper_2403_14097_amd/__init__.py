@@ -25,11 +25,14 @@ PARCAE_EINFEASIBLE = -4
 PARCAE_MAX_INSTANCES = 256
 PARCAE_POOL_USED = 0
 PARCAE_POOL_ALL = 1
+PARCAE_COLD_START = -2
+PARCAE_REPLAY_PROACTIVE = 0
+PARCAE_REPLAY_REACTIVE = 1
 
 EXPORTED_SYMBOLS = (
     "parcae_workspace_bytes", "parcae_hist_len", "parcae_liveput_eval", "parcae_plan_from_hist",
     "parcae_liveput_plan", "parcae_transition_weights", "parcae_dp_plan", "parcae_debug_sample",
-    "parcae_strerror", "parcae_version",
+    "parcae_strerror", "parcae_version", "parcae_replay", "parcae_replay_workspace_bytes",
 )
 
 
@@ -79,6 +82,8 @@ def load_library() -> ct.CDLL:
     lib.parcae_transition_weights.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.parcae_dp_plan.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.parcae_debug_sample.argtypes = [pp, i32, i32, i32, u32, u32, vp, vp, vp, vp, sz, vp]
+    lib.parcae_replay_workspace_bytes.argtypes = [pp, i32, ct.POINTER(sz)]
+    lib.parcae_replay.argtypes = [pp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.parcae_strerror.argtypes = [ct.c_int]
     lib.parcae_strerror.restype = ct.c_char_p
     lib.parcae_version.restype = ct.c_int
@@ -323,3 +328,28 @@ def parcae_debug_sample(p: Problem, q: int, t: int, c: int, s0: int, ns: int):
     _check(load_library().parcae_debug_sample(ct.byref(cs), q, t, c, s0, ns, _ptr(masks), _ptr(n_int), _ptr(d_min), ws,
                                               nbytes, _stream_handle()), "parcae_debug_sample")
     return masks, n_int, d_min
+
+
+def parcae_replay(p: Problem, true_avail, windows, mode: int = PARCAE_REPLAY_PROACTIVE):
+    """Replay every query over H = true_avail.shape[1] - 1 steps; returns (chosen [nq, H], reward [nq, H], total [nq])."""
+    torch = _require_gpu()
+    dev = p.thr.device
+    nq, H = int(true_avail.shape[0]), int(true_avail.shape[1]) - 1
+    assert true_avail.dtype == torch.int32 and true_avail.is_contiguous()
+    if windows is not None:
+        assert windows.dtype == torch.int32 and windows.is_contiguous()
+        assert tuple(windows.shape) == (H, nq, p.n_intervals + 1)
+    chosen = torch.empty((nq, H), dtype=torch.int32, device=dev)
+    reward = torch.empty((nq, H), dtype=torch.float32, device=dev)
+    total = torch.empty(nq, dtype=torch.float32, device=dev)
+    cs = p.c_struct()
+    need = ct.c_size_t(0)
+    _check(load_library().parcae_replay_workspace_bytes(ct.byref(cs), H, ct.byref(need)), "parcae_replay_workspace_bytes")
+    ws = torch.empty(need.value + 256, dtype=torch.uint8, device=dev)
+    ptr = ws.data_ptr()
+    pad = (-ptr) % 256
+    _check(load_library().parcae_replay(ct.byref(cs), H, _ptr(true_avail), _ptr(windows), int(mode), _ptr(chosen),
+                                        _ptr(reward), _ptr(total), ptr + pad, ws.numel() - pad, _stream_handle()),
+           "parcae_replay")
+    torch.cuda.current_stream().synchronize()   # the workspace tensor must outlive the enqueued work
+    return chosen, reward, total

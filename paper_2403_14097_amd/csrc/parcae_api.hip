@@ -11,6 +11,7 @@
 #include "device_common.hpp"
 #include "eval_kernels.hpp"
 #include "plan_kernels.hpp"
+#include "replay_kernels.hpp"
 
 namespace {
 
@@ -411,6 +412,121 @@ int parcae_dp_plan(const float* W, int32_t n_queries, int32_t n_intervals, int32
     if ((int64_t)n_queries * n_intervals >= (int64_t)1 << 31 || n_queries > 65535 * 32) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return launch_dp(W, n_queries, n_intervals, n_configs, nullptr, F, nullptr, bp, plan, start, objective, status, st);
+}
+
+namespace {
+
+struct ReplayLayout {
+    size_t hist_int_off, hist_min_off, plan_off, hist1_int_off, hist1_min_off, state_off, total;
+};
+
+ReplayLayout replay_layout(const parcae_problem* p, const Layout& lay)
+{
+    const size_t nq = (size_t)p->n_queries, T = (size_t)p->n_intervals, L = (size_t)lay.L;
+    ReplayLayout r;
+    r.hist_int_off = lay.total;
+    r.hist_min_off = r.hist_int_off + align_up(sizeof(uint32_t) * nq * T * L);
+    r.plan_off = r.hist_min_off + align_up(sizeof(uint32_t) * nq * T * L);
+    r.hist1_int_off = r.plan_off + align_up(sizeof(int32_t) * nq * T);
+    r.hist1_min_off = r.hist1_int_off + align_up(sizeof(uint32_t) * nq * L);
+    r.state_off = r.hist1_min_off + align_up(sizeof(uint32_t) * nq * L);
+    r.total = r.state_off + align_up(sizeof(int32_t) * nq);
+    return r;
+}
+
+// The problem as the replay sees it: availability comes from the windows, no profiling events.
+parcae_problem replay_problem(const parcae_problem* p, const int32_t* windows)
+{
+    parcae_problem q = *p;
+    q.avail = windows;
+    q.event_before_sampling = nullptr;
+    q.event_after_sampling = nullptr;
+    return q;
+}
+
+}  // namespace
+
+int parcae_replay_workspace_bytes(const parcae_problem* p, int32_t n_steps, size_t* bytes)
+{
+    if (!p || !bytes || n_steps < 1) return PARCAE_EINVAL;
+    int32_t dummy = 0;
+    const parcae_problem q = replay_problem(p, p->avail ? p->avail : &dummy);
+    Layout lay;
+    const int rc = check_problem(&q, nullptr, &lay);
+    if (rc != PARCAE_OK) return rc;
+    *bytes = replay_layout(&q, lay).total;
+    return PARCAE_OK;
+}
+
+int parcae_replay(const parcae_problem* p, int32_t n_steps, const int32_t* true_avail, const int32_t* windows,
+                  int32_t mode, int32_t* chosen, float* reward, float* total, void* workspace, size_t workspace_bytes,
+                  void* stream)
+{
+    if (!p || !true_avail || !chosen || !reward || !total || n_steps < 1) return PARCAE_EINVAL;
+    if (mode != PARCAE_REPLAY_PROACTIVE && mode != PARCAE_REPLAY_REACTIVE) return PARCAE_EINVAL;
+    if (mode == PARCAE_REPLAY_PROACTIVE && !windows) return PARCAE_EINVAL;
+    if ((int64_t)p->n_queries * ((int64_t)n_steps + 1) >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    const parcae_problem q = replay_problem(p, windows ? windows : true_avail);
+    std::vector<CfgRec> table;
+    Layout lay;
+    int rc = check_problem(&q, &table, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!plan_fits(&q, lay)) return PARCAE_EINVAL;
+    const ReplayLayout rl = replay_layout(&q, lay);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < rl.total)
+        return PARCAE_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    uint32_t* hist_int = reinterpret_cast<uint32_t*>(base + rl.hist_int_off);
+    uint32_t* hist_min = reinterpret_cast<uint32_t*>(base + rl.hist_min_off);
+    int32_t* plan = reinterpret_cast<int32_t*>(base + rl.plan_off);
+    uint32_t* hist1_int = reinterpret_cast<uint32_t*>(base + rl.hist1_int_off);
+    uint32_t* hist1_min = reinterpret_cast<uint32_t*>(base + rl.hist1_min_off);
+    int32_t* state = reinterpret_cast<int32_t*>(base + rl.state_off);
+
+    Batch b = make_batch(&q, lay, workspace);
+    if (mode == PARCAE_REPLAY_REACTIVE) {  // no windows: the staging check reads the true walk instead
+        b.avail = true_avail;
+        b.avail_stride = n_steps + 1;
+        b.T = 1;
+    }
+    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    b = make_batch(&q, lay, workspace);
+    const unsigned qblocks = (unsigned)((b.nq + 255) / 256);
+    parcae::replay_init_kernel<<<dim3(qblocks), dim3(256), 0, st>>>(b.nq, p->cur_config, state, total);
+    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+
+    for (int i = 0; i < n_steps; ++i) {
+        const int32_t* window = nullptr;
+        if (mode == PARCAE_REPLAY_PROACTIVE) {
+            Batch bi = b;
+            window = windows + (int64_t)i * b.nq * (b.T + 1);
+            bi.avail = window;
+            bi.cur_config = state;
+            bi.stream_offset = 2u * (uint32_t)i;
+            if ((rc = launch_eval(&q, bi, lay, workspace, hist_int, hist_min, nullptr, nullptr, nullptr, nullptr, st)) !=
+                PARCAE_OK)
+                return rc;
+            if ((rc = launch_plan(bi, lay, workspace, hist_int, hist_min, nullptr, nullptr, plan, nullptr, nullptr,
+                                  nullptr, st)) != PARCAE_OK)
+                return rc;
+        }
+        // the interval that actually happened: one step from true[i] to true[i + 1]
+        Batch b1 = b;
+        b1.T = 1;
+        b1.avail = true_avail + i;
+        b1.avail_stride = n_steps + 1;
+        b1.cur_config = state;
+        b1.stream_offset = 2u * (uint32_t)i + 1u;
+        if ((rc = launch_eval(&q, b1, lay, workspace, hist1_int, hist1_min, nullptr, nullptr, nullptr, nullptr, st)) !=
+            PARCAE_OK)
+            return rc;
+        parcae::replay_step_kernel<<<dim3(qblocks), dim3(256), 0, st>>>(b1, mode, i, n_steps, b.T, true_avail, window,
+                                                                         plan, hist1_int, hist1_min, state, chosen,
+                                                                         reward, total);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
+    return PARCAE_OK;
 }
 
 int parcae_debug_sample(const parcae_problem* p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,

@@ -381,6 +381,71 @@ def test_grouped_instances_full_parity(pk, pool_all):
             assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
 
 
+# ------------------------------------------------------------------ receding-horizon replay
+
+def _replay_inputs(b, H, noise_seed):
+    """True walks = the batch's own walks; forecasts = the truth plus a small seeded error, clipped."""
+    T = b.n_intervals
+    rng = np.random.default_rng(noise_seed)
+    true = np.ascontiguousarray(b.avail[:, : H + 1])
+    nq = b.n_queries
+    win = np.zeros((H, nq, T + 1), np.int32)
+    for i in range(H):
+        for q in range(nq):
+            fut = [b.avail[q, min(i + 1 + t, b.avail.shape[1] - 1)] for t in range(T)]
+            err = rng.integers(-3, 4, size=T)
+            win[i, q, 0] = true[q, i]
+            win[i, q, 1:] = np.clip(np.asarray(fut) + err, 0, b.n_instances)
+    return true, win
+
+
+@pytest.mark.parametrize("nq,pool_all", [(3, False), (40, False), (5, True)])
+def test_replay_matches_the_oracle_replay(pk, nq, pool_all):
+    import torch
+    from oracle import replay as rp
+    spec = pi.WorkloadSpec("replay", nq, 64, 18, 60.0, (2, 4, 8, 16, 32), 4, 6, 16, 0.12, False, 2, 300)
+    b = pi.make_batch(spec, seed=404)
+    H = 7
+    b_plan = b.take(range(nq))
+    b_plan.n_intervals = 10                                   # look-ahead of the planner inside the replay
+    b_plan.avail = np.ascontiguousarray(b.avail[:, :11])
+    b_plan.cur_config[1 % nq] = -1                            # one query starts with nothing running
+    true, win = _replay_inputs(b, H, 5)
+    win = np.ascontiguousarray(win[:, :, :11])
+    p = pk.upload(b_plan)
+    if pool_all:
+        p.flags = pk.PARCAE_POOL_ALL
+    t_true = torch.from_numpy(true).cuda()
+    t_win = torch.from_numpy(win).cuda()
+    for mode in (pk.PARCAE_REPLAY_PROACTIVE, pk.PARCAE_REPLAY_REACTIVE):
+        chosen, reward, total = pk.parcae_replay(p, t_true, t_win if mode == pk.PARCAE_REPLAY_PROACTIVE else None, mode)
+        _sync()
+        for q in sorted({0, 1 % nq, nq - 1}):
+            r = rp.replay(b_plan, q, true[q], win[:, q, :], mode, n_threads=8, pool_all=pool_all)
+            assert np.array_equal(_np(chosen[q]), r.chosen), (mode, q)
+            assert np.array_equal(_np(reward[q]), r.reward), (mode, q)
+            assert float(total[q]) == r.total
+            assert abs(float(total[q]) - r.total_d) <= REL * abs(r.total_d)
+
+
+def test_replay_suspends_and_restarts(pk):
+    """Availability falls below the memory floor and comes back: nothing runs, then a cold start."""
+    import torch
+    from oracle import replay as rp
+    cfg = pi.candidate_list(8, (2, 4), 2)
+    b = pi.custom_batch(8, cfg, [[8, 8, 8]], thr_per_pipeline=[1.0 + p for _, p in cfg], n_scenarios=128, p_min=2,
+                        cur_config=len(cfg) - 1)
+    true = np.asarray([[8, 3, 1, 6, 7]], np.int32)
+    win = np.asarray([[[8, 8, 8]], [[3, 8, 8]], [[1, 8, 8]], [[6, 6, 6]]], np.int32)
+    p = pk.upload(b)
+    chosen, reward, total = pk.parcae_replay(p, torch.from_numpy(true).cuda(), torch.from_numpy(win).cuda())
+    _sync()
+    r = rp.replay(b, 0, true[0], win[:, 0, :], rp.PROACTIVE)
+    assert r.chosen[1] == -1 and r.chosen[2] >= 0
+    assert np.array_equal(_np(chosen[0]), r.chosen) and np.array_equal(_np(reward[0]), r.reward)
+    assert float(total[0]) == r.total
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_degenerate_shapes(pk):
