@@ -41,6 +41,8 @@ def lib() -> ct.CDLL:
         _lib = ct.CDLL(_LIB)
         _lib.orc_word.restype = ct.c_uint32
         _lib.orc_word.argtypes = [ct.c_uint64, ct.c_uint32, ct.c_uint32, ct.c_uint32, ct.c_uint32]
+        _lib.orc_word_at.restype = ct.c_uint32
+        _lib.orc_word_at.argtypes = [ct.c_uint64, ct.c_uint32, ct.c_uint32, ct.c_uint32, ct.c_uint32, ct.c_uint32]
         _lib.orc_dp_f32.restype = ct.c_int
         _lib.orc_dp_f64.restype = ct.c_double
         _lib.orc_num_threads.restype = ct.c_int
@@ -66,6 +68,28 @@ def sample_preempted(M: int, k: int, seed: int, stream_id: int, unit: int, s: in
     return out
 
 
+def _zones(zone, weight):
+    """(n_zones, zone pointer, weight pointer, keep-alive arrays) for the C calls; uniform when zone is None."""
+    if zone is None:
+        return ct.c_int(0), None, None, ()
+    z = np.ascontiguousarray(zone, dtype=np.uint8)
+    w = np.ascontiguousarray(weight, dtype=np.uint32)
+    return ct.c_int(int(w.size)), _p(z, ct.c_uint8), _p(w, ct.c_uint32), (z, w)
+
+
+def word_at(seed: int, stream_id: int, unit: int, s: int, prefix: int, i: int) -> int:
+    return int(lib().orc_word_at(ct.c_uint64(seed), stream_id, unit, s, prefix, i))
+
+
+def sample_preempted_zoned(M: int, k: int, zone, weight, seed: int, stream_id: int, unit: int, s: int) -> np.ndarray:
+    out = np.zeros(M, dtype=np.uint8)
+    nz, zp, wp, keep = _zones(zone, weight)
+    assert len(keep[0]) >= M
+    lib().orc_sample_preempted_zoned(ct.c_int(M), ct.c_int(k), nz, zp, wp, ct.c_uint64(seed), ct.c_uint32(stream_id),
+                                     ct.c_uint32(unit), ct.c_uint32(s), _p(out, ct.c_uint8))
+    return out
+
+
 def reduce(D: int, P: int, preempted: np.ndarray):
     pre = np.ascontiguousarray(preempted, dtype=np.uint8)
     assert pre.size == D * P
@@ -77,23 +101,27 @@ def reduce(D: int, P: int, preempted: np.ndarray):
 
 
 def debug_sample(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s0: int, ns: int,
-                 a_prev: int = -1, group: int = 1):
+                 a_prev: int = -1, group: int = 1, zone=None, weight=None):
     """a_prev >= 0: preemptions drawn among all a_prev available instances (the first D * P run the grid)."""
     masks = np.zeros((ns, 8), dtype=np.uint32)
     n_int = np.zeros(ns, dtype=np.int32)
     d_min = np.zeros(ns, dtype=np.int32)
-    lib().orc_debug_sample(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
+    nz, zp, wp, _keep = _zones(zone, weight)
+    lib().orc_debug_sample(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), nz, zp, wp,
+                           ct.c_uint64(seed),
                            ct.c_uint32(stream_id), ct.c_uint32(unit), ct.c_uint32(s0), ct.c_uint32(ns),
                            _p(masks, ct.c_uint32), _p(n_int, ct.c_int32), _p(d_min, ct.c_int32))
     return masks, n_int, d_min
 
 
 def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s_begin: int, s_end: int,
-              a_prev: int = -1, group: int = 1):
+              a_prev: int = -1, group: int = 1, zone=None, weight=None):
     """Histograms [D + 1] of one unit (unit = t * C + c) over scenarios [s_begin, s_end)."""
     hi = np.zeros(D + 1, dtype=np.uint32)
     hm = np.zeros(D + 1, dtype=np.uint32)
-    lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), ct.c_uint64(seed),
+    nz, zp, wp, _keep = _zones(zone, weight)
+    lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), nz, zp, wp,
+                        ct.c_uint64(seed),
                         ct.c_uint32(stream_id),
                         ct.c_uint32(unit), ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32),
                         _p(hm, ct.c_uint32))
@@ -101,8 +129,9 @@ def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int,
 
 
 def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1,
-              pool_all: bool = False, group: int = 1):
+              pool_all: bool = False, group: int = 1, zone=None, weight=None):
     """Histograms [T][L] of one query over scenarios [s_begin, s_end)."""
+    nz, zp, wp, _keep = _zones(zone, weight)
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
     avail = np.ascontiguousarray(avail, dtype=np.int32)
@@ -112,7 +141,7 @@ def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, 
     lib().orc_eval_hist(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                         _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
                         ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
-                        ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group))
+                        ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group), nz, zp, wp)
     return hi, hm
 
 
@@ -211,13 +240,22 @@ class QueryResult:
     objective_d: float
 
 
+def batch_zones(batch, q: int):
+    """(zone[N], weight[n_zones]) of query q, or (None, None) when the batch draws uniformly."""
+    zone = getattr(batch, "zone", None)
+    if zone is None:
+        return None, None
+    return zone[q], batch.zone_weight[q][: int(batch.n_zones)]
+
+
 def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int = 1, want_plan: bool = True,
               pool_all: bool = False) -> QueryResult:
     """Whole path for query q of a batch object that carries the input arrays."""
     group = int(getattr(batch, "group_size", 1))
     S = batch.n_scenarios if n_scenarios is None else int(n_scenarios)
+    zone, weight = batch_zones(batch, q)
     hi, hm = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
-                       0, S, n_threads, pool_all, group)
+                       0, S, n_threads, pool_all, group, zone, weight)
     tab = finalise(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
                    batch.interval_sec, S, hi, hm, pool_all, group)
     if not want_plan:

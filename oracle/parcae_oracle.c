@@ -24,6 +24,9 @@
  *   word i is output lane i mod 4.
  *   Subset: R. Floyd's sampling (Bentley & Floyd, CACM 1987) of the smaller
  *   of the preempted / surviving sets, bounded integers by multiply-shift.
+ *   Non-uniform preemption (optional): zones with integer hazard weights,
+ *   successive weighted sampling without replacement, see
+ *   orc_sample_preempted_zoned.
  *
  * Precision: every floating-point result is produced twice, in double
  * (the reference value) and in float with one fixed operation order and no
@@ -74,6 +77,17 @@ uint32_t orc_word(uint64_t seed, uint32_t stream_id, uint32_t unit, uint32_t s, 
     return out[i % 4u];
 }
 
+/* Random word i of the sequence `prefix` (0 .. 0xFFFF) of a scenario: block index = prefix * 2^16 + i / 4.
+ * Sequence 0 is orc_word's. */
+uint32_t orc_word_at(uint64_t seed, uint32_t stream_id, uint32_t unit, uint32_t s, uint32_t prefix, uint32_t i)
+{
+    uint32_t ctr[4] = { s, (prefix << 16) + i / 4u, unit, stream_id };
+    uint32_t key[2] = { (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return out[i % 4u];
+}
+
 /* ---------------------------------------------------------------- sampler */
 
 /*
@@ -96,6 +110,65 @@ void orc_sample_preempted(int M, int k, uint64_t seed, uint32_t stream_id, uint3
     }
     int complement = (k > M - k);
     for (int j = 0; j < M; ++j) preempted[j] = complement ? (uint8_t)!chosen[j] : chosen[j];
+}
+
+#define ORC_MAX_ZONES 4
+
+/*
+ * Preempted set when instances are NOT equally likely to go (section 5.1 allows the uniform assumption to
+ * be replaced by better estimates; section 4.1 names availability zones and instance types as what drives
+ * preemptions).  Instance j of the pool belongs to zone zone[j] < n_zones, zone z has the integer hazard
+ * weight weight[z] in [1, 255].  The k preempted instances leave one after the other, each time one of the
+ * remaining instances with probability proportional to its weight (successive weighted sampling without
+ * replacement).  Instances of one zone are interchangeable, so the same distribution is drawn in two parts:
+ *   1. the zones of the k departures: draw i takes zone z with probability weight[z] * left[z] / total,
+ *      left[z] = instances of zone z still there; word i of sequence 0xFFFF, r = (word * total) >> 32,
+ *      zone = first z whose running sum of weight * left exceeds r;
+ *   2. which gone[z] instances of zone z: a uniform subset of the zone's members (ranks 0 .. size-1 in
+ *      ascending instance order) by Floyd's method on the smaller side, exactly as orc_sample_preempted
+ *      does on the whole pool, with the words of sequence z.
+ * With a single zone this is orc_sample_preempted bit for bit.
+ */
+void orc_sample_preempted_zoned(int M, int k, int n_zones, const uint8_t *zone, const uint32_t *weight,
+                                uint64_t seed, uint32_t stream_id, uint32_t unit, uint32_t s, uint8_t *preempted)
+{
+    int members[ORC_MAX_ZONES][ORC_MAX_INSTANCES];
+    int size[ORC_MAX_ZONES] = { 0, 0, 0, 0 }, left[ORC_MAX_ZONES], gone[ORC_MAX_ZONES] = { 0, 0, 0, 0 };
+    for (int j = 0; j < M; ++j) {
+        int z = zone[j];
+        members[z][size[z]++] = j;
+    }
+    for (int z = 0; z < n_zones; ++z) left[z] = size[z];
+    for (int i = 0; i < k; ++i) {
+        uint32_t total = 0u, running = 0u;
+        for (int z = 0; z < n_zones; ++z) total += weight[z] * (uint32_t)left[z];
+        uint32_t w = orc_word_at(seed, stream_id, unit, s, 0xFFFFu, (uint32_t)i);
+        uint32_t r = (uint32_t)(((uint64_t)w * (uint64_t)total) >> 32); /* in [0, total) */
+        for (int z = 0; z < n_zones; ++z) {
+            running += weight[z] * (uint32_t)left[z];
+            if (r < running) {
+                left[z] -= 1;
+                gone[z] += 1;
+                break;
+            }
+        }
+    }
+    memset(preempted, 0, (size_t)M);
+    for (int z = 0; z < n_zones; ++z) {
+        uint8_t chosen[ORC_MAX_INSTANCES];
+        int Mz = size[z], kz = gone[z];
+        int m = (kz < Mz - kz) ? kz : Mz - kz;
+        memset(chosen, 0, sizeof chosen);
+        for (int i = 0; i < m; ++i) {
+            int j = Mz - m + i;
+            uint32_t w = orc_word_at(seed, stream_id, unit, s, (uint32_t)z, (uint32_t)i);
+            uint32_t r = (uint32_t)(((uint64_t)w * (uint64_t)(j + 1)) >> 32);
+            if (chosen[r]) chosen[j] = 1; else chosen[r] = 1;
+        }
+        int complement = (kz > Mz - kz);
+        for (int rank = 0; rank < Mz; ++rank)
+            preempted[members[z][rank]] = complement ? (uint8_t)!chosen[rank] : chosen[rank];
+    }
 }
 
 /* ---------------------------------------------------------------- reducer */
@@ -157,10 +230,14 @@ void orc_expand_groups(int D, int P, int group, const uint8_t *instance_preempte
 }
 
 /* One scenario of a unit: which instances of the pool go (pool_pre[M]) and what is left of the D x P grid. */
-static void scenario(int D, int P, int group, int M, int k, uint64_t seed, uint32_t stream_id, uint32_t unit,
+static void scenario(int D, int P, int group, int M, int k, int n_zones, const uint8_t *zone,
+                     const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
                      uint32_t s, uint8_t *pool_pre, int *n_int, int *d_min)
 {
-    orc_sample_preempted(M, k, seed, stream_id, unit, s, pool_pre);
+    if (n_zones > 0 && zone && weight)
+        orc_sample_preempted_zoned(M, k, n_zones, zone, weight, seed, stream_id, unit, s, pool_pre);
+    else
+        orc_sample_preempted(M, k, seed, stream_id, unit, s, pool_pre);
     if (group <= 1) {
         orc_reduce(D, P, pool_pre, n_int, d_min, NULL);
     } else {
@@ -175,9 +252,11 @@ static void scenario(int D, int P, int group, int M, int k, uint64_t seed, uint3
  * (bit j of word j/32 = instance j of the pool preempted, 8 words per scenario;
  * instances D*P and up are idle ones) and the two per-scenario integers.
  * a_prev < 0 selects the used-instance pool.  With group > 1 the mask is over instances
- * of `group` GPUs each, n_int and d_min count GPU pipelines.
+ * of `group` GPUs each, n_int and d_min count GPU pipelines.  n_zones > 0 with zone[] (zone of every
+ * instance of the pool) and weight[] draws by orc_sample_preempted_zoned, otherwise uniformly.
  */
-void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, int n_zones, const uint8_t *zone,
+                      const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
                       uint32_t s0, uint32_t ns, uint32_t *masks, int32_t *n_int, int32_t *d_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
@@ -185,7 +264,7 @@ void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, uint64_t 
     unit_pool(D, P, group, a_prev, a_next, &M, &k);
     for (uint32_t x = 0; x < ns; ++x) {
         int ni, dm;
-        scenario(D, P, group, M, k, seed, stream_id, unit, s0 + x, pre, &ni, &dm);
+        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s0 + x, pre, &ni, &dm);
         for (int w = 0; w < 8; ++w) masks[x * 8u + (uint32_t)w] = 0u;
         for (int j = 0; j < M; ++j)
             if (pre[j]) masks[x * 8u + (uint32_t)(j / 32)] |= (1u << (j % 32));
@@ -199,7 +278,8 @@ void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, uint64_t 
  * a_prev < 0 selects the used-instance pool.
  * unit = t * C + c is the value that enters the random-word counter.
  */
-void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, uint64_t seed, uint32_t stream_id, uint32_t unit,
+void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, int n_zones, const uint8_t *zone,
+                   const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
                    uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
@@ -208,7 +288,7 @@ void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, uint64_t see
     for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; }
     for (uint32_t s = s_begin; s < s_end; ++s) {
         int ni, dm;
-        scenario(D, P, group, M, k, seed, stream_id, unit, s, pre, &ni, &dm);
+        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s, pre, &ni, &dm);
         bins_int[ni] += 1u;
         bins_min[dm] += 1u;
     }
@@ -221,10 +301,12 @@ void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, uint64_t see
  * Buffers are [T][off[C]] and are overwritten.  n_threads > 1 splits the
  * independent units over OpenMP threads (no effect on the integers).  pool_all != 0
  * draws the preemptions among all avail[t] instances instead of the used ones.
+ * n_zones > 0: zone[N] and weight[n_zones] select the non-uniform draw.
  */
 void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                    uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
-                   uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group)
+                   uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
+                   int n_zones, const uint8_t *zone, const uint32_t *weight)
 {
     const int L = thr_off[C];
     memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
@@ -243,7 +325,7 @@ void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off,
         uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
         for (uint32_t s = s_begin; s < s_end; ++s) {
             int ni, dm;
-            scenario(D, P, group, M, k, seed, stream_id, (uint32_t)u, s, pre, &ni, &dm);
+            scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, (uint32_t)u, s, pre, &ni, &dm);
             hi[ni] += 1u;
             hm[dm] += 1u;
         }

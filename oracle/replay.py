@@ -26,7 +26,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-from . import dp_f32, eval_hist, transition
+from . import batch_zones, dp_f32, eval_hist, transition
 
 PROACTIVE, REACTIVE = 0, 1
 _F = np.float32
@@ -111,6 +111,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
     thr_full = thr[off[1:] - 1]
     seed, stream = int(batch.seed[q]), int(batch.stream_id[q])
     H = len(windows)
+    zone, weight = batch_zones(batch, q)
     cur = int(batch.cur_config[q])
     chosen = np.zeros(H, np.int32)
     reward = np.zeros(H, np.float32)
@@ -119,7 +120,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
         a_now, a = int(true_avail[i]), int(true_avail[i + 1])
         if mode == PROACTIVE:
             win = np.asarray(windows[i], np.int32)
-            hi, hm = eval_hist(batch.configs, off, win, seed, (stream + 2 * i) & 0xFFFFFFFF, 0, S, n_threads, pool_all, group)
+            hi, hm = eval_hist(batch.configs, off, win, seed, (stream + 2 * i) & 0xFFFFFFFF, 0, S, n_threads, pool_all, group, zone, weight)
             _, W_f = transition(batch.configs, off, win, thr, cost, batch.interval_sec, S, batch.p_min,
                                 cur if cur >= 0 else -2, hi, hm, group)   # nothing running: cold start
             plan = dp_f32(W_f)
@@ -131,7 +132,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
         nxt = adapt(configs, batch.p_min, group, target, a, forecast)
         pair = np.asarray([a_now, a], np.int32)
         hi1, hm1 = eval_hist(batch.configs, off, pair, seed, (stream + 2 * i + 1) & 0xFFFFFFFF, 0, S, n_threads, pool_all,
-                             group)
+                             group, zone, weight)
         if cur >= 0:
             sl = slice(off[cur], off[cur + 1])
             r_f, r_d = transition_reward(configs, off, thr, cost, batch.interval_sec, S, cur, nxt, hi1[0, sl], hm1[0, sl])

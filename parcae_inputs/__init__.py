@@ -24,6 +24,7 @@ from typing import Dict, List, Sequence
 import numpy as np
 
 BASE_SEED = 0x240314097
+MAX_ZONES = 4
 _GOLDEN = 0x9E3779B97F4A7C15
 _MASK64 = (1 << 64) - 1
 
@@ -97,6 +98,8 @@ class ProblemBatch:
       stream_id   uint32 [nq]
       cur_config  int32  [nq]        index of the configuration running now, or -1
     group_size > 1: instances of that many GPUs; n_instances and avail then count instances, D * P counts GPUs.
+    n_zones > 0: preemption is not uniform; zone uint8 [nq, N] is the zone of every instance,
+    zone_weight uint32 [nq, 4] the hazard weight of every zone (entries at and above n_zones unused).
     """
 
     name: str
@@ -115,6 +118,9 @@ class ProblemBatch:
     cur_config: np.ndarray
     meta: dict = field(default_factory=dict)
     group_size: int = 1        # GPUs per instance (preempted together); availability counts instances
+    n_zones: int = 0           # 0: every instance equally likely to be preempted
+    zone: np.ndarray | None = None
+    zone_weight: np.ndarray | None = None
 
     @property
     def n_queries(self) -> int:
@@ -137,7 +143,31 @@ class ProblemBatch:
             np.ascontiguousarray(self.avail[idx]), np.ascontiguousarray(self.thr[idx]),
             np.ascontiguousarray(self.cost[idx]), np.ascontiguousarray(self.seed[idx]),
             np.ascontiguousarray(self.stream_id[idx]), np.ascontiguousarray(self.cur_config[idx]),
-            dict(self.meta), self.group_size)
+            dict(self.meta), self.group_size, self.n_zones,
+            None if self.zone is None else np.ascontiguousarray(self.zone[idx]),
+            None if self.zone_weight is None else np.ascontiguousarray(self.zone_weight[idx]))
+
+    def with_zones(self, n_zones: int, seed: int = 7, max_weight: int = 8) -> "ProblemBatch":
+        """Same inputs with the instances spread over zones of unequal preemption hazard.
+
+        Stand-in for a cluster that spans availability zones or instance types (section 4.1): per query the
+        zone shares are drawn from U[0.5, 1.5] and normalised, every instance falls into a zone by those
+        shares, and every zone gets an integer weight in [1, max_weight].
+        """
+        out = self.take(range(self.n_queries))
+        nq, N = self.n_queries, self.n_instances
+        zone = np.zeros((nq, N), dtype=np.uint8)
+        weight = np.ones((nq, MAX_ZONES), dtype=np.uint32)
+        for q in range(nq):
+            rng = SplitMix64(_mix64(BASE_SEED ^ (seed * 0x1000193 + q)))
+            share = np.asarray([rng.uniform(0.5, 1.5) for _ in range(n_zones)])
+            edges = np.cumsum(share / share.sum())
+            for j in range(N):
+                zone[q, j] = min(int(np.searchsorted(edges, rng.uniform(0.0, 1.0), side="right")), n_zones - 1)
+            for z in range(n_zones):
+                weight[q, z] = rng.randint(1, max_weight)
+        out.n_zones, out.zone, out.zone_weight = int(n_zones), zone, weight
+        return out
 
     def with_scenarios(self, n_scenarios: int) -> "ProblemBatch":
         """Same inputs with another scenario count (scenario s never depends on the count)."""

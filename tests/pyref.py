@@ -110,3 +110,40 @@ def exact_histograms_pool(D, P, pool, k):
         hm[b] += 1
         n += 1
     return hi, hm, n
+
+
+def successive_sampling_subset_probs(w, k):
+    """Exact probability of every k-subset when k items leave one after the other, each time one of the
+    remaining items with probability proportional to its weight w[j] (sum over the k! orders of departure)."""
+    M, total = len(w), float(sum(w))
+    probs = {}
+    for sub in itertools.combinations(range(M), k):
+        p = 0.0
+        for order in itertools.permutations(sub):
+            left, q = total, 1.0
+            for j in order:
+                q *= w[j] / left
+                left -= w[j]
+            p += q
+        probs[sub] = p
+    return probs
+
+
+def zone_count_distribution(sizes, weights, k):
+    """Exact distribution of how many of the k departures fall into each zone (urn process, by dynamic programming
+    over the numbers already gone per zone).  Returns {counts tuple: probability}."""
+    Z = len(sizes)
+    dist = {tuple([0] * Z): 1.0}
+    for _ in range(k):
+        nxt = {}
+        for gone, p in dist.items():
+            left = [sizes[z] - gone[z] for z in range(Z)]
+            total = float(sum(weights[z] * left[z] for z in range(Z)))
+            for z in range(Z):
+                if left[z] > 0:
+                    g = list(gone)
+                    g[z] += 1
+                    g = tuple(g)
+                    nxt[g] = nxt.get(g, 0.0) + p * weights[z] * left[z] / total
+        dist = nxt
+    return dist
