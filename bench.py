@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
-def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False):
+def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False, zoned=False):
     """Sum over units of S * A(M, k, P): the 32-bit lane operations the method itself needs.
 
     A(M, k, P) = 33 m + 2 P W + P + W (log2 P + 2) + 10 with M the pool, m = min(k, M - k) random words (25 operations for a
@@ -33,6 +33,9 @@ def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False):
     and + popcount per stage and word, a min per stage, an OR-fold per word for the untouched pipelines) and 10
     for the two histogram updates.  Units whose scenarios all land in one bin (k = 0, k = M, a single stage, or a
     single pipeline) have a closed form and count as zero.
+    With zones (non-uniform preemption) a scenario also draws the zone of each of its k departures: one more
+    random word (25) and a compare chain over the zones (12) per departure; the subset draws inside the zones
+    need at most m words together, which is what is counted.
     Returns (total lane-ops, scenarios of non-trivial units).
     """
     import numpy as np
@@ -52,7 +55,7 @@ def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False):
     fixed = 2 * Pb * W + Pb + W * (lg + 2) + 10
     grid_is_pool = M == used[None, None, :]
     sampled = (m > 0) & ~(grid_is_pool & ((P == 1) | (D == 1))[None, None, :])
-    A = np.where(sampled, 33 * m + fixed, 0)
+    A = np.where(sampled, 33 * m + fixed + (37 * k if zoned else 0), 0)
     return float(A.sum()) * n_scenarios, int(sampled.sum()) * n_scenarios
 
 
@@ -119,6 +122,8 @@ def main():
     ap.add_argument("--queries", type=int, default=None, help="override the number of queries in the batch")
     ap.add_argument("--pool-all", action="store_true",
                     help="draw preemptions among all available instances (idle ones included) instead of the used ones")
+    ap.add_argument("--zones", type=int, default=0,
+                    help="spread the instances over this many zones of unequal preemption hazard (0 = uniform)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -143,6 +148,8 @@ def main():
     pk.load_library()
 
     batch = pi.workload(args.workload, dense=args.dense, n_queries=args.queries)
+    if args.zones:
+        batch = batch.with_zones(args.zones)
     prob = pk.upload(batch, device="cuda:0")
     if args.pool_all:
         prob.flags = pk.PARCAE_POOL_ALL
@@ -151,7 +158,7 @@ def main():
     nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
     scenarios = nq * T * C * S
     cells = nq * T * C * C
-    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S, args.pool_all)
+    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S, args.pool_all, args.zones > 0)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
@@ -207,7 +214,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u32+f32",
         "data": "synthetic",
-        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
+        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else "") + (f"+zones{args.zones}" if args.zones else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
                    "n_configs": C, "n_scenarios": S, "scenarios_per_step": scenarios,
                    "nontrivial_scenarios_per_step": nontrivial, "dp_cells_per_step": cells,
                    "infeasible_queries": int((status != 0).sum())},

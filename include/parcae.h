@@ -72,6 +72,7 @@ extern "C" {
 #define PARCAE_MAX_INSTANCES 256        /* N limit: one preemption mask is 256 bits */
 #define PARCAE_MAX_SCENARIOS 16777216   /* S limit: counts stay exact in float      */
 #define PARCAE_MASK_WORDS 8
+#define PARCAE_MAX_ZONES 4
 
 /* parcae_problem.flags */
 #define PARCAE_POOL_USED 0u /* preemptions fall on the D * P instances the configuration uses (default) */
@@ -113,6 +114,11 @@ typedef struct parcae_problem {
     void *event_after_sampling;   /* hipEvent_t or NULL: recorded right after it       */
     int32_t group_size;           /* g, GPUs per instance, 0 or 1 = single-GPU instances,
                                      at most 64; see "Multi-GPU instances" below         */
+    int32_t n_zones;              /* 0 = every instance equally likely to be preempted;
+                                     1..PARCAE_MAX_ZONES: see "Non-uniform preemption"   */
+    const uint8_t *zone;          /* DEVICE [nq][N] zone of every instance (n_zones > 0)  */
+    const uint32_t *zone_weight;  /* DEVICE [nq][PARCAE_MAX_ZONES] hazard weight of every
+                                     zone, 1..255 for z < n_zones (n_zones > 0)           */
 } parcae_problem;
 
 /*
@@ -149,6 +155,25 @@ typedef struct parcae_problem {
  * i = 0..m-1: j = M - m + i, r = (word(i) * (j + 1)) >> 32 (64-bit product);
  * insert j if r is already in the set, else insert r.  The preempted set is
  * that set if k <= M - k, otherwise its complement in [0, M).
+ *
+ * Non-uniform preemption (section 5.1 lets better estimates replace the equal
+ * probabilities; section 4.1 names availability zones and instance types as
+ * what drives preemptions).  With n_zones > 0 instance j of the pool belongs to
+ * zone[q][j] < n_zones and the k preempted instances leave one after the other,
+ * each time one of the remaining instances with probability proportional to the
+ * weight of its zone (successive weighted sampling without replacement).
+ * Instances of one zone are interchangeable, so the set is drawn in two parts,
+ * word(x, i) being word i of the sequence with counter (s, x * 65536 + i / 4,
+ * t * C + c, stream_id) (the uniform draw above uses x = 0):
+ *   1. left[z] = members of zone z in [0, M), gone[z] = 0; for i = 0..k-1:
+ *      total = sum_z weight[z] * left[z], r = (word(0xFFFF, i) * total) >> 32,
+ *      z* = first z with r < sum_{z' <= z} weight[z'] * left[z'];
+ *      left[z*] -= 1, gone[z*] += 1;
+ *   2. per zone z, with its members ranked in ascending instance order: the
+ *      uniform draw above with M = members, k = gone[z] and word(z, i) gives the
+ *      ranks of the preempted members.
+ * One zone gives the uniform draw bit for bit.  Everything downstream
+ * (histograms, tables, weights, plan) is unchanged.
  *
  * Per scenario (section 5.2, section 7): occ_s = alive instances of stage s;
  * d_min = min over s of occ_s (pipelines that intra-stage re-routing can

@@ -23,6 +23,7 @@ PARCAE_EWORKSPACE = -2
 PARCAE_EHIP = -3
 PARCAE_EINFEASIBLE = -4
 PARCAE_MAX_INSTANCES = 256
+PARCAE_MAX_ZONES = 4
 PARCAE_POOL_USED = 0
 PARCAE_POOL_ALL = 1
 PARCAE_COLD_START = -2
@@ -55,7 +56,8 @@ class parcae_problem(ct.Structure):
         ("avail", ct.c_void_p), ("thr", ct.c_void_p), ("cost", ct.c_void_p), ("seed", ct.c_void_p),
         ("stream_id", ct.c_void_p), ("cur_config", ct.c_void_p),
         ("event_before_sampling", ct.c_void_p), ("event_after_sampling", ct.c_void_p),
-        ("group_size", ct.c_int32),
+        ("group_size", ct.c_int32), ("n_zones", ct.c_int32),
+        ("zone", ct.c_void_p), ("zone_weight", ct.c_void_p),
     ]
 
 
@@ -136,6 +138,9 @@ class Problem:
     cur_config: "object" = None   # int32 [nq] device, or None
     flags: int = 0                # PARCAE_POOL_USED or PARCAE_POOL_ALL
     group_size: int = 1           # GPUs per instance (preempted together)
+    n_zones: int = 0              # 0: uniform preemption; else zones of unequal hazard
+    zone: "object" = None         # uint8 [nq, N] device, zone of every instance
+    zone_weight: "object" = None  # int32 view of uint32 [nq, PARCAE_MAX_ZONES] device
     event_before_sampling: Optional[int] = None   # raw hipEvent_t handles, recorded around the sampling kernel
     event_after_sampling: Optional[int] = None
     _cfg_arr: object = field(default=None, repr=False)
@@ -163,7 +168,8 @@ class Problem:
             self.n_queries, self.n_instances, self.n_intervals, self.n_configs, self.n_scenarios, self.p_min,
             self.interval_sec, int(self.flags), ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
-            _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling, int(self.group_size))
+            _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling, int(self.group_size),
+            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight))
 
     def workspace(self):
         """Device workspace of the size the library asks for (allocated once per Problem)."""
@@ -199,6 +205,13 @@ def upload(batch, device="cuda:0", n_scenarios: Optional[int] = None) -> Problem
                                batch.n_scenarios if n_scenarios is None else n_scenarios, batch.configs, batch.avail,
                                batch.thr, batch.cost, batch.seed, batch.stream_id, batch.cur_config, device)
     prob.group_size = int(getattr(batch, "group_size", 1))
+    if int(getattr(batch, "n_zones", 0)) > 0:
+        torch = _require_gpu()
+        import numpy as np
+        prob.n_zones = int(batch.n_zones)
+        prob.zone = torch.from_numpy(np.array(batch.zone, dtype=np.uint8, order="C")).to(device)
+        prob.zone_weight = torch.from_numpy(
+            np.array(batch.zone_weight, dtype=np.uint32, order="C").view(np.int32)).to(device)
     return prob
 
 

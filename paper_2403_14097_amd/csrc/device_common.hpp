@@ -10,6 +10,7 @@ namespace parcae {
 
 constexpr int kWave = 64;
 constexpr int kMaxInstances = 256;
+constexpr int kMaxZones = 4;
 
 // One candidate configuration as the kernels see it (16 bytes, one vector load).
 struct CfgRec {
@@ -34,6 +35,9 @@ struct Batch {
     const uint64_t* seed;       // [nq]
     const uint32_t* stream_id;  // [nq] or null
     const int32_t* cur_config;  // [nq] or null
+    int32_t n_zones;              // 0: uniform preemption; else instances fall into zones of unequal hazard
+    const uint8_t* zone;          // [nq][N] zone of every instance, or null
+    const uint32_t* zone_weight;  // [nq][kMaxZones] hazard weight of every zone, or null
 };
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }

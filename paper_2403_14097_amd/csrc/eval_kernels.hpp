@@ -200,6 +200,112 @@ __device__ __forceinline__ void sample_mask_lds(Mask<NW>& mask, uint32_t* lds_co
     if (k > M - k) mask.complement(M);
 }
 
+// ------------------------------------------------------------------ non-uniform preemption (zones)
+
+// Zones of the pool of one unit, built once per work item by the wave that owns it (section 5.1: the
+// equal-probability assumption may be replaced; here instances fall into zones of unequal hazard weight and
+// leave by successive weighted sampling without replacement).
+struct ZoneCtx {
+    const uint8_t* perm;    // LDS [kMaxZones][256]: perm[z * 256 + r] = pool index of the r-th member of zone z
+    const uint32_t* zmask;  // LDS [kMaxZones][8]: members of zone z among the pool as a bit set
+    int size[kMaxZones];    // members of zone z in the pool
+    uint32_t weight[kMaxZones];
+};
+
+// All 64 lanes of the wave must be active.  perm and zmask are this wave's LDS tables.
+__device__ __forceinline__ ZoneCtx zone_setup(const Batch& b, int q, int M, uint8_t* perm, uint32_t* zmask)
+{
+    const int lane = lane_id();
+    const uint8_t* zq = b.zone + (int64_t)q * b.N;
+    ZoneCtx zc;
+    zc.perm = perm;
+    zc.zmask = zmask;
+    static_for<kMaxZones>([&](auto z) {
+        zc.size[z.value] = 0;
+        zc.weight[z.value] = z.value < b.n_zones ? b.zone_weight[(int64_t)q * kMaxZones + z.value] : 0u;
+    });
+    if (lane < kMaxZones * 8) zmask[lane] = 0u;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int j0 = 0; j0 < M; j0 += kWave) {
+        const int j = j0 + lane;
+        const int zj = j < M ? (int)zq[j] : -1;
+        static_for<kMaxZones>([&](auto z) {
+            const unsigned long long votes = __ballot(zj == z.value);
+            if (zj == z.value) perm[z.value * 256 + zc.size[z.value] + __popcll(votes & below)] = (uint8_t)j;
+            if (lane == 0) {
+                zmask[z.value * 8 + (j0 >> 5)] = (uint32_t)votes;
+                zmask[z.value * 8 + (j0 >> 5) + 1] = (uint32_t)(votes >> 32);
+            }
+            zc.size[z.value] += __popcll(votes);
+        });
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return zc;
+}
+
+// Preempted set of scenario s when preemption is not uniform.  Part 1 draws the zones of the k departures
+// (word sequence 0xFFFF): per lane the products weight * instances left of every zone, one compare chain
+// per draw.  Part 2 draws, per zone, which members go: Floyd's method on the ranks of the zone's members
+// (word sequence z), the smaller side, ranks mapped to pool indices through perm; lanes differ in how many
+// members of a zone go, so the loop runs to the largest count in the wave with the other lanes masked off.
+// The set is built in LDS ([word][lane], as in sample_mask_lds) whatever the pool size.
+template <int NW>
+__device__ __forceinline__ void sample_mask_zoned(Mask<NW>& mask, uint32_t* lds_col, int stride, const ZoneCtx& zc,
+                                                  int k, uint32_t s, uint32_t unit, uint32_t stream_id,
+                                                  const PhiloxKeys& ks)
+{
+    uint32_t left_w[kMaxZones], gone[kMaxZones];
+    static_for<kMaxZones>([&](auto z) {
+        left_w[z.value] = zc.weight[z.value] * (uint32_t)zc.size[z.value];
+        gone[z.value] = 0u;
+    });
+    for (int i0 = 0; i0 < k; i0 += 4) {
+        const Philox4 blk = philox4x32_10(s, 0xFFFF0000u + (uint32_t)(i0 >> 2), unit, stream_id, ks);
+        static_for<4>([&](auto x) {
+            if (i0 + x.value < k) {
+                const uint32_t c0 = left_w[0], c1 = c0 + left_w[1], c2 = c1 + left_w[2], total = c2 + left_w[3];
+                const uint32_t r = __umulhi(blk.x[x.value], total);
+                const bool lt0 = r < c0, lt1 = r < c1, lt2 = r < c2;
+                const bool pick[kMaxZones] = {lt0, lt1 && !lt0, lt2 && !lt1, !lt2};
+                static_for<kMaxZones>([&](auto z) {
+                    left_w[z.value] -= pick[z.value] ? zc.weight[z.value] : 0u;
+                    gone[z.value] += pick[z.value] ? 1u : 0u;
+                });
+            }
+        });
+    }
+    static_for<NW>([&](auto i) { lds_col[i.value * stride] = 0u; });
+    static_for<kMaxZones>([&](auto zi) {
+        constexpr int z = zi.value;
+        const int Mz = zc.size[z];
+        if (Mz > 0) {
+            const int kz = (int)gone[z];
+            const int rest = Mz - kz;
+            const int mz = kz < rest ? kz : rest;
+            const uint8_t* perm = zc.perm + z * 256;
+            for (int i0 = 0; __any(i0 < mz); i0 += 4) {
+                const Philox4 blk = philox4x32_10(s, ((uint32_t)z << 16) + (uint32_t)(i0 >> 2), unit, stream_id, ks);
+                static_for<4>([&](auto x) {
+                    const int i = i0 + x.value;
+                    if (i < mz) {
+                        const uint32_t j = (uint32_t)(Mz - mz + i);
+                        const uint32_t r = __umulhi(blk.x[x.value], j + 1u);
+                        const uint32_t pr = perm[r], pj = perm[j];
+                        const uint32_t old = lds_col[(pr >> 5) * (uint32_t)stride];
+                        const uint32_t put = ((old >> (pr & 31u)) & 1u) ? pj : pr;  // r already there: j goes in
+                        atomicOr(lds_col + (put >> 5) * (uint32_t)stride, 1u << (put & 31u));
+                    }
+                });
+            }
+            if (kz > rest) static_for<NW>([&](auto w) { lds_col[w.value * stride] ^= zc.zmask[z * 8 + w.value]; });
+        }
+    });
+    static_for<NW>([&](auto i) { mask.w[i.value] = lds_col[i.value * stride]; });
+}
+
 // ------------------------------------------------------------------ reducer
 
 // Bits at multiples of P inside a 32-bit word (P a power of two <= 32).
@@ -583,18 +689,20 @@ __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col,
     }
 }
 
-// One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.
-template <int NW>
+// One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.  zc: zones of the pool, or null for the
+// uniform draw.
+template <int NW, bool kZoned>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int M, int k, uint32_t unit,
                                                 uint32_t stream_id, const PhiloxKeys& ks, uint32_t s_begin,
                                                 uint32_t s_end, uint32_t* lds_col, uint32_t* bins_int,
-                                                uint32_t* bins_min)
+                                                uint32_t* bins_min, const ZoneCtx* zc)
 {
     const int rows = cr.D / group;  // pipelines of the instance grid
     for (uint32_t s = s_begin + (uint32_t)lane_id(); s < s_end; s += kWave) {
         int n_int, d_min;
         Mask<NW> mask;
-        draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
+        if constexpr (kZoned) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
+        else draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
         if (M > rows * cr.P) mask.keep_below(rows * cr.P);  // idle instances of the pool are not on the grid
         reduce_mask<NW>(mask, rows, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int * group, true);
@@ -605,6 +713,8 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
 // Persistent kernel: every wave pulls (unit, chunk) items from the work queue until it is empty, so waves never
 // wait for each other and units without sampling cost nothing here.  Item i is chunk i % n_chunks of
 // list[i / n_chunks]; a chunk is chunk_len consecutive scenarios.  Each wave owns a slice of the LDS bins.
+// kZoned selects the non-uniform draw (a kernel of its own, so the uniform one keeps its registers).
+template <bool kZoned>
 __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
@@ -612,6 +722,8 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     constexpr int kWaves = kEvalThreads / kWave;
     __shared__ uint32_t bins_all[kWaves][2 * (kMaxInstances + 1)];
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
+    __shared__ uint8_t zone_perm[kZoned ? kWaves : 1][kMaxZones * 256];
+    __shared__ uint32_t zone_mask[kZoned ? kWaves : 1][kMaxZones * 8];
     const int lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
     uint32_t* bins = bins_all[wave];
@@ -673,10 +785,12 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
         uint32_t s_end = s_begin + (uint32_t)chunk_len;
         s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
 
-        if (M <= 32) eval_unit_chunk<1>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else if (M <= 64) eval_unit_chunk<2>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else if (M <= 128) eval_unit_chunk<4>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
-        else eval_unit_chunk<8>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min);
+        ZoneCtx zc;
+        if constexpr (kZoned) zc = zone_setup(b, q, M, zone_perm[wave], zone_mask[wave]);
+        if (M <= 32) eval_unit_chunk<1, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+        else if (M <= 64) eval_unit_chunk<2, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+        else if (M <= 128) eval_unit_chunk<4, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+        else eval_unit_chunk<8, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -699,11 +813,12 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
 // One scenario through the same code path the histogram kernel takes for a unit of this size.
 template <int NW>
 __device__ __forceinline__ void debug_one(const CfgRec cr, int group, uint32_t* lds_col, int M, int k, uint32_t s, uint32_t unit,
-                                          uint32_t stream_id, const PhiloxKeys& ks, uint32_t* mask_out, int& n_int,
-                                          int& d_min)
+                                          uint32_t stream_id, const PhiloxKeys& ks, const ZoneCtx* zc,
+                                          uint32_t* mask_out, int& n_int, int& d_min)
 {
     Mask<NW> mask;
-    draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
+    if (zc) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
+    else draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
     static_for<8>([&](auto i) {
         if constexpr (i.value < NW) mask_out[i.value] = mask.w[i.value];
         else mask_out[i.value] = 0u;
@@ -722,11 +837,20 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
                                                                     int32_t* __restrict__ d_min_out)
 {
     __shared__ uint32_t lmask[8 * kEvalThreads];
+    __shared__ uint8_t zone_perm[kEvalThreads / kWave][kMaxZones * 256];
+    __shared__ uint32_t zone_mask[kEvalThreads / kWave][kMaxZones * 8];
     const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
-    if (x >= ns) return;
     const CfgRec cr = b.cfg[c];
     int M, k;
     unit_pool(b, q, t, cr.D, cr.P, M, k);
+    ZoneCtx zones;
+    const ZoneCtx* zc = nullptr;
+    if (b.n_zones > 0) {  // every lane takes part in building the tables, also those past the last scenario
+        const int wave = (int)threadIdx.x / kWave;
+        zones = zone_setup(b, q, M, zone_perm[wave], zone_mask[wave]);
+        zc = &zones;
+    }
+    if (x >= ns) return;
     const uint64_t seed = b.seed[q];
     const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
     const uint32_t stream_id = (b.stream_id ? b.stream_id[q] : 0u) + b.stream_offset;
@@ -734,10 +858,10 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     uint32_t* lds_col = lmask + threadIdx.x;
     uint32_t* out = masks + (size_t)x * 8;
     int n_int, d_min;
-    if (M <= 32) debug_one<1>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else if (M <= 64) debug_one<2>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else if (M <= 128) debug_one<4>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
-    else debug_one<8>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, out, n_int, d_min);
+    if (M <= 32) debug_one<1>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
+    else if (M <= 64) debug_one<2>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
+    else if (M <= 128) debug_one<4>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
+    else debug_one<8>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
     n_int_out[x] = n_int;
     d_min_out[x] = d_min;
 }

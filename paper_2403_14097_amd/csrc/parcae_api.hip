@@ -45,6 +45,8 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
     if (!(p->interval_sec > 0.0f) || !std::isfinite(p->interval_sec)) return PARCAE_EINVAL;
     if ((int64_t)p->n_configs * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     if (p->group_size < 0 || p->group_size > 64) return PARCAE_EINVAL;
+    if (p->n_zones < 0 || p->n_zones > PARCAE_MAX_ZONES) return PARCAE_EINVAL;
+    if (p->n_zones > 0 && (!p->zone || !p->zone_weight)) return PARCAE_EINVAL;
     const int group = p->group_size > 1 ? p->group_size : 1;
     int64_t L = 0;
     int max_row = 0;
@@ -107,6 +109,7 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     b.cfg = reinterpret_cast<const CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
     b.cur_config = p->cur_config;
+    b.n_zones = p->n_zones; b.zone = p->zone; b.zone_weight = p->zone_weight;
     return b;
 }
 
@@ -213,8 +216,12 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     if (p->event_before_sampling &&
         hipEventRecord(static_cast<hipEvent_t>(p->event_before_sampling), st) != hipSuccess)
         return PARCAE_EHIP;
-    parcae::eval_hist_kernel<<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
-        b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    if (b.n_zones > 0)
+        parcae::eval_hist_kernel<true><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
+            b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    else
+        parcae::eval_hist_kernel<false><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
+            b, wq, n_chunks, chunk_len, hist_int, hist_min);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     if (p->event_after_sampling &&
         hipEventRecord(static_cast<hipEvent_t>(p->event_after_sampling), st) != hipSuccess)

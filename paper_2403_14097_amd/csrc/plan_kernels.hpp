@@ -61,6 +61,14 @@ __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restr
         const int cur = b.cur_config[q];
         if (cur < -2 || cur >= b.C) my_bad = 1;
     }
+    if (b.n_zones > 0) {
+        for (int j = threadIdx.x; j < b.N; j += blockDim.x)
+            if ((int)b.zone[(int64_t)q * b.N + j] >= b.n_zones) my_bad = 1;
+        if ((int)threadIdx.x < b.n_zones) {
+            const uint32_t w = b.zone_weight[(int64_t)q * kMaxZones + threadIdx.x];
+            if (w < 1u || w > 255u) my_bad = 1;
+        }
+    }
     if (my_bad) atomicOr(&bad, 1);
     __syncthreads();
     if (threadIdx.x == 0) valid[q] = bad ? 0 : 1;

@@ -381,6 +381,138 @@ def test_grouped_instances_full_parity(pk, pool_all):
             assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
 
 
+# ------------------------------------------------------------------ non-uniform preemption (zones)
+
+def _with_zone_arrays(b, zone, weight):
+    b.n_zones = len(weight)
+    b.zone = np.ascontiguousarray(np.broadcast_to(np.asarray(zone, np.uint8), (b.n_queries, b.n_instances)))
+    w = np.ones((b.n_queries, pi.MAX_ZONES), np.uint32)
+    w[:, : len(weight)] = weight
+    b.zone_weight = w
+    return b
+
+
+def test_zoned_scenarios_one_by_one(pk):
+    """Weighted draws: every mask width, zones with no member in the pool, counts past the half, idle instances,
+    multi-GPU instances."""
+    rng = pi.SplitMix64(4242)
+    cases = [  # D, P, group, a_prev (-1: used pool), a_next, weights
+        (2, 3, 1, -1, 4, [1, 6]), (3, 4, 1, -1, 7, [5, 1, 2]), (8, 4, 1, -1, 20, [1, 2, 3, 4]), (4, 8, 1, -1, 6, [9, 1]),
+        (16, 4, 1, -1, 33, [1, 255, 7]), (8, 8, 1, -1, 60, [3, 3, 3, 3]), (2, 32, 1, -1, 31, [2, 1, 8]),
+        (16, 8, 1, -1, 100, [1, 4, 2, 9]), (4, 32, 1, -1, 20, [7, 2]), (32, 8, 1, -1, 128, [1, 3, 5, 7]),
+        (2, 128, 1, -1, 250, [4, 1, 1, 6]), (1, 256, 1, -1, 3, [1, 200, 30]), (5, 7, 1, -1, 18, [2, 5, 1]),
+        (11, 23, 1, -1, 140, [1, 9]), (3, 65, 1, -1, 111, [6, 1, 3]), (64, 1, 1, 80, 41, [1, 5]),
+        (3, 4, 1, 20, 13, [8, 1, 3]), (8, 16, 1, 200, 120, [1, 2, 4, 8]), (16, 4, 4, -1, 9, [1, 7]),
+        (8, 4, 2, 30, 22, [3, 1, 9]), (6, 2, 1, -1, 12, [1, 2]), (6, 2, 1, -1, 0, [1, 2]), (7, 9, 1, -1, 62, [1, 1, 1, 50]),
+    ]
+    for D, P, g, a_prev, a_next, weight in cases:
+        cfg = np.asarray([[D, P]], np.int32)
+        b = pi.custom_batch(256, cfg, [[max(a_prev, 0), a_next]], thr_per_pipeline=[1.0], n_scenarios=64, seed=17,
+                            group_size=g)
+        zone = [rng.randint(0, len(weight) - 1) for _ in range(256)]
+        if len(weight) == 4:
+            zone = [z if z != 2 or j > 40 else 0 for j, z in enumerate(zone)]   # zone 2 is empty in small pools
+        _with_zone_arrays(b, zone, weight)
+        b.stream_id[:] = 9
+        p = pk.upload(b)
+        if a_prev >= 0:
+            p.flags = pk.PARCAE_POOL_ALL
+        ns, s0 = 200, 31
+        masks, n_int, d_min = pk.parcae_debug_sample(p, 0, 0, 0, s0, ns)
+        _sync()
+        om, oi, od = oracle.debug_sample(D, P, a_next, int(b.seed[0]), 9, 0, s0, ns, a_prev=a_prev, group=g,
+                                         zone=b.zone[0], weight=weight)
+        assert np.array_equal(_np(masks, np.uint32), om), (D, P, g, a_prev, a_next)
+        assert np.array_equal(_np(n_int), oi) and np.array_equal(_np(d_min), od), (D, P, g, a_prev, a_next)
+
+
+def test_one_zone_gives_the_uniform_results(pk):
+    b = pi.workload("small", n_scenarios=600)
+    ev_u, pl_u = pk.parcae_liveput_plan(pk.upload(b))
+    z = _with_zone_arrays(pi.workload("small", n_scenarios=600), [0] * 32, [37])
+    ev_z, pl_z = pk.parcae_liveput_plan(pk.upload(z))
+    _sync()
+    assert np.array_equal(_np(ev_u.hist_int), _np(ev_z.hist_int)) and np.array_equal(_np(ev_u.hist_min), _np(ev_z.hist_min))
+    assert np.array_equal(_np(pl_u.plan), _np(pl_z.plan))
+
+
+@pytest.mark.parametrize("name,S,nq,pool_all", [("tiny", 256, 1, False), ("small", 1000, 1, False),
+                                                ("medium", 700, 1, True), ("large", 300, 1, False),
+                                                ("sweep", 500, 40, False), ("sweep", 300, 36, True)])
+def test_zoned_full_parity(pk, name, S, nq, pool_all):
+    b = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None).with_zones(3 if name != "large" else 4)
+    p = pk.upload(b)
+    if pool_all:
+        p.flags = pk.PARCAE_POOL_ALL
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in sorted({0, nq // 2, nq - 1}):
+        r = oracle.run_query(b, q, n_scenarios=S, n_threads=8, pool_all=pool_all)
+        assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int)
+        assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min)
+        assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f)
+        assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f)
+        assert np.all(np.abs(_np(ev.gain[q]) - r.tables.gain_d) <= REL * np.abs(r.tables.gain_d))
+        assert np.array_equal(_np(W[q]), r.W_f)
+        assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F)
+        assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
+    # the weights matter: the same batch without zones gives other histograms
+    u = pk.upload(pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None))
+    if pool_all:
+        u.flags = pk.PARCAE_POOL_ALL
+    ev_u = pk.parcae_liveput_eval(u)
+    _sync()
+    assert not np.array_equal(_np(ev_u.hist_min), _np(ev.hist_min))
+
+
+def test_zoned_full_size_sweep_sampled(pk):
+    """The 1024-query sweep at its full scenario count with three zones: sampled units against the oracle."""
+    b = pi.workload("sweep").with_zones(3)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    hi, hm = _np(ev.hist_int, np.uint32), _np(ev.hist_min, np.uint32)
+    T, C, S = b.n_intervals, b.n_configs, b.n_scenarios
+    assert np.all(hi.reshape(b.n_queries, T, -1).sum(axis=2) == C * S)
+    rng = pi.SplitMix64(99)
+    checked = 0
+    while checked < 24:
+        q, t, c = rng.randint(0, b.n_queries - 1), rng.randint(0, T - 1), rng.randint(0, C - 1)
+        D, P = (int(x) for x in b.configs[c])
+        k = max(0, D * P - int(b.avail[q, t + 1]))
+        if k == 0 or k == D * P:
+            continue
+        zone, weight = oracle.batch_zones(b, q)
+        oi, om = oracle.eval_unit(D, P, int(b.avail[q, t + 1]), int(b.seed[q]), int(b.stream_id[q]), t * C + c, 0, S,
+                                  zone=zone, weight=weight)
+        sl = slice(int(b.thr_off[c]), int(b.thr_off[c + 1]))
+        assert np.array_equal(hi[q, t, sl], oi) and np.array_equal(hm[q, t, sl], om), (q, t, c)
+        checked += 1
+    assert np.all(_np(pl.status) == 0)
+
+
+def test_invalid_zone_data_is_flagged_per_query(pk):
+    b = pi.workload("sweep", n_scenarios=128, n_queries=6).with_zones(3)
+    b.zone[1, 5] = 3            # zone index out of range
+    b.zone_weight[2, 1] = 0     # weight below 1
+    b.zone_weight[4, 0] = 256   # weight above 255
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    st = _np(pl.status)
+    assert list(st) == [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, 0, pk.PARCAE_EINVAL, 0]
+    r = oracle.run_query(b, 3, n_threads=4)
+    assert np.array_equal(_np(ev.hist_int[3], np.uint32), r.hist_int) and np.array_equal(_np(pl.plan[3]), r.plan.plan)
+    # host-visible errors
+    p.n_zones = 5
+    with pytest.raises(pk.ParcaeError):
+        pk.parcae_liveput_plan(p)
+    p.n_zones, p.zone = 3, None
+    with pytest.raises(pk.ParcaeError):
+        pk.parcae_liveput_plan(p)
+
+
 # ------------------------------------------------------------------ receding-horizon replay
 
 def _replay_inputs(b, H, noise_seed):
@@ -399,8 +531,8 @@ def _replay_inputs(b, H, noise_seed):
     return true, win
 
 
-@pytest.mark.parametrize("nq,pool_all", [(3, False), (40, False), (5, True)])
-def test_replay_matches_the_oracle_replay(pk, nq, pool_all):
+@pytest.mark.parametrize("nq,pool_all,zones", [(3, False, 0), (40, False, 0), (5, True, 0), (4, False, 3)])
+def test_replay_matches_the_oracle_replay(pk, nq, pool_all, zones):
     import torch
     from oracle import replay as rp
     spec = pi.WorkloadSpec("replay", nq, 64, 18, 60.0, (2, 4, 8, 16, 32), 4, 6, 16, 0.12, False, 2, 300)
@@ -410,6 +542,8 @@ def test_replay_matches_the_oracle_replay(pk, nq, pool_all):
     b_plan.n_intervals = 10                                   # look-ahead of the planner inside the replay
     b_plan.avail = np.ascontiguousarray(b.avail[:, :11])
     b_plan.cur_config[1 % nq] = -1                            # one query starts with nothing running
+    if zones:
+        b_plan = b_plan.with_zones(zones)
     true, win = _replay_inputs(b, H, 5)
     win = np.ascontiguousarray(win[:, :, :11])
     p = pk.upload(b_plan)
