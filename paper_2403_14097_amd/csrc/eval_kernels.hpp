@@ -257,26 +257,35 @@ __device__ __forceinline__ void sample_mask_zoned(Mask<NW>& mask, uint32_t* lds_
                                                   int k, uint32_t s, uint32_t unit, uint32_t stream_id,
                                                   const PhiloxKeys& ks)
 {
-    uint32_t left_w[kMaxZones], gone[kMaxZones];
+    // Part 1 without compares or selects (selects through the condition register are slow on this chip):
+    // all quantities stay below 2^31, so the sign of r - c is the outcome of r < c as an all-ones mask.
+    // below[j] counts the draws that fell into zones 0..j.
+    uint32_t left_w[kMaxZones], below[kMaxZones - 1], wv[kMaxZones];
     static_for<kMaxZones>([&](auto z) {
         left_w[z.value] = zc.weight[z.value] * (uint32_t)zc.size[z.value];
-        gone[z.value] = 0u;
+        wv[z.value] = in_vgpr(zc.weight[z.value]);
     });
+    static_for<kMaxZones - 1>([&](auto z) { below[z.value] = 0u; });
     for (int i0 = 0; i0 < k; i0 += 4) {
         const Philox4 blk = philox4x32_10(s, 0xFFFF0000u + (uint32_t)(i0 >> 2), unit, stream_id, ks);
         static_for<4>([&](auto x) {
             if (i0 + x.value < k) {
                 const uint32_t c0 = left_w[0], c1 = c0 + left_w[1], c2 = c1 + left_w[2], total = c2 + left_w[3];
                 const uint32_t r = __umulhi(blk.x[x.value], total);
-                const bool lt0 = r < c0, lt1 = r < c1, lt2 = r < c2;
-                const bool pick[kMaxZones] = {lt0, lt1 && !lt0, lt2 && !lt1, !lt2};
-                static_for<kMaxZones>([&](auto z) {
-                    left_w[z.value] -= pick[z.value] ? zc.weight[z.value] : 0u;
-                    gone[z.value] += pick[z.value] ? 1u : 0u;
-                });
+                const uint32_t m0 = (uint32_t)((int32_t)(r - c0) >> 31);  // all ones if r < c0
+                const uint32_t m1 = (uint32_t)((int32_t)(r - c1) >> 31);
+                const uint32_t m2 = (uint32_t)((int32_t)(r - c2) >> 31);
+                below[0] -= m0;
+                below[1] -= m1;
+                below[2] -= m2;
+                left_w[0] -= m0 & wv[0];
+                left_w[1] -= (m1 ^ m0) & wv[1];  // m0 implies m1 implies m2
+                left_w[2] -= (m2 ^ m1) & wv[2];
+                left_w[3] -= ~m2 & wv[3];
             }
         });
     }
+    const uint32_t gone[kMaxZones] = {below[0], below[1] - below[0], below[2] - below[1], (uint32_t)k - below[2]};
     static_for<NW>([&](auto i) { lds_col[i.value * stride] = 0u; });
     static_for<kMaxZones>([&](auto zi) {
         constexpr int z = zi.value;
@@ -715,7 +724,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
 // list[i / n_chunks]; a chunk is chunk_len consecutive scenarios.  Each wave owns a slice of the LDS bins.
 // kZoned selects the non-uniform draw (a kernel of its own, so the uniform one keeps its registers).
 template <bool kZoned>
-__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
+__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(kZoned ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {
