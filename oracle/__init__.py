@@ -155,8 +155,15 @@ class Tables:
     gain_f: np.ndarray
 
 
+def _rounds(cost_round):
+    if cost_round is None:
+        return None, None
+    r = np.ascontiguousarray(cost_round, dtype=np.float32)
+    return _p(r, ct.c_float), r
+
+
 def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, hist_min,
-             pool_all: bool = False, group: int = 1) -> Tables:
+             pool_all: bool = False, group: int = 1, cost_round=None) -> Tables:
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
     avail = np.ascontiguousarray(avail, dtype=np.int32)
@@ -167,8 +174,9 @@ def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, h
     C, T = configs.shape[0], avail.shape[0] - 1
     out = Tables(np.zeros((3, T, C)), np.zeros((T, C)), np.zeros((T, C)),
                  np.zeros((3, T, C), np.float32), np.zeros((T, C), np.float32), np.zeros((T, C), np.float32))
+    rp, _keep = _rounds(cost_round)
     lib().orc_finalise(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
-                       _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
+                       _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), rp, ct.c_float(tau),
                        ct.c_uint32(S), ct.c_int(1 if pool_all else 0), ct.c_int(group), _p(hi, ct.c_uint32),
                        _p(hm, ct.c_uint32), _p(out.liveput_d, ct.c_double), _p(out.teff_d, ct.c_double), _p(out.gain_d, ct.c_double),
                        _p(out.liveput_f, ct.c_float), _p(out.teff_f, ct.c_float), _p(out.gain_f, ct.c_float))
@@ -176,7 +184,7 @@ def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, h
 
 
 def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: int, cur_config: int,
-               hist_int, hist_min, group: int = 1):
+               hist_int, hist_min, group: int = 1, cost_round=None):
     """W[T][C][C] in double and in fixed-order float."""
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -188,8 +196,9 @@ def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: in
     C, T = configs.shape[0], avail.shape[0] - 1
     W_d = np.zeros((T, C, C), dtype=np.float64)
     W_f = np.zeros((T, C, C), dtype=np.float32)
+    rp, _keep = _rounds(cost_round)
     lib().orc_transition(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
-                         _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), ct.c_float(tau),
+                         _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), rp, ct.c_float(tau),
                          ct.c_uint32(S), ct.c_int(p_min), ct.c_int(cur_config), ct.c_int(group),
                          _p(hi, ct.c_uint32), _p(hm, ct.c_uint32), _p(W_d, ct.c_double), _p(W_f, ct.c_float))
     return W_d, W_f
@@ -248,6 +257,12 @@ def batch_zones(batch, q: int):
     return zone[q], batch.zone_weight[q][: int(batch.n_zones)]
 
 
+def batch_rounds(batch, q: int):
+    """cost_round[C] of query q, or None when inter-stage migrations have one fixed cost."""
+    r = getattr(batch, "cost_round", None)
+    return None if r is None else r[q]
+
+
 def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int = 1, want_plan: bool = True,
               pool_all: bool = False) -> QueryResult:
     """Whole path for query q of a batch object that carries the input arrays."""
@@ -256,10 +271,11 @@ def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int =
     zone, weight = batch_zones(batch, q)
     hi, hm = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
                        0, S, n_threads, pool_all, group, zone, weight)
+    rounds = batch_rounds(batch, q)
     tab = finalise(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                   batch.interval_sec, S, hi, hm, pool_all, group)
+                   batch.interval_sec, S, hi, hm, pool_all, group, rounds)
     if not want_plan:
         return QueryResult(hi, hm, tab, None, None, None, float("nan"))
     W_d, W_f = transition(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm, group)
+                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm, group, rounds)
     return QueryResult(hi, hm, tab, W_d, W_f, dp_f32(W_f), dp_f64(W_d))

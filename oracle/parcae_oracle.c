@@ -356,6 +356,64 @@ static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int widt
 }
 
 /*
+ * Expected effective seconds of a unit read at a same-depth target of width `width` with the target's cost row
+ * co = (intra, inter, re-partition): interval length minus the migration cost of the scenario's class, not below
+ * zero, averaged over the S scenarios (Eq. 4: T_eff = T - T_mig).
+ *
+ * round_sec == 0: every inter-stage migration costs co[1].
+ * round_sec > 0 (section 8.4: the state-transfer part of the cost varies with the preemption scenario and follows
+ * an alpha-beta communication model): a stage with j survivors has to bring `width` instances to hold its state;
+ * every instance that holds it passes it on to one more per round, the stages work in parallel, so the worst
+ * stage (j = d_min) sets the number of rounds r = smallest r with d_min * 2^r >= width, and the migration costs
+ * co[1] + round_sec * (r - 1), capped by the re-partition cost co[2] (one can always re-partition instead).
+ * Float order: ((n0 * tau + n1 * e_intra) + inter) + n3 * e_repartition, inter = sum over r = 1..8 ascending of
+ * (float)count_r * e_r, each product and sum rounded separately; one division by S.
+ */
+static void effective_seconds(const uint32_t *hi, const uint32_t *hm, int D, int width, uint32_t S, float tau,
+                              const float *co, float round_sec, double *out_d, float *out_f)
+{
+    uint32_t n[4];
+    class_counts(hi, hm, D, width, S, n);
+    double e_d[3];
+    float e_f[3];
+    for (int x = 0; x < 3; ++x) {
+        e_d[x] = dmax0((double)tau - (double)co[x]);
+        e_f[x] = fmax0(tau - co[x]);
+    }
+    double inter_d;
+    float inter_f;
+    if (round_sec == 0.0f) {
+        inter_d = (double)n[2] * e_d[1];
+        inter_f = (float)n[2] * e_f[1];
+    } else {
+        uint32_t by_rounds[9] = { 0, 0, 0, 0, 0, 0, 0, 0, 0 };
+        for (int j = 1; j <= D && j < width; ++j) { /* inter-stage scenarios: 1 <= d_min < width */
+            int r = 0;
+            while ((j << r) < width) ++r;
+            by_rounds[r] += hm[j];
+        }
+        inter_d = 0.0;
+        inter_f = 0.0f;
+        for (int r = 1; r <= 8; ++r) {
+            double cost_d = (double)co[1] + (double)round_sec * (double)(r - 1);
+            if (cost_d > (double)co[2]) cost_d = (double)co[2];
+            float extra = round_sec * (float)(r - 1);
+            float cost_f = co[1] + extra;
+            if (cost_f > co[2]) cost_f = co[2];
+            inter_d += (double)by_rounds[r] * dmax0((double)tau - cost_d);
+            float term = (float)by_rounds[r] * fmax0(tau - cost_f);
+            inter_f = inter_f + term;
+        }
+    }
+    *out_d = ((double)n[0] * (double)tau + (double)n[1] * e_d[0] + inter_d + (double)n[3] * e_d[2]) / (double)S;
+    float q0 = (float)n[0] * tau, q1 = (float)n[1] * e_f[0], q3 = (float)n[3] * e_f[2];
+    float sum = q0 + q1;
+    sum = sum + inter_f;
+    sum = sum + q3;
+    *out_f = sum / (float)S;
+}
+
+/*
  * Liveput tables of one query (Definition 1 / Eq. 1 and Eq. 4) from histograms
  * taken over S scenarios.  Levels: 0 = no migration (only untouched pipelines
  * run), 1 = intra-stage re-routing only, 2 = all live migrations (as many
@@ -363,12 +421,14 @@ static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int widt
  * teff = expected effective seconds (interval minus the class's migration
  * cost, not below zero) when the configuration keeps its depth through the
  * boundary; gain = throughput after migration times teff.
+ * cost_round: [C] seconds per further state-transfer round of an inter-stage
+ * migration into each configuration, or NULL (see effective_seconds).
  * Outputs: liveput [3][T][C], teff [T][C], gain [T][C], each in double (*_d)
  * and in the fixed float order (*_f).
  */
 void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
-                  const float *thr, const float *cost, float tau, uint32_t S, int pool_all, int group,
-                  const uint32_t *hist_int, const uint32_t *hist_min,
+                  const float *thr, const float *cost, const float *cost_round, float tau, uint32_t S, int pool_all,
+                  int group, const uint32_t *hist_int, const uint32_t *hist_min,
                   double *liveput_d, double *teff_d, double *gain_d,
                   float *liveput_f, float *teff_f, float *gain_f)
 {
@@ -403,22 +463,9 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
             liveput_f[1 * lvl + o] = b_f / (float)S;
             liveput_f[2 * lvl + o] = th[d_star];
 
-            uint32_t n[4];
-            class_counts(hi, hm, D, d_star, S, n);
-            double e_d[3];
-            float e_f[3];
-            for (int x = 0; x < 3; ++x) {
-                e_d[x] = dmax0((double)tau - (double)co[x]);
-                e_f[x] = fmax0(tau - co[x]);
-            }
-            double td = ((double)n[0] * (double)tau + (double)n[1] * e_d[0] + (double)n[2] * e_d[1]
-                         + (double)n[3] * e_d[2]) / (double)S;
-            float q0 = (float)n[0] * tau, q1 = (float)n[1] * e_f[0];
-            float q2 = (float)n[2] * e_f[1], q3 = (float)n[3] * e_f[2];
-            float sum = q0 + q1;
-            sum = sum + q2;
-            sum = sum + q3;
-            float tf = sum / (float)S;
+            double td;
+            float tf;
+            effective_seconds(hi, hm, D, d_star, S, tau, co, cost_round ? cost_round[c] : 0.0f, &td, &tf);
             teff_d[o] = td;
             teff_f[o] = tf;
             gain_d[o] = (double)th[d_star] * td;
@@ -442,8 +489,9 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
  * Both outputs are [T][C][C], row c, column c' contiguous.
  */
 void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
-                    const float *thr, const float *cost, float tau, uint32_t S, int p_min, int cur_config, int group,
-                    const uint32_t *hist_int, const uint32_t *hist_min, double *W_d, float *W_f)
+                    const float *thr, const float *cost, const float *cost_round, float tau, uint32_t S, int p_min,
+                    int cur_config, int group, const uint32_t *hist_int, const uint32_t *hist_min, double *W_d,
+                    float *W_f)
 {
     const int L = thr_off[C];
     for (int t = 0; t < T; ++t) {
@@ -481,23 +529,10 @@ void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off
                     W_f[o] = full * fmax0(tau - co[2]);
                     continue;
                 }
-                uint32_t n[4];
                 /* a target wider than the source (D2 > D) sums over no bins: nothing is kept or re-routed */
-                class_counts(hi, hm, D, D2, S, n);
-                double e_d[3];
-                float e_f[3];
-                for (int x = 0; x < 3; ++x) {
-                    e_d[x] = dmax0((double)tau - (double)co[x]);
-                    e_f[x] = fmax0(tau - co[x]);
-                }
-                double td = ((double)n[0] * (double)tau + (double)n[1] * e_d[0] + (double)n[2] * e_d[1]
-                             + (double)n[3] * e_d[2]) / (double)S;
-                float q0 = (float)n[0] * tau, q1 = (float)n[1] * e_f[0];
-                float q2 = (float)n[2] * e_f[1], q3 = (float)n[3] * e_f[2];
-                float sum = q0 + q1;
-                sum = sum + q2;
-                sum = sum + q3;
-                float tf = sum / (float)S;
+                double td;
+                float tf;
+                effective_seconds(hi, hm, D, D2, S, tau, co, cost_round ? cost_round[c2] : 0.0f, &td, &tf);
                 W_d[o] = (double)full * td;
                 W_f[o] = full * tf;
             }

@@ -26,7 +26,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-from . import batch_zones, dp_f32, eval_hist, transition
+from . import batch_rounds, batch_zones, dp_f32, eval_hist, transition
 
 PROACTIVE, REACTIVE = 0, 1
 _F = np.float32
@@ -72,8 +72,11 @@ def adapt(configs, p_min, group, target, a, a_forecast):
     return -1
 
 
-def transition_reward(configs, thr_off, thr, cost, tau, S, cur, nxt, bins_int, bins_min):
-    """Expected committed samples of cur -> nxt in float (the library's operation order) and in double."""
+def transition_reward(configs, thr_off, thr, cost, tau, S, cur, nxt, bins_int, bins_min, round_sec=0.0):
+    """Expected committed samples of cur -> nxt in float (the library's operation order) and in double.
+
+    round_sec > 0: an inter-stage migration with d_min survivors in its worst stage needs r rounds of state
+    transfer (d_min * 2^r >= width) and costs inter + round_sec * (r - 1), at most the re-partition cost."""
     if nxt < 0:
         return _F(0.0), 0.0
     full = thr[thr_off[nxt] + configs[nxt][0]]
@@ -86,11 +89,26 @@ def transition_reward(configs, thr_off, thr, cost, tau, S, cur, nxt, bins_int, b
     n01 = int(bins_min[w:D + 1].sum()) if w <= D else 0
     n3 = int(bins_min[0])
     n1, n2 = n01 - n0, S - n01 - n3
+    if float(round_sec) == 0.0:
+        inter, inter_d = _F(_F(n2) * e[1]), n2 * e_d[1]
+    else:
+        by_rounds = [0] * 9
+        for j in range(1, min(D, w - 1) + 1):
+            r = 0
+            while (j << r) < w:
+                r += 1
+            by_rounds[r] += int(bins_min[j])
+        inter, inter_d = _F(0.0), 0.0
+        for r in range(1, 9):
+            c_f = min(_F(cost[nxt][1] + _F(_F(round_sec) * _F(r - 1))), cost[nxt][2])
+            c_d = min(float(cost[nxt][1]) + float(round_sec) * (r - 1), float(cost[nxt][2]))
+            inter = _F(inter + _F(_F(by_rounds[r]) * max(_F(0.0), _F(_F(tau) - c_f))))
+            inter_d += by_rounds[r] * max(0.0, float(tau) - c_d)
     num = _F(_F(_F(n0) * _F(tau)) + _F(_F(n1) * e[0]))
-    num = _F(num + _F(_F(n2) * e[1]))
+    num = _F(num + inter)
     num = _F(num + _F(_F(n3) * e[2]))
     teff = _F(num / _F(S))
-    teff_d = (n0 * float(tau) + n1 * e_d[0] + n2 * e_d[1] + n3 * e_d[2]) / S
+    teff_d = (n0 * float(tau) + n1 * e_d[0] + inter_d + n3 * e_d[2]) / S
     return _F(full * teff), float(full) * teff_d
 
 
@@ -112,6 +130,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
     seed, stream = int(batch.seed[q]), int(batch.stream_id[q])
     H = len(windows)
     zone, weight = batch_zones(batch, q)
+    rounds = batch_rounds(batch, q)
     cur = int(batch.cur_config[q])
     chosen = np.zeros(H, np.int32)
     reward = np.zeros(H, np.float32)
@@ -122,7 +141,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
             win = np.asarray(windows[i], np.int32)
             hi, hm = eval_hist(batch.configs, off, win, seed, (stream + 2 * i) & 0xFFFFFFFF, 0, S, n_threads, pool_all, group, zone, weight)
             _, W_f = transition(batch.configs, off, win, thr, cost, batch.interval_sec, S, batch.p_min,
-                                cur if cur >= 0 else -2, hi, hm, group)   # nothing running: cold start
+                                cur if cur >= 0 else -2, hi, hm, group, rounds)   # nothing running: cold start
             plan = dp_f32(W_f)
             target = int(plan.plan[0]) if plan.feasible else cur
             forecast = int(win[1])
@@ -135,7 +154,8 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
                              group, zone, weight)
         if cur >= 0:
             sl = slice(off[cur], off[cur + 1])
-            r_f, r_d = transition_reward(configs, off, thr, cost, batch.interval_sec, S, cur, nxt, hi1[0, sl], hm1[0, sl])
+            r_f, r_d = transition_reward(configs, off, thr, cost, batch.interval_sec, S, cur, nxt, hi1[0, sl], hm1[0, sl],
+                                         0.0 if rounds is None or nxt < 0 else rounds[nxt])
         else:
             r_f, r_d = transition_reward(configs, off, thr, cost, batch.interval_sec, S, cur, nxt, None, None)
         chosen[i], reward[i] = nxt, r_f

@@ -100,6 +100,7 @@ class ProblemBatch:
     group_size > 1: instances of that many GPUs; n_instances and avail then count instances, D * P counts GPUs.
     n_zones > 0: preemption is not uniform; zone uint8 [nq, N] is the zone of every instance,
     zone_weight uint32 [nq, 4] the hazard weight of every zone (entries at and above n_zones unused).
+    cost_round float32 [nq, C] (optional): seconds per further state-transfer round of an inter-stage migration.
     """
 
     name: str
@@ -121,6 +122,7 @@ class ProblemBatch:
     n_zones: int = 0           # 0: every instance equally likely to be preempted
     zone: np.ndarray | None = None
     zone_weight: np.ndarray | None = None
+    cost_round: np.ndarray | None = None   # float32 [nq, C] seconds per further state-transfer round, or None
 
     @property
     def n_queries(self) -> int:
@@ -145,7 +147,21 @@ class ProblemBatch:
             np.ascontiguousarray(self.stream_id[idx]), np.ascontiguousarray(self.cur_config[idx]),
             dict(self.meta), self.group_size, self.n_zones,
             None if self.zone is None else np.ascontiguousarray(self.zone[idx]),
-            None if self.zone_weight is None else np.ascontiguousarray(self.zone_weight[idx]))
+            None if self.zone_weight is None else np.ascontiguousarray(self.zone_weight[idx]),
+            None if self.cost_round is None else np.ascontiguousarray(self.cost_round[idx]))
+
+    def with_rounds(self, lo: float = 2.0, hi: float = 8.0, seed: int = 11) -> "ProblemBatch":
+        """Same inputs with a per-candidate cost of every further state-transfer round of an inter-stage
+        migration, drawn from U[lo, hi] seconds (the state-transfer share of the cost, which section 8.4 and
+        appendix A put at up to a minute)."""
+        out = self.take(range(self.n_queries))
+        rounds = np.zeros((self.n_queries, self.n_configs), dtype=np.float32)
+        for q in range(self.n_queries):
+            rng = SplitMix64(_mix64(BASE_SEED ^ (seed * 0x9E3779B1 + q)))
+            for c in range(self.n_configs):
+                rounds[q, c] = np.float32(rng.uniform(lo, hi))
+        out.cost_round = rounds
+        return out
 
     def with_zones(self, n_zones: int, seed: int = 7, max_weight: int = 8) -> "ProblemBatch":
         """Same inputs with the instances spread over zones of unequal preemption hazard.
