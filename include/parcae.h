@@ -119,6 +119,9 @@ typedef struct parcae_problem {
     const uint8_t *zone;          /* DEVICE [nq][N] zone of every instance (n_zones > 0)  */
     const uint32_t *zone_weight;  /* DEVICE [nq][PARCAE_MAX_ZONES] hazard weight of every
                                      zone, 1..255 for z < n_zones (n_zones > 0)           */
+    const float *cost_round;      /* DEVICE [nq][C] or NULL (= 0): seconds per further
+                                     state-transfer round of an inter-stage migration INTO
+                                     configuration c, finite, >= 0; see "Transfer rounds"  */
 } parcae_problem;
 
 /*
@@ -194,6 +197,20 @@ typedef struct parcae_problem {
  *                        + (float)n3 * e_2) / (float)S
  * evaluated in float exactly in this order, every product and sum rounded
  * separately (no fused multiply-add), one correctly rounded division.
+ *
+ * Transfer rounds (section 8.4: the state-transfer part of the migration cost
+ * varies with the preemption scenario and follows an alpha-beta model).  With
+ * b = cost_round[q][c'] > 0 an inter-stage migration to width w costs
+ * min(cost[.][2], cost[.][1] + b * (r - 1)), r = smallest r with d_min * 2^r >= w:
+ * a stage with d_min survivors brings w instances to hold its state by
+ * doubling, every holder serving one more instance per round; the stages work
+ * in parallel, so the worst stage decides.  teff then replaces (float)n2 * e_1 by
+ *   inter = sum over r = 1, 2, .. (ascending, from 0.0f, products and sums
+ *           rounded separately) of (float)n_r * max(0, tau - cost_r),
+ *   n_r = sum of hist_min[j] over 1 <= j <= D with ceil(w / 2^r) <= j < ceil(w / 2^(r-1)),
+ *   cost_r = min(cost[.][2], cost[.][1] + b * (float)(r - 1)) in float,
+ * and teff = (((float)n0 * tau + (float)n1 * e_0) + inter + (float)n3 * e_2) / (float)S.
+ * With b == 0 (or cost_round NULL) the formula above applies unchanged.
  *
  * Liveput tables (Eq. 1, Eq. 4), all float, sums in ascending bin order,
  * acc = acc + (float)count * thr (product and sum rounded separately):

@@ -57,7 +57,7 @@ class parcae_problem(ct.Structure):
         ("stream_id", ct.c_void_p), ("cur_config", ct.c_void_p),
         ("event_before_sampling", ct.c_void_p), ("event_after_sampling", ct.c_void_p),
         ("group_size", ct.c_int32), ("n_zones", ct.c_int32),
-        ("zone", ct.c_void_p), ("zone_weight", ct.c_void_p),
+        ("zone", ct.c_void_p), ("zone_weight", ct.c_void_p), ("cost_round", ct.c_void_p),
     ]
 
 
@@ -141,6 +141,7 @@ class Problem:
     n_zones: int = 0              # 0: uniform preemption; else zones of unequal hazard
     zone: "object" = None         # uint8 [nq, N] device, zone of every instance
     zone_weight: "object" = None  # int32 view of uint32 [nq, PARCAE_MAX_ZONES] device
+    cost_round: "object" = None   # float32 [nq, C] device: seconds per further transfer round, or None
     event_before_sampling: Optional[int] = None   # raw hipEvent_t handles, recorded around the sampling kernel
     event_after_sampling: Optional[int] = None
     _cfg_arr: object = field(default=None, repr=False)
@@ -169,7 +170,7 @@ class Problem:
             self.interval_sec, int(self.flags), ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
             _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling, int(self.group_size),
-            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight))
+            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight), _ptr(self.cost_round))
 
     def workspace(self):
         """Device workspace of the size the library asks for (allocated once per Problem)."""
@@ -212,6 +213,10 @@ def upload(batch, device="cuda:0", n_scenarios: Optional[int] = None) -> Problem
         prob.zone = torch.from_numpy(np.array(batch.zone, dtype=np.uint8, order="C")).to(device)
         prob.zone_weight = torch.from_numpy(
             np.array(batch.zone_weight, dtype=np.uint32, order="C").view(np.int32)).to(device)
+    if getattr(batch, "cost_round", None) is not None:
+        torch = _require_gpu()
+        import numpy as np
+        prob.cost_round = torch.from_numpy(np.array(batch.cost_round, dtype=np.float32, order="C")).to(device)
     return prob
 
 

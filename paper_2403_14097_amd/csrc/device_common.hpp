@@ -38,6 +38,7 @@ struct Batch {
     int32_t n_zones;              // 0: uniform preemption; else instances fall into zones of unequal hazard
     const uint8_t* zone;          // [nq][N] zone of every instance, or null
     const uint32_t* zone_weight;  // [nq][kMaxZones] hazard weight of every zone, or null
+    const float* cost_round;      // [nq][C] seconds per further state-transfer round of an inter-stage migration, or null
 };
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }

@@ -110,6 +110,7 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     b.avail = p->avail; b.thr = p->thr; b.cost = p->cost; b.seed = p->seed; b.stream_id = p->stream_id;
     b.cur_config = p->cur_config;
     b.n_zones = p->n_zones; b.zone = p->zone; b.zone_weight = p->zone_weight;
+    b.cost_round = p->cost_round;
     return b;
 }
 

@@ -31,6 +31,43 @@ __device__ __forceinline__ float teff_from_counts(uint32_t n0, uint32_t n01, uin
     return __fdiv_rn(sum, (float)S);
 }
 
+// Inter-stage share of the expected effective seconds when the cost of an inter-stage migration depends on
+// the scenario (section 8.4: the state-transfer cost varies with the preemptions, alpha-beta model): a stage with
+// j survivors brings w instances to hold its state by doubling, the worst stage (j = d_min) sets the number of
+// rounds r (smallest r with j * 2^r >= w), the migration costs c_inter + round_sec * (r - 1), at most c_repart.
+// tail(x) = scenarios with d_min >= x (x >= 1).  Sum over r ascending of (float)count_r * max(0, tau - cost_r);
+// bands past the one that reaches j = 1 are empty and would add +0.
+template <typename Tail>
+__device__ __forceinline__ float inter_seconds_by_rounds(Tail tail, int w, float tau, float c_inter, float c_repart,
+                                                         float round_sec)
+{
+    float acc = 0.0f;
+    if (w < 2) return acc;
+    uint32_t above = tail(w);  // scenarios that need no inter-stage migration at this width
+    for (int r = 1; r <= 8; ++r) {
+        const int lo = (w + (1 << r) - 1) >> r;  // smallest j with j * 2^r >= w
+        const uint32_t from_lo = tail(lo);
+        float cost = __fadd_rn(c_inter, __fmul_rn(round_sec, (float)(r - 1)));
+        cost = cost > c_repart ? c_repart : cost;
+        acc = __fadd_rn(acc, __fmul_rn((float)(from_lo - above), max0(__fsub_rn(tau, cost))));
+        above = from_lo;
+        if (lo <= 1) break;
+    }
+    return acc;
+}
+
+// teff with the inter-stage share given as a sum of seconds (see the header's teff() with transfer rounds).
+__device__ __forceinline__ float teff_with_inter(uint32_t n0, uint32_t n01, uint32_t h0, int w, uint32_t S, float tau,
+                                                 float e0, float e2, float inter)
+{
+    const uint32_t n1 = n01 - n0;
+    const uint32_t n3 = (w >= 1) ? h0 : 0u;
+    float sum = __fadd_rn(__fmul_rn((float)n0, tau), __fmul_rn((float)n1, e0));
+    sum = __fadd_rn(sum, inter);
+    sum = __fadd_rn(sum, __fmul_rn((float)n3, e2));
+    return __fdiv_rn(sum, (float)S);
+}
+
 // ------------------------------------------------------------------ input checks
 
 // valid[q] = 1 if the query's device inputs obey the documented ranges, else 0.  One block per query.
@@ -60,6 +97,12 @@ __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restr
     if (threadIdx.x == 0 && b.cur_config) {
         const int cur = b.cur_config[q];
         if (cur < -2 || cur >= b.C) my_bad = 1;
+    }
+    if (b.cost_round) {
+        for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+            const float v = b.cost_round[(int64_t)q * b.C + c];
+            if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
+        }
     }
     if (b.n_zones > 0) {
         for (int j = threadIdx.x; j < b.N; j += blockDim.x)
@@ -121,8 +164,21 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
     }
     const float fS = (float)S;
     const float full = th[d_star];
-    const float te = teff_from_counts(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
-                                      max0(__fsub_rn(b.tau, co[1])), max0(__fsub_rn(b.tau, co[2])));
+    const float round_sec = b.cost_round ? b.cost_round[(int64_t)q * b.C + c] : 0.0f;
+    float te;
+    if (round_sec == 0.0f) {
+        te = teff_from_counts(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
+                              max0(__fsub_rn(b.tau, co[1])), max0(__fsub_rn(b.tau, co[2])));
+    } else {
+        auto tail = [&](int x) {
+            uint32_t sum = 0u;
+            for (int j = x; j <= cr.D; ++j) sum += hm[j];
+            return sum;
+        };
+        const float inter = inter_seconds_by_rounds(tail, d_star, b.tau, co[1], co[2], round_sec);
+        te = teff_with_inter(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
+                             max0(__fsub_rn(b.tau, co[2])), inter);
+    }
     const int64_t lvl = (int64_t)b.T * b.C;
     const int64_t o = (int64_t)t * b.C + c;
     if (liveput) {
@@ -144,6 +200,7 @@ struct PlanShared {
     CfgRec* cfg;         // [C]
     float* full;         // [C] thr[c][D_c]
     float* e;            // [C][3] max(0, tau - cost)
+    float* rnd;          // [C][3] inter-stage cost, re-partition cost, seconds per further transfer round
     int* from_ok;        // [C] may be left at this step
     int* to_ok;          // [C] may be entered at this step
     int* chunk_start;    // [n_chunks + 1] first candidate of each chunk
@@ -162,7 +219,7 @@ constexpr uint16_t kNoPred16 = 0xffffu;
 
 inline size_t plan_lds_bytes(int C, int cap, size_t bp16_bytes)
 {
-    return 56 * (size_t)C + 16 + 8 * (size_t)cap + ((bp16_bytes + 15) & ~(size_t)15);
+    return 68 * (size_t)C + 16 + 8 * (size_t)cap + ((bp16_bytes + 15) & ~(size_t)15);
 }
 
 __device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool bp_in_lds, PlanShared& sh)
@@ -171,6 +228,7 @@ __device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool 
     sh.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
     sh.full = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
     sh.e = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
+    sh.rnd = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
     sh.from_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
     sh.to_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
     sh.chunk_start = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)(C + 1);
@@ -195,6 +253,9 @@ __device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap
         sh.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
         sh.e[3 * c + 1] = max0(__fsub_rn(b.tau, co[1]));
         sh.e[3 * c + 2] = max0(__fsub_rn(b.tau, co[2]));
+        sh.rnd[3 * c + 0] = co[1];
+        sh.rnd[3 * c + 1] = co[2];
+        sh.rnd[3 * c + 2] = b.cost_round ? b.cost_round[(int64_t)q * b.C + c] : 0.0f;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -275,6 +336,13 @@ __device__ __forceinline__ float transition_weight(const Batch& b, const PlanSha
         n01 = sh.tail_min[o + z.D];
     }
     const uint32_t h0 = sh.tail_min[o];
+    const float round_sec = sh.rnd[3 * c2 + 2];
+    if (round_sec != 0.0f) {
+        auto tail = [&](int x) { return x <= a.D ? sh.tail_min[o + x] : 0u; };
+        const float inter = inter_seconds_by_rounds(tail, z.D, b.tau, sh.rnd[3 * c2], sh.rnd[3 * c2 + 1], round_sec);
+        return __fmul_rn(full, teff_with_inter(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, sh.e[3 * c2], sh.e[3 * c2 + 2],
+                                               inter));
+    }
     const float te = teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, sh.e[3 * c2], sh.e[3 * c2 + 1],
                                       sh.e[3 * c2 + 2]);
     return __fmul_rn(full, te);

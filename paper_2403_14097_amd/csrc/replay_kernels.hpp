@@ -114,8 +114,20 @@ __global__ void __launch_bounds__(256) replay_step_kernel(
             }
             const uint32_t n3 = hm[0];
             const uint32_t n1 = n01 - n0, n2 = (uint32_t)b.S - n01 - n3;
+            const float round_sec = b.cost_round ? b.cost_round[(int64_t)q * b.C + next] : 0.0f;
+            float inter;
+            if (round_sec == 0.0f) {
+                inter = __fmul_rn((float)n2, e1);
+            } else {
+                auto tail = [&](int x) {
+                    uint32_t sum = 0u;
+                    for (int j = x; j <= s.D; ++j) sum += hm[j];
+                    return sum;
+                };
+                inter = inter_seconds_by_rounds(tail, z.D, b.tau, cost[3 * next + 1], cost[3 * next + 2], round_sec);
+            }
             float num = __fadd_rn(__fmul_rn((float)n0, b.tau), __fmul_rn((float)n1, e0));
-            num = __fadd_rn(num, __fmul_rn((float)n2, e1));
+            num = __fadd_rn(num, inter);
             num = __fadd_rn(num, __fmul_rn((float)n3, e2));
             r = __fmul_rn(full, __fdiv_rn(num, (float)b.S));
         }

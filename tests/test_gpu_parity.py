@@ -513,6 +513,79 @@ def test_invalid_zone_data_is_flagged_per_query(pk):
         pk.parcae_liveput_plan(p)
 
 
+# ------------------------------------------------------------------ inter-stage cost by transfer rounds
+
+@pytest.mark.parametrize("name,S,nq,dense,extra", [("tiny", 256, 1, False, ""), ("small", 1000, 1, False, ""),
+                                                    ("medium", 600, 1, True, ""), ("large", 300, 1, False, "pool"),
+                                                    ("sweep", 500, 40, False, ""), ("sweep", 300, 33, False, "zones")])
+def test_transfer_round_costs_full_parity(pk, name, S, nq, dense, extra):
+    """Every planning kernel (weights in memory for few queries, on the fly for many) and the tables."""
+    b = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None, dense=dense).with_rounds()
+    if extra == "zones":
+        b = b.with_zones(3)
+    b.cost_round[:, ::5] = 0.0                 # some candidates keep the fixed inter-stage cost
+    b.cost_round[:, 1::7] = 45.0               # some hit the re-partition cap at once
+    p = pk.upload(b)
+    if extra == "pool":
+        p.flags = pk.PARCAE_POOL_ALL
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in sorted({0, nq // 2, nq - 1}):
+        r = oracle.run_query(b, q, n_scenarios=S, n_threads=8, pool_all=(extra == "pool"))
+        assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int)
+        assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min)
+        assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f)
+        assert np.all(np.abs(_np(ev.gain[q]) - r.tables.gain_d) <= REL * np.abs(r.tables.gain_d))
+        assert np.array_equal(_np(W[q]), r.W_f)
+        fin = np.isfinite(r.W_d)
+        assert np.all(np.abs(_np(W[q])[fin] - r.W_d[fin]) <= REL * np.abs(r.W_d[fin]))
+        assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F)
+        assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
+    # the round cost is felt: weights differ from the fixed-cost ones
+    b0 = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None, dense=dense)
+    if extra == "zones":
+        b0 = b0.with_zones(3)
+    p0 = pk.upload(b0)
+    if extra == "pool":
+        p0.flags = pk.PARCAE_POOL_ALL
+    W0 = pk.parcae_transition_weights(p0, ev.hist_int, ev.hist_min)
+    _sync()
+    w, w0 = _np(W[0]), _np(W0[0])
+    fin = np.isfinite(w0)
+    assert np.all(w[fin] <= w0[fin]) and np.any(w[fin] < w0[fin])
+
+
+def test_transfer_round_costs_in_the_replay_and_bad_values(pk):
+    import torch
+    from oracle import replay as rp
+    nq, H = 4, 6
+    spec = pi.WorkloadSpec("replay", nq, 64, 16, 60.0, (2, 4, 8, 16, 32), 4, 6, 16, 0.12, False, 2, 300)
+    b = pi.make_batch(spec, seed=77)
+    b_plan = b.take(range(nq))
+    b_plan.n_intervals = 8
+    b_plan.avail = np.ascontiguousarray(b.avail[:, :9])
+    b_plan = b_plan.with_rounds(4.0, 12.0)
+    true, win = _replay_inputs(b, H, 9)
+    win = np.ascontiguousarray(win[:, :, :9])
+    p = pk.upload(b_plan)
+    t_true, t_win = torch.from_numpy(true).cuda(), torch.from_numpy(win).cuda()
+    for mode in (pk.PARCAE_REPLAY_PROACTIVE, pk.PARCAE_REPLAY_REACTIVE):
+        chosen, reward, total = pk.parcae_replay(p, t_true, t_win if mode == pk.PARCAE_REPLAY_PROACTIVE else None, mode)
+        _sync()
+        for q in range(nq):
+            r = rp.replay(b_plan, q, true[q], win[:, q, :], mode, n_threads=8)
+            assert np.array_equal(_np(chosen[q]), r.chosen) and np.array_equal(_np(reward[q]), r.reward), (mode, q)
+            assert float(total[q]) == r.total
+    # bad values are flagged per query
+    bad = pi.workload("sweep", n_scenarios=64, n_queries=4).with_rounds()
+    bad.cost_round[1, 3] = -1.0
+    bad.cost_round[2, 0] = np.inf
+    _, pl = pk.parcae_liveput_plan(pk.upload(bad))
+    _sync()
+    assert list(_np(pl.status)) == [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, 0]
+
+
 # ------------------------------------------------------------------ receding-horizon replay
 
 def _replay_inputs(b, H, noise_seed):
