@@ -95,13 +95,15 @@ def _soname_loaded(name: str) -> bool:
         return False
 
 
-def cpu_baseline(batch, budget_queries: int, pool_all: bool = False):
+def cpu_baseline(batch, budget_queries: int, pool_all: bool = False, max_threads: int | None = None):
     """The oracle, as it stands, on a bounded sample of the same workload (first queries, all scenarios)."""
     import oracle
     threads = min(oracle.num_threads(), os.cpu_count() or 1)
+    if max_threads:
+        threads = max(1, min(threads, max_threads))
     nq = min(budget_queries, batch.n_queries)
     units = batch.n_intervals * batch.n_configs
-    s_cpu = min(batch.n_scenarios, max(256, int(2.5e8 // (units * nq))))   # scenario prefix if one query is too big
+    s_cpu = min(batch.n_scenarios, max(256, int(6e7 * threads // (units * nq))))   # scenario prefix if one query is too big
     t0 = time.perf_counter()
     for q in range(nq):
         oracle.run_query(batch, q, n_scenarios=s_cpu, n_threads=threads, pool_all=pool_all)
@@ -124,8 +126,11 @@ def main():
                     help="draw preemptions among all available instances (idle ones included) instead of the used ones")
     ap.add_argument("--zones", type=int, default=0,
                     help="spread the instances over this many zones of unequal preemption hazard (0 = uniform)")
+    ap.add_argument("--rounds", action="store_true",
+                    help="inter-stage migration cost by state-transfer rounds (a per-candidate cost per further round)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
+    ap.add_argument("--cpu-threads", type=int, default=None, help="threads the CPU baseline may use (default: all)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel three times (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -150,6 +155,8 @@ def main():
     batch = pi.workload(args.workload, dense=args.dense, n_queries=args.queries)
     if args.zones:
         batch = batch.with_zones(args.zones)
+    if args.rounds:
+        batch = batch.with_rounds()
     prob = pk.upload(batch, device="cuda:0")
     if args.pool_all:
         prob.flags = pk.PARCAE_POOL_ALL
@@ -214,7 +221,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u32+f32",
         "data": "synthetic",
-        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else "") + (f"+zones{args.zones}" if args.zones else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
+        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else "") + (f"+zones{args.zones}" if args.zones else "") + ("+rounds" if args.rounds else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
                    "n_configs": C, "n_scenarios": S, "scenarios_per_step": scenarios,
                    "nontrivial_scenarios_per_step": nontrivial, "dp_cells_per_step": cells,
                    "infeasible_queries": int((status != 0).sum())},
@@ -232,8 +239,9 @@ def main():
     }
     if not args.no_cpu_baseline:
         per_query = T * C * S
-        budget = args.cpu_queries or max(1, min(nq, int(2.5e8 // max(per_query, 1)) or 1))
-        out["cpu_baseline"] = cpu_baseline(batch, budget, args.pool_all)
+        threads_hint = args.cpu_threads or (os.cpu_count() or 1)
+        budget = args.cpu_queries or max(1, min(nq, int(6e7 * min(threads_hint, 16) // max(per_query, 1)) or 1))
+        out["cpu_baseline"] = cpu_baseline(batch, budget, args.pool_all, args.cpu_threads)
     print(json.dumps(out), flush=True)
 
 

@@ -24,6 +24,7 @@ PARCAE_EHIP = -3
 PARCAE_EINFEASIBLE = -4
 PARCAE_MAX_INSTANCES = 256
 PARCAE_MAX_ZONES = 4
+PARCAE_MAX_SCENARIOS = 1 << 24
 PARCAE_POOL_USED = 0
 PARCAE_POOL_ALL = 1
 PARCAE_COLD_START = -2

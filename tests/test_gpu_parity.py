@@ -670,6 +670,26 @@ def test_degenerate_shapes(pk):
     _check_query_against_oracle(pk, b, 0, ev, pl, 300)
 
 
+def test_largest_scenario_count(pk):
+    """S = 2^24, the largest count the float tables take exactly: one sampled unit, 16384 work items that meet
+    in the same bins, counts and tables against the oracle."""
+    S = pk.PARCAE_MAX_SCENARIOS
+    b = pi.custom_batch(8, [[2, 4]], [[8, 5]], thr_per_pipeline=[7.0], cost=[[2.0, 10.0, 40.0]], n_scenarios=S, seed=12)
+    ev, pl = pk.parcae_liveput_plan(pk.upload(b))
+    _sync()
+    hi, hm = _np(ev.hist_int[0], np.uint32), _np(ev.hist_min[0], np.uint32)
+    assert hi.sum() == S and hm.sum() == S
+    r = oracle.run_query(b, 0, n_threads=8)
+    assert np.array_equal(hi, r.hist_int) and np.array_equal(hm, r.hist_min)
+    assert np.array_equal(_np(ev.liveput[0]), r.tables.liveput_f) and np.array_equal(_np(ev.teff[0]), r.tables.teff_f)
+    assert np.array_equal(_np(pl.plan[0]), r.plan.plan) and float(pl.objective[0]) == r.plan.objective
+    # one more scenario is refused on the host
+    p = pk.upload(b)
+    p.n_scenarios = S + 1
+    with pytest.raises(pk.ParcaeError):
+        pk.parcae_liveput_plan(p)
+
+
 def test_depths_that_are_not_powers_of_two(pk):
     cfg = pi.candidate_list(60, (3, 5, 7, 12, 13, 23), 3)
     b = pi.custom_batch(60, cfg, [[60, 41, 52, 33, 60, 20]], thr_per_pipeline=[float(p) ** 0.5 for _, p in cfg],
