@@ -21,8 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Plain 32-bit vector ALU issue peak: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz.
-ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# Plain 32-bit vector ALU peak: 256 compute units x 4 SIMDs x 32 lanes per cycle x 2.4 GHz = 78.6 T lane-op/s,
+# i.e. the chip's fp32 vector rate of 157.3 TFLOP/s with a fused multiply-add counted as ONE lane operation.
+ALU_PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
 
 
 def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False, zoned=False):
@@ -232,10 +233,11 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
                      "kernel": "eval_hist_kernel", "algorithmic_lane_ops_per_launch": alg_ops,
-                     "note": "algorithmic lane-ops follow the per-scenario formula in DESIGN.md; the kernel needs fewer "
-                             "issued instructions than that (fused multiply-wide, 3-input logic, bit-sliced counters) "
-                             "and gfx950 issues simple 32-bit ops at twice the 16-lane rate the peak assumes, so the "
-                             "fraction can exceed 1; measured VALU busy is in profiles/"},
+                     "note": "algorithmic lane-ops per launch follow the per-scenario formula in DESIGN.md (textbook "
+                             "operation count of the method); peak = 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz, the "
+                             "rate at which gfx950 issues simple 32-bit vector ops (measured 2.2 cycles per wave64 "
+                             "instruction); 32-bit multiplies, left shifts, compares and popcounts issue at half "
+                             "that rate, so a kernel with this mix cannot reach 1; measured VALU busy is in profiles/"},
     }
     if not args.no_cpu_baseline:
         per_query = T * C * S

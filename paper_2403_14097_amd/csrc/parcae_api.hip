@@ -34,6 +34,17 @@ struct Layout {
     int max_row;  // bins of the widest candidate, max over c of D_c + 1
 };
 
+// Histogram bins the planning kernels keep in LDS at a time: all of them if they fit, else as many as
+// the LDS budget allows; -1 if not even the widest row fits next to the per-candidate tables.
+int pick_plan_cap(int C, const Layout& lay, size_t bp16_bytes, bool per_query)
+{
+    const size_t fixed = parcae::plan_lds_bytes(C, 0, bp16_bytes, per_query);
+    if (fixed >= kMaxPlanLds) return -1;
+    int64_t cap = (int64_t)((kMaxPlanLds - fixed) / 8);
+    if (cap > lay.L) cap = lay.L;
+    return cap >= lay.max_row ? (int)cap : -1;
+}
+
 // Host-visible shape checks; fills the packed candidate table.
 int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* lay)
 {
@@ -81,7 +92,8 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
         lay->queue_off = lay->bp_off + align_up(sizeof(int32_t) * n_units);
         lay->list_off = lay->queue_off + kAlign * (1 + parcae::kQueueShards);  // item count, then one line per shard counter
         lay->w_off = lay->list_off + align_up(sizeof(uint32_t) * n_units);
-        lay->stepwise = p->n_queries < kFusedMinQueries;
+        // the per-query planner needs more LDS per candidate; where it does not fit the weights go through memory
+        lay->stepwise = p->n_queries < kFusedMinQueries || pick_plan_cap(p->n_configs, *lay, 0, true) < 0;
         const size_t w_bytes = lay->stepwise ? sizeof(float) * n_units * (size_t)p->n_configs : 0;
         const size_t f_bytes =
             lay->stepwise ? sizeof(float) * (size_t)p->n_queries * ((size_t)p->n_intervals + 1) * (size_t)p->n_configs : 0;
@@ -147,17 +159,6 @@ int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batc
 int32_t* valid_ptr(const Layout& lay, void* ws)
 {
     return reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
-}
-
-// Histogram bins the planning kernels keep in LDS at a time: all of them if they fit, else as many as
-// the LDS budget allows; -1 if not even the widest row fits next to the per-candidate tables.
-int pick_plan_cap(int C, const Layout& lay, size_t bp16_bytes)
-{
-    const size_t fixed = parcae::plan_lds_bytes(C, 0, bp16_bytes);
-    if (fixed >= kMaxPlanLds) return -1;
-    int64_t cap = (int64_t)((kMaxPlanLds - fixed) / 8);
-    if (cap > lay.L) cap = lay.L;
-    return cap >= lay.max_row ? (int)cap : -1;
 }
 
 // Bytes of a 16-bit copy of the back-pointers of one query if it is small enough to live in LDS, else 0.
@@ -272,27 +273,31 @@ int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* his
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
     if (lay.stepwise) {
         // few queries: every (query, step) writes its weights in parallel, then the DP runs on them
-        const int cap = pick_plan_cap(b.C, lay, 0);
+        const int cap = pick_plan_cap(b.C, lay, 0, false);
         if (cap < 0 || b.C > kMaxConfigsDp) return PARCAE_EINVAL;
         float* W = reinterpret_cast<float*>(base + lay.w_off);
         parcae::transition_kernel<<<dim3((unsigned)(b.nq * b.T)), dim3(parcae::kPlanThreads),
-                                    parcae::plan_lds_bytes(b.C, cap, 0), st>>>(b, cap, hist_int, hist_min, W);
+                                    parcae::plan_lds_bytes(b.C, cap, 0, false), st>>>(b, cap, hist_int, hist_min, W);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
         return launch_dp(W, b.nq, b.T, b.C, valid_ptr(lay, ws), F, reinterpret_cast<float*>(base + lay.f_off), bp_use,
                          plan, start, objective, status, st);
     }
     const size_t b16 = bp16_bytes_for(b.T, b.C);
-    int cap = pick_plan_cap(b.C, lay, b16);
+    int cap = pick_plan_cap(b.C, lay, b16, true);
     size_t b16_use = b16;
     if (cap < 0) {  // no room for the LDS copy of the back-pointers: walk back through memory instead
         b16_use = 0;
-        cap = pick_plan_cap(b.C, lay, 0);
+        cap = pick_plan_cap(b.C, lay, 0, true);
     }
     if (cap < 0) return PARCAE_EINVAL;
+    // small problems keep the histogram rows of every step in LDS (no memory access inside the chain of steps)
+    const int64_t all_bins = (int64_t)b.T * lay.L;
+    const bool resident = parcae::plan_lds_bytes(b.C, 0, b16_use, true) + 8 * (size_t)all_bins <= kMaxPlanLds;
+    if (resident) cap = (int)all_bins;
     parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(parcae::kPlanThreads),
-                                parcae::plan_lds_bytes(b.C, cap, b16_use), st>>>(
-        b, cap, b16_use ? 1 : 0, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start, objective, status,
-        PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+                                parcae::plan_lds_bytes(b.C, cap, b16_use, true), st>>>(
+        b, cap, b16_use ? 1 : 0, resident ? 1 : 0, hist_int, hist_min, valid_ptr(lay, ws), F, bp_use, plan, start,
+        objective, status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
 
@@ -300,7 +305,7 @@ int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* his
 bool plan_fits(const parcae_problem* p, const Layout& lay)
 {
     if (lay.stepwise && p->n_configs > kMaxConfigsDp) return false;
-    return pick_plan_cap(p->n_configs, lay, 0) >= 0;
+    return pick_plan_cap(p->n_configs, lay, 0, !lay.stepwise) >= 0;
 }
 
 }  // namespace
@@ -401,9 +406,9 @@ int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int,
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !W) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
-    const int cap = pick_plan_cap(p->n_configs, lay, 0);
+    const int cap = pick_plan_cap(p->n_configs, lay, 0, false);
     if (cap < 0) return PARCAE_EINVAL;
-    const size_t lds = parcae::plan_lds_bytes(p->n_configs, cap, 0);
+    const size_t lds = parcae::plan_lds_bytes(p->n_configs, cap, 0, false);
     if ((int64_t)p->n_queries * p->n_intervals >= (int64_t)1 << 31) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);

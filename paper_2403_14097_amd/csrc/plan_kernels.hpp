@@ -213,25 +213,31 @@ struct PlanShared {
     int* from_ok;        // [C] may be left at this step
     int* to_ok;          // [C] may be entered at this step
     int* chunk_start;    // [n_chunks + 1] first candidate of each chunk
-    float* F0;           // [C]
-    float* F1;           // [C]
-    int* arg;            // [C]
+    // the per-query planner only:
+    float* F;                 // [C] value function of the previous step
+    float* Feff;              // [C] the same, -inf where the candidate may not be left at this step
+    float* R;                 // [C] thr[c][D_c] * max(0, tau - re-partition cost): weight of reaching c from another depth
+    uint32_t* gspan;          // [C] candidates of the same depth as c: first | (one past last) << 16
+    unsigned long long* key;  // [C] best (value, source) offered to each target in the step being built
     uint32_t* tail_int;  // [cap] suffix sums of hist_int inside each row of the current chunk
     uint32_t* tail_min;  // [cap] same for hist_min, except that slot 0 of a row keeps the raw bin 0
     uint16_t* bp16;      // [T][C] back-pointers (0xffff = none) if they fit in LDS, else null
     int n_chunks;
+    int tile_log2;       // log2 of the tile width of the same-depth cells: smallest power of two >= the largest depth group
     int cold;            // this step starts from nothing running (t == 0 and cur_config == -2)
 };
 
 constexpr int kPlanThreads = 256;
 constexpr uint16_t kNoPred16 = 0xffffu;
 
-inline size_t plan_lds_bytes(int C, int cap, size_t bp16_bytes)
+// per_query: the layout of plan_fused_kernel (value function, offers, depth groups); else that of transition_kernel.
+inline size_t plan_lds_bytes(int C, int cap, size_t bp16_bytes, bool per_query)
 {
-    return 68 * (size_t)C + 16 + 8 * (size_t)cap + ((bp16_bytes + 15) & ~(size_t)15);
+    return (per_query ? 88 : 56) * (size_t)C + 32 + 8 * (size_t)cap + ((bp16_bytes + 15) & ~(size_t)15);
 }
 
-__device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool bp_in_lds, PlanShared& sh)
+__device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool bp_in_lds, bool per_query,
+                                      PlanShared& sh)
 {
     size_t o = 0;
     sh.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
@@ -241,9 +247,17 @@ __device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool 
     sh.from_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
     sh.to_ok = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
     sh.chunk_start = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)(C + 1);
-    sh.F0 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
-    sh.F1 = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
-    sh.arg = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
+    sh.F = sh.Feff = sh.R = nullptr;
+    sh.gspan = nullptr;
+    sh.key = nullptr;
+    if (per_query) {
+        o = (o + 7) & ~(size_t)7;
+        sh.key = reinterpret_cast<unsigned long long*>(smem + o); o += 8 * (size_t)C;
+        sh.F = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+        sh.Feff = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+        sh.R = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
+        sh.gspan = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)C;
+    }
     o = (o + 15) & ~(size_t)15;
     sh.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)cap;
     sh.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)cap;
@@ -254,9 +268,13 @@ __device__ __forceinline__ void carve(unsigned char* smem, int C, int cap, bool 
 __device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap, PlanShared& sh)
 {
     __shared__ int n_chunks_s;
+    __shared__ int widest_group_s;
+    if (threadIdx.x == 0) widest_group_s = 1;
+    __syncthreads();
     for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
         const CfgRec cr = b.cfg[c];
         sh.cfg[c] = cr;
+
         sh.full[c] = b.thr[(int64_t)q * b.L + cr.off + cr.D];
         const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
         sh.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
@@ -265,8 +283,19 @@ __device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap
         sh.rnd[3 * c + 0] = co[1];
         sh.rnd[3 * c + 1] = co[2];
         sh.rnd[3 * c + 2] = b.cost_round ? b.cost_round[(int64_t)q * b.C + c] : 0.0f;
+        if (sh.R) sh.R[c] = __fmul_rn(sh.full[c], sh.e[3 * c + 2]);
     }
     __syncthreads();
+    if (sh.gspan) {  // candidates are sorted by depth: the candidates of the depth of c are a run around c
+        for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
+            const int P = sh.cfg[c].P;
+            int lo = c, hi = c + 1;
+            while (lo > 0 && sh.cfg[lo - 1].P == P) --lo;
+            while (hi < b.C && sh.cfg[hi].P == P) ++hi;
+            sh.gspan[c] = (uint32_t)lo | ((uint32_t)hi << 16);
+            atomicMax(&widest_group_s, hi - lo);
+        }
+    }
     if (threadIdx.x == 0) {
         int n = 0, c = 0;
         while (c < b.C) {
@@ -281,15 +310,16 @@ __device__ __forceinline__ void load_query_tables(const Batch& b, int q, int cap
     }
     __syncthreads();
     sh.n_chunks = n_chunks_s;
+    int lg = 0;
+    while ((1 << lg) < widest_group_s) ++lg;
+    sh.tile_log2 = lg;
 }
 
 // Feasibility of leaving / entering each candidate at step t (constraint D * P <= N of Eq. 6, memory floor,
-// and the current configuration at t = 0).  Ends with a barrier.
-__device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, PlanShared& sh)
+// and the current configuration at t = 0) from the availability before and after the boundary.  Ends with a
+// barrier.
+__device__ __forceinline__ void set_step_flags(const Batch& b, int t, int cur, int a_prev, int a_next, PlanShared& sh)
 {
-    const int a_prev = clampi(b.avail[(int64_t)q * b.avail_stride + t], 0, b.N);
-    const int a_next = clampi(b.avail[(int64_t)q * b.avail_stride + t + 1], 0, b.N);
-    const int cur = b.cur_config ? b.cur_config[q] : -1;
     sh.cold = (t == 0 && cur == -2) ? 1 : 0;
     for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
         const CfgRec cr = sh.cfg[c];
@@ -297,6 +327,61 @@ __device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, Pl
         const bool deep = cr.P >= b.p_min;
         sh.from_ok[c] = (used <= b.group * a_prev) && deep && (t > 0 || cur < 0 || c == cur);
         sh.to_ok[c] = (used <= b.group * a_next) && deep;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void load_step_flags(const Batch& b, int q, int t, PlanShared& sh)
+{
+    const int a_prev = clampi(b.avail[(int64_t)q * b.avail_stride + t], 0, b.N);
+    const int a_next = clampi(b.avail[(int64_t)q * b.avail_stride + t + 1], 0, b.N);
+    set_step_flags(b, t, b.cur_config ? b.cur_config[q] : -1, a_prev, a_next, sh);
+}
+
+// Suffix sums inside the histogram row of candidate cr that starts at bin o of the LDS arrays (slot 0 of
+// tail_min keeps the raw bin 0).
+__device__ __forceinline__ void suffix_row(const PlanShared& sh, const CfgRec cr, int o)
+{
+    uint32_t ri = 0u, rm = 0u;
+    int j = cr.D;
+    // eight bins at a time: the loads are independent of the running sums, so they travel together
+    for (; j >= 8; j -= 8) {
+        uint32_t vi[8], vm[8];
+        static_for<8>([&](auto x) {
+            vi[x.value] = sh.tail_int[o + j - x.value];
+            vm[x.value] = sh.tail_min[o + j - x.value];
+        });
+        static_for<8>([&](auto x) {
+            ri += vi[x.value];
+            rm += vm[x.value];
+            sh.tail_int[o + j - x.value] = ri;
+            sh.tail_min[o + j - x.value] = rm;
+        });
+    }
+    for (; j >= 1; --j) {
+        ri += sh.tail_int[o + j];
+        rm += sh.tail_min[o + j];
+        sh.tail_int[o + j] = ri;
+        sh.tail_min[o + j] = rm;
+    }
+}
+
+// The histogram rows of ALL steps of query q into LDS as suffix sums (step t at bins [t * L, (t + 1) * L)), for
+// problems small enough that they fit: the sequential steps then touch no memory.  Ends with a barrier.
+__device__ __forceinline__ void load_all_steps(const Batch& b, int q, const uint32_t* __restrict__ hist_int,
+                                               const uint32_t* __restrict__ hist_min, const PlanShared& sh)
+{
+    const int64_t base = (int64_t)q * b.T * b.L;
+    const int total = b.T * b.L;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+        sh.tail_int[i] = hist_int[base + i];
+        sh.tail_min[i] = hist_min[base + i];
+    }
+    __syncthreads();
+    for (int row = threadIdx.x; row < b.T * b.C; row += blockDim.x) {
+        const int t = row / b.C;
+        const CfgRec cr = sh.cfg[row - t * b.C];
+        suffix_row(sh, cr, t * b.L + cr.off);
     }
     __syncthreads();
 }
@@ -317,16 +402,36 @@ __device__ __forceinline__ void load_chunk(const Batch& b, int q, int t, int c_l
     __syncthreads();
     for (int c = c_lo + threadIdx.x; c < c_hi; c += blockDim.x) {
         const CfgRec cr = sh.cfg[c];
-        const int o = cr.off - first;
-        uint32_t ri = 0u, rm = 0u;
-        for (int j = cr.D; j >= 1; --j) {
-            ri += sh.tail_int[o + j];
-            rm += sh.tail_min[o + j];
-            sh.tail_int[o + j] = ri;
-            sh.tail_min[o + j] = rm;
-        }
+        suffix_row(sh, cr, cr.off - first);
     }
     __syncthreads();
+}
+
+// Weight of a same-depth transition c -> c2 (both feasible, not a cold start): throughput of c2 times the expected
+// effective seconds of unit (t, c) read at the width of c2.  `first` = first bin of the rows held in LDS.
+template <bool kRounds>
+__device__ __forceinline__ float same_depth_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2)
+{
+    // every table value is loaded before the first use, so that the loads travel together
+    const CfgRec a = sh.cfg[c], z = sh.cfg[c2];
+    const float full = sh.full[c2];
+    const float e0 = sh.e[3 * c2], e1 = sh.e[3 * c2 + 1], e2 = sh.e[3 * c2 + 2];
+    const int o = a.off - first;
+    // a target wider than the source keeps nothing; the loads stay unconditional on a clamped index
+    const int at = z.D <= a.D ? z.D : a.D;  // z.D >= 1, so the raw slot 0 is never read as a suffix sum
+    const uint32_t t_int = sh.tail_int[o + at], t_min = sh.tail_min[o + at];
+    const uint32_t n0 = z.D <= a.D ? t_int : 0u, n01 = z.D <= a.D ? t_min : 0u;
+    const uint32_t h0 = sh.tail_min[o];
+    if constexpr (kRounds) {
+        const float round_sec = sh.rnd[3 * c2 + 2];
+        if (round_sec != 0.0f) {
+            auto tail = [&](int x) { return x <= a.D ? sh.tail_min[o + x] : 0u; };
+            const float inter =
+                inter_seconds_by_rounds(tail, z.D, b.tau, sh.rnd[3 * c2], sh.rnd[3 * c2 + 1], round_sec);
+            return __fmul_rn(full, teff_with_inter(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, e0, e2, inter));
+        }
+    }
+    return __fmul_rn(full, teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, e0, e1, e2));
 }
 
 // W_t[c][c'] for a source c inside the chunk that starts at bin `first`.
@@ -335,26 +440,8 @@ __device__ __forceinline__ float transition_weight(const Batch& b, const PlanSha
     if (sh.cold)  // nothing is running: the first configuration comes up at its re-partition cost
         return (c == c2 && sh.to_ok[c2]) ? __fmul_rn(sh.full[c2], sh.e[3 * c2 + 2]) : kNegInf;
     if (!sh.from_ok[c] || !sh.to_ok[c2]) return kNegInf;
-    const CfgRec a = sh.cfg[c], z = sh.cfg[c2];
-    const float full = sh.full[c2];
-    if (a.P != z.P) return __fmul_rn(full, sh.e[3 * c2 + 2]);
-    const int o = a.off - first;
-    uint32_t n0 = 0u, n01 = 0u;
-    if (z.D <= a.D) {  // z.D >= 1, so the raw slot 0 is never read as a suffix sum
-        n0 = sh.tail_int[o + z.D];
-        n01 = sh.tail_min[o + z.D];
-    }
-    const uint32_t h0 = sh.tail_min[o];
-    const float round_sec = sh.rnd[3 * c2 + 2];
-    if (round_sec != 0.0f) {
-        auto tail = [&](int x) { return x <= a.D ? sh.tail_min[o + x] : 0u; };
-        const float inter = inter_seconds_by_rounds(tail, z.D, b.tau, sh.rnd[3 * c2], sh.rnd[3 * c2 + 1], round_sec);
-        return __fmul_rn(full, teff_with_inter(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, sh.e[3 * c2], sh.e[3 * c2 + 2],
-                                               inter));
-    }
-    const float te = teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, sh.e[3 * c2], sh.e[3 * c2 + 1],
-                                      sh.e[3 * c2 + 2]);
-    return __fmul_rn(full, te);
+    if (sh.cfg[c].P != sh.cfg[c2].P) return __fmul_rn(sh.full[c2], sh.e[3 * c2 + 2]);
+    return b.cost_round ? same_depth_weight<true>(b, sh, first, c, c2) : same_depth_weight<false>(b, sh, first, c, c2);
 }
 
 // Writes W[q][t][c][c'] (one block per (q, t)).
@@ -363,7 +450,7 @@ __global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const
 {
     extern __shared__ __align__(16) unsigned char smem[];
     PlanShared sh;
-    carve(smem, b.C, cap, false, sh);
+    carve(smem, b.C, cap, false, false, sh);
     const int q = blockIdx.x / b.T;
     const int t = blockIdx.x - q * b.T;
     load_query_tables(b, q, cap, sh);
@@ -427,6 +514,25 @@ __device__ __forceinline__ void merge_groups(const ColumnGrid& cg, int c2, int C
     __syncthreads();
 }
 
+// Order-preserving map of a float to an unsigned integer (a larger float gives a larger key; no float maps to 0).
+__device__ __forceinline__ uint32_t float_key(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// Offers value v reached from source c to a target's slot: the larger value wins and, among equal values, the
+// smaller source, which is the order in which a plain ascending scan with a strict comparison decides.  -inf (and
+// NaN) is no offer.  One LDS atomic; the result does not depend on the order of the offers.
+__device__ __forceinline__ void offer(unsigned long long* slot, float v, int c)
+{
+    if (v > kNegInf) atomicMax(slot, ((unsigned long long)float_key(v) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)c));
+}
+
 // Final arg-max and walk back along the back-pointers; thread 0 of the block only.
 // bp16 (LDS, 0xffff = none) is used when present, else the back-pointers in memory.
 __device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_last, const int32_t* bp_q,
@@ -469,69 +575,163 @@ __device__ __forceinline__ void finish_plan(int q, int T, int C, const float* F_
 // One block per query: T dependent max-plus steps with the weights computed on the fly from the
 // histogram tails (the weights never touch HBM), then the walk back.  Used when there are enough
 // queries to fill the chip.
+//
+// A step offers, for every pair (source c, target c2), F[c] + W[c][c2] to the target's slot (see offer()).  Pairs
+// of different depth all carry the same weight R[c2], so they cost one addition each: a thread scans a slice of the
+// sources for its target column and makes one offer.  Pairs of the same depth need the histogram tails of the source;
+// the candidates of one depth are contiguous, so these pairs form square tiles on the diagonal: they are laid out
+// row by row in tiles `1 << tile_log2` wide and dealt to the threads evenly, each pair one offer.
 __global__ void __launch_bounds__(kPlanThreads) plan_fused_kernel(
-    Batch b, int cap, int bp_in_lds, const uint32_t* __restrict__ hist_int, const uint32_t* __restrict__ hist_min,
-    const int32_t* __restrict__ valid, float* __restrict__ F, int32_t* __restrict__ bp, int32_t* __restrict__ plan,
-    int32_t* __restrict__ start, float* __restrict__ objective, int32_t* __restrict__ status, int einval,
-    int einfeasible)
+    Batch b, int cap, int bp_in_lds, int resident, const uint32_t* __restrict__ hist_int,
+    const uint32_t* __restrict__ hist_min, const int32_t* __restrict__ valid, float* __restrict__ F,
+    int32_t* __restrict__ bp, int32_t* __restrict__ plan, int32_t* __restrict__ start, float* __restrict__ objective,
+    int32_t* __restrict__ status, int einval, int einfeasible)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red_val[kPlanThreads];
-    __shared__ int red_arg[kPlanThreads];
     PlanShared sh;
-    carve(smem, b.C, cap, bp_in_lds != 0, sh);
+    carve(smem, b.C, cap, bp_in_lds != 0, true, sh);
     const int q = blockIdx.x;
     const int C = b.C;
+    const int tid = (int)threadIdx.x;
     const ColumnGrid cg = column_grid(C);
     load_query_tables(b, q, cap, sh);
     float* Fq = F ? F + (int64_t)q * (b.T + 1) * C : nullptr;
     int32_t* bpq = bp ? bp + (int64_t)q * b.T * C : nullptr;
-    float* Fc = sh.F0;
-    float* Fn = sh.F1;
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
-        Fc[c] = 0.0f;
+    for (int c = tid; c < C; c += kPlanThreads) {
+        sh.F[c] = 0.0f;
         if (Fq) Fq[c] = 0.0f;
     }
+    // resident: cap holds the rows of every step (T * L bins), loaded once; the steps then run out of LDS
+    if (resident) load_all_steps(b, q, hist_int, hist_min, sh);
+    uint32_t* const all_int = sh.tail_int;
+    uint32_t* const all_min = sh.tail_min;
+    const int n_chunks = resident ? 1 : sh.n_chunks;
+    const int wlog = sh.tile_log2;
+    const int rows_per_pass = kPlanThreads >> wlog;
+    const int tile_row = tid >> wlog, tile_col = tid & ((1 << wlog) - 1);
+    const int rpg = (C + cg.rg - 1) / cg.rg;  // sources per thread of the different-depth scan
+    const int r0 = cg.g * rpg, r1 = r0 + rpg < C ? r0 + rpg : C;
+    // availability is read one step ahead of its use, so its latency never sits on the chain of steps
+    const int32_t* av = b.avail + (int64_t)q * b.avail_stride;
+    const int cur = b.cur_config ? b.cur_config[q] : -1;
+    int a_prev = clampi(av[0], 0, b.N);
+    int a_next = clampi(av[1], 0, b.N);
+    // Opens step t for candidate c whose value is f: Feff (feasibility of leaving c: constraint D * P <= N of Eq. 6,
+    // memory floor, the current configuration at t = 0), to_ok (feasibility of entering c), empty offer slot.
+    auto open_step = [&](int t, int c, float f, int before, int after) __attribute__((always_inline)) {
+        const CfgRec cr = sh.cfg[c];
+        const int used = cr.D * cr.P;
+        const bool deep = cr.P >= b.p_min;
+        const bool from = (used <= b.group * before) && deep && (t > 0 || cur < 0 || c == cur);
+        sh.Feff[c] = from ? f : kNegInf;
+        sh.to_ok[c] = (used <= b.group * after) && deep;
+        sh.key[c] = 0ull;
+    };
+    for (int c = tid; c < C; c += kPlanThreads) open_step(0, c, 0.0f, a_prev, a_next);
+    __syncthreads();
     for (int t = 0; t < b.T; ++t) {
-        load_step_flags(b, q, t, sh);  // ends with a barrier (also orders the writes of Fc)
-        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            Fn[c2] = kNegInf;
-            sh.arg[c2] = -1;
-        }
-        for (int ch = 0; ch < sh.n_chunks; ++ch) {
-            const int c_lo = sh.chunk_start[ch], c_hi = sh.chunk_start[ch + 1];
-            load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);  // barriers before and after
-            const int first = sh.cfg[c_lo].off;
-            const int rpg = (c_hi - c_lo + cg.rg - 1) / cg.rg;
-            const int r0 = c_lo + cg.g * rpg;
-            const int r1 = r0 + rpg < c_hi ? r0 + rpg : c_hi;
+        const int a_after = av[t + 2 <= b.T ? t + 2 : b.T];
+        if (t == 0 && cur == -2) {
+            // nothing is running: every candidate can only be "reached from itself", at its re-partition cost
+            for (int c2 = tid; c2 < C; c2 += kPlanThreads)
+                if (sh.to_ok[c2]) offer(&sh.key[c2], __fadd_rn(0.0f, sh.R[c2]), c2);
+        } else {
+            // sources of another depth
             for (int base = 0; base < C; base += cg.cw) {
                 const int c2 = base + cg.x;
-                float best = kNegInf;
-                int arg = -1;
-                if (c2 < C && sh.to_ok[c2]) {
-                    for (int c = r0; c < r1; ++c) {
-                        const float v = __fadd_rn(Fc[c], transition_weight(b, sh, first, c, c2));
-                        if (v > best) {
-                            best = v;
-                            arg = c;
-                        }
+                if (c2 < C) {
+                    const uint32_t span = sh.gspan[c2];
+                    const int lo = (int)(span & 0xffffu), hi = (int)(span >> 16);
+                    const float reach = sh.R[c2];
+                    const int entered = sh.to_ok[c2];
+                    float best = kNegInf;
+                    int arg = -1;
+                    for (int c0 = r0; c0 < r1; c0 += 4) {  // four sources at a time, loads on clamped indices
+                        float f[4];
+                        static_for<4>([&](auto x) { f[x.value] = sh.Feff[c0 + x.value < r1 ? c0 + x.value : r0]; });
+                        static_for<4>([&](auto x) {
+                            const int c = c0 + x.value;
+                            const float v = __fadd_rn(f[x.value], reach);
+                            if (c < r1 && (c < lo || c >= hi) && v > best) {
+                                best = v;
+                                arg = c;
+                            }
+                        });
                     }
+                    if (entered && arg >= 0) offer(&sh.key[c2], best, arg);
                 }
-                merge_groups(cg, c2, C, best, arg, red_val, red_arg, Fn, sh.arg);
+            }
+            // sources of the same depth
+            if (resident) {
+                sh.tail_int = all_int + t * b.L;
+                sh.tail_min = all_min + t * b.L;
+            }
+            for (int ch = 0; ch < n_chunks; ++ch) {
+                const int c_lo = resident ? 0 : sh.chunk_start[ch], c_hi = resident ? C : sh.chunk_start[ch + 1];
+                if (!resident) load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);  // barriers before and after
+                const int first = sh.cfg[c_lo].off;
+                auto tiles = [&](auto rounds, auto batch) __attribute__((always_inline)) {
+                    constexpr int kTileBatch = decltype(batch)::value;
+                    // `batch` passes at a time: table loads of the batch go out together, every load on clamped
+                    // indices, only the offers are predicated
+                    for (int row0 = c_lo; row0 < c_hi; row0 += kTileBatch * rows_per_pass) {
+                        int cs[kTileBatch], c2s[kTileBatch];
+                        bool live[kTileBatch];
+                        uint32_t span[kTileBatch];
+                        static_for<kTileBatch>([&](auto x) {
+                            const int c = row0 + x.value * rows_per_pass + tile_row;
+                            live[x.value] = c < c_hi;
+                            cs[x.value] = live[x.value] ? c : c_lo;
+                            span[x.value] = sh.gspan[cs[x.value]];
+                        });
+                        static_for<kTileBatch>([&](auto x) {
+                            const int lo = (int)(span[x.value] & 0xffffu), hi = (int)(span[x.value] >> 16);
+                            live[x.value] = live[x.value] && lo + tile_col < hi;
+                            c2s[x.value] = live[x.value] ? lo + tile_col : lo;
+                        });
+                        float f[kTileBatch], w[kTileBatch];
+                        int entered[kTileBatch];
+                        static_for<kTileBatch>([&](auto x) {
+                            f[x.value] = sh.Feff[cs[x.value]];
+                            entered[x.value] = sh.to_ok[c2s[x.value]];
+                            w[x.value] = same_depth_weight<decltype(rounds)::value>(b, sh, first, cs[x.value], c2s[x.value]);
+                        });
+                        static_for<kTileBatch>([&](auto x) {
+                            if (live[x.value] && entered[x.value])
+                                offer(&sh.key[c2s[x.value]], __fadd_rn(f[x.value], w[x.value]), cs[x.value]);
+                        });
+                    }
+                };
+                const bool few = c_hi - c_lo <= 2 * rows_per_pass;  // small candidate lists: no more slots than cells
+                if (b.cost_round) {
+                    if (few) tiles(std::true_type{}, std::integral_constant<int, 2>{});
+                    else tiles(std::true_type{}, std::integral_constant<int, 4>{});
+                } else {
+                    if (few) tiles(std::false_type{}, std::integral_constant<int, 2>{});
+                    else tiles(std::false_type{}, std::integral_constant<int, 4>{});
+                }
             }
         }
-        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            const int a = sh.arg[c2];
+        __syncthreads();
+        // close step t and open step t + 1: one pass, the thread of candidate c2 holds its new value
+        const int before = a_next, after = clampi(a_after, 0, b.N);
+        for (int c2 = tid; c2 < C; c2 += kPlanThreads) {
+            const unsigned long long k = sh.key[c2];
+            const float v = k ? key_float((uint32_t)(k >> 32)) : kNegInf;
+            const int a = k ? (int)(0xffffffffu - (uint32_t)k) : -1;
+            sh.F[c2] = v;
             if (bpq) bpq[(int64_t)t * C + c2] = a;
             if (sh.bp16) sh.bp16[t * C + c2] = a < 0 ? kNoPred16 : (uint16_t)a;
-            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = Fn[c2];
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = v;
+            open_step(t + 1, c2, v, before, after);
         }
+        a_prev = before;
+        a_next = after;
         __syncthreads();
-        float* tmp = Fc; Fc = Fn; Fn = tmp;
     }
-    if (threadIdx.x == 0) {
-        finish_plan(q, b.T, C, Fc, bpq, sh.bp16, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
+    __syncthreads();
+    if (tid == 0) {
+        finish_plan(q, b.T, C, sh.F, bpq, sh.bp16, plan, start, objective, status, valid ? valid[q] != 0 : true, einval,
                     einfeasible);
     }
 }

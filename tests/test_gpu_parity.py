@@ -178,6 +178,21 @@ def test_many_queries_take_the_per_query_planning_kernel(pk):
     assert np.array_equal(_np(lean.plan), _np(pl.plan)) and np.array_equal(_np(lean.objective), _np(pl.objective))
 
 
+def test_per_query_planning_kernel_with_rows_that_do_not_fit_in_lds_at_once(pk):
+    """33 queries on 128 instances with every depth listed (296 candidates, 12 thousand histogram bins per
+    step): the per-query planner has to bring the source rows in several chunks; many depths, cold start and a
+    free start among the queries."""
+    spec = pi.WorkloadSpec("wide", 33, 128, 5, 60.0, (1, 2, 3, 4, 8, 16, 32, 64), 1, 10, 32, 0.2, False, 4, 96)
+    b = pi.make_batch(spec, seed=606)
+    b.cur_config[3] = -1
+    b.cur_config[4] = -2
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    for q in (0, 3, 4, 32):
+        _check_query_against_oracle(pk, b, q, ev, pl, 96)
+
+
 def test_dp_on_stored_weights_all_kernel_variants(pk):
     """Weights in memory: tiles staged in LDS (C <= 64), read in place (one block), and one launch per step."""
     for name, dense, S in (("small", False, 200), ("medium", True, 100), ("large", True, 64)):
