@@ -24,6 +24,9 @@ constexpr int kFusedMinQueries = 32;     // fewer queries than this: weights go 
 constexpr int kSingleBlockMaxConfigs = 128;  // stepwise DP: up to this many candidates one block per query does all steps
 constexpr size_t kMaxBpLds = 16 * 1024;  // back-pointers stay in LDS (16-bit) when they fit in this
 constexpr size_t kMaxPlanLds = 60 * 1024;  // dynamic LDS per block, leaves room for the static part within 64 KB
+constexpr size_t kLdsPerCu = 160 * 1024;   // LDS of one compute unit
+constexpr size_t kPlanStaticLds = 512;     // static LDS of the planning kernel, rounded up
+constexpr size_t kMaxPlanBlocksPerCu = 8;  // 32 waves per compute unit / 4 waves per block
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -292,7 +295,19 @@ int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* his
     if (cap < 0) return PARCAE_EINVAL;
     // small problems keep the histogram rows of every step in LDS (no memory access inside the chain of steps)
     const int64_t all_bins = (int64_t)b.T * lay.L;
-    const bool resident = parcae::plan_lds_bytes(b.C, 0, b16_use, true) + 8 * (size_t)all_bins <= kMaxPlanLds;
+    // ... as long as all queries still run at once: with more blocks than the chip holds at that LDS size, smaller
+    // blocks that stream their rows finish sooner (measured crossover: 512 against 1024 queries of the sweep shape)
+    const size_t resident_bytes = parcae::plan_lds_bytes(b.C, 0, b16_use, true) + 8 * (size_t)all_bins;
+    bool resident = resident_bytes <= kMaxPlanLds;
+    if (resident) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            return PARCAE_EHIP;
+        size_t per_cu = kLdsPerCu / (resident_bytes + kPlanStaticLds);
+        if (per_cu > kMaxPlanBlocksPerCu) per_cu = kMaxPlanBlocksPerCu;
+        resident = (size_t)b.nq <= per_cu * (size_t)cus;
+    }
     if (resident) cap = (int)all_bins;
     parcae::plan_fused_kernel<<<dim3((unsigned)b.nq), dim3(parcae::kPlanThreads),
                                 parcae::plan_lds_bytes(b.C, cap, b16_use, true), st>>>(
