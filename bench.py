@@ -129,6 +129,9 @@ def main():
                     help="spread the instances over this many zones of unequal preemption hazard (0 = uniform)")
     ap.add_argument("--rounds", action="store_true",
                     help="inter-stage migration cost by state-transfer rounds (a per-candidate cost per further round)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time replays of a HIP graph that captured one whole call (reported as "
+                         "graph_replay_ms_per_step next to the eager figures; the call enqueues kernels only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
     ap.add_argument("--cpu-threads", type=int, default=None, help="threads the CPU baseline may use (default: all)")
@@ -206,6 +209,25 @@ def main():
     torch.cuda.synchronize()
     dp_s = (time.perf_counter() - t1) / dp_reps
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            pk.parcae_liveput_plan(prob, ev_out, pl_out)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            pk.parcae_liveput_plan(prob, ev_out, pl_out)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t2) / args.steps * 1e3
+
     status = pl_out.status.cpu().numpy()
     ms_per_step = dt / args.steps * 1e3
     achieved = alg_ops / kern_avg_s
@@ -239,6 +261,8 @@ def main():
                              "instruction); 32-bit multiplies, left shifts, compares and popcounts issue at half "
                              "that rate, so a kernel with this mix cannot reach 1; measured VALU busy is in profiles/"},
     }
+    if graph_ms is not None:
+        out["graph_replay_ms_per_step"] = graph_ms
     if not args.no_cpu_baseline:
         per_query = T * C * S
         threads_hint = args.cpu_threads or (os.cpu_count() or 1)

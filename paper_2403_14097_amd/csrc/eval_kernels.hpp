@@ -738,37 +738,56 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     uint32_t* bins = bins_all[wave];
     uint32_t* lds_col = lmask + threadIdx.x;
     const uint32_t total = *wq.count * (uint32_t)n_chunks;
-    // A wave claims `batch` consecutive items at a time (about eight claims per wave over the launch), first
-    // from its home shard, then from the following shards; a shard is probed with a plain load before the
-    // atomic, so exhausted shards cost no serialised traffic.  Every wave leaves after at most
-    // kQueueShards failed probes.
+    // A wave claims `batch` consecutive items at a time (about eight claims per wave over the launch) from its
+    // current shard, which is its home shard until that runs dry.  Then it looks at all shard counters AT ONCE (one
+    // load per lane, one round trip) and moves to the next shard that still has items; a walk over the shards one
+    // probe after the other would cost a memory round trip per shard in every wave at the end of the launch.  A wave
+    // leaves when no shard has items left; counters only grow, so that point is reached.
     const uint32_t per_shard = (total + kQueueShards - 1u) / kQueueShards;
     uint32_t batch = total / ((uint32_t)gridDim.x * kWaves * 8u);
     batch = batch < 1u ? 1u : (batch > 64u ? 64u : batch);
-    const uint32_t home = ((uint32_t)blockIdx.x * kWaves + wave) % kQueueShards;
-    uint32_t visited = 0u;
+    const uint32_t wave_id = (uint32_t)blockIdx.x * kWaves + wave;
+    uint32_t shard = wave_id % kQueueShards;
     uint32_t item = 0u, item_end = 0u;
 
     for (;;) {
-        while (item == item_end && visited < (uint32_t)kQueueShards) {
-            const uint32_t shard = (home + visited) % kQueueShards;
+        bool drained = false;
+        while (item == item_end) {
             const uint32_t lo = shard * per_shard;
             uint32_t hi = lo + per_shard;
             hi = hi > total ? total : hi;
-            uint32_t first = hi;
-            if (lo < hi && __hip_atomic_load(&wq.next[shard * kShardStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < hi - lo) {
+            if (lo < hi) {
                 uint32_t got = 0u;
                 if (lane == 0) got = atomicAdd(&wq.next[shard * kShardStride], batch);
-                first = lo + __builtin_amdgcn_readfirstlane(got);
+                const uint32_t first = lo + __builtin_amdgcn_readfirstlane(got);
+                if (first < hi) {
+                    item = first;
+                    item_end = first + batch < hi ? first + batch : hi;
+                    break;
+                }
             }
-            if (first < hi) {
-                item = first;
-                item_end = first + batch < hi ? first + batch : hi;
-            } else {
-                ++visited;
+            bool has_items = false;
+            if (lane < kQueueShards) {
+                const uint32_t l = (uint32_t)lane * per_shard;
+                uint32_t h = l + per_shard;
+                h = h > total ? total : h;
+                const uint32_t taken =
+                    __hip_atomic_load(&wq.next[lane * kShardStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                has_items = l < h && taken < h - l;
             }
+            const unsigned long long open = __ballot(has_items);
+            if (open == 0ull) {
+                drained = true;
+                break;
+            }
+            // move to one of the open shards, a different one for different waves (all waves heading for the same
+            // shard would queue up on its counter)
+            const uint32_t pick = wave_id % (uint32_t)__popcll(open);
+            unsigned long long rest = open;
+            for (uint32_t i = 0; i < pick; ++i) rest &= rest - 1ull;  // drop the lowest set bit
+            shard = (uint32_t)__builtin_ctzll(rest);
         }
-        if (item == item_end) break;
+        if (drained) break;
         const uint32_t unit_global = wq.list[item / (uint32_t)n_chunks];
         const int chunk = (int)(item % (uint32_t)n_chunks);
         ++item;
