@@ -609,6 +609,8 @@ constexpr int kEvalThreads = 256;
 // ranges, each with its own claim counter: atomics on ONE address complete at a fixed, low rate (about 86
 // per microsecond on this chip), which a single counter would turn into the bottleneck of small launches.
 constexpr int kQueueShards = 32;
+constexpr uint32_t kClaimsPerWave = 32;  // claims a wave makes over a launch if all waves take equal shares (measured: 8 leaves a
+                                        // 4 % longer tail on a 1024-query batch, 128 is no better)
 constexpr int kShardStride = 64;  // counters sit 256 bytes apart: atomics on one cache line serialise too
 struct WorkQueue {
     uint32_t* list;   // [n_units] global unit indices (q * T * C + t * C + c) that need sampling, any order
@@ -738,59 +740,55 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     uint32_t* bins = bins_all[wave];
     uint32_t* lds_col = lmask + threadIdx.x;
     const uint32_t total = *wq.count * (uint32_t)n_chunks;
-    // A wave claims `batch` consecutive items at a time (about eight claims per wave over the launch) from its
-    // current shard, which is its home shard until that runs dry.  Then it looks at all shard counters AT ONCE (one
-    // load per lane, one round trip) and moves to the next shard that still has items; a walk over the shards one
-    // probe after the other would cost a memory round trip per shard in every wave at the end of the launch.  A wave
-    // leaves when no shard has items left; counters only grow, so that point is reached.
-    const uint32_t per_shard = (total + kQueueShards - 1u) / kQueueShards;
-    uint32_t batch = total / ((uint32_t)gridDim.x * kWaves * 8u);
+    // Shard s holds the items g with g mod kQueueShards == s (neighbouring items cost about the same, whole ranges of
+    // the list do not: interleaving gives every shard the same mix).  A wave claims `batch` items of its current
+    // shard at a time; that is its home shard until it runs dry.  Then the wave looks at all shard counters AT ONCE
+    // (one load per lane, one round trip) and moves to one of the shards that still have items, a different one for
+    // different waves; a walk over the shards one probe after the other would cost a memory round trip per shard in
+    // every wave at the end of the launch.  A wave leaves when no shard has items left; counters only grow, so that
+    // point is reached.
+    auto shard_size = [&](uint32_t s) { return s < total ? (total - s + kQueueShards - 1u) / kQueueShards : 0u; };
+    uint32_t batch = total / ((uint32_t)gridDim.x * kWaves * kClaimsPerWave);
     batch = batch < 1u ? 1u : (batch > 64u ? 64u : batch);
     const uint32_t wave_id = (uint32_t)blockIdx.x * kWaves + wave;
     uint32_t shard = wave_id % kQueueShards;
-    uint32_t item = 0u, item_end = 0u;
+    uint32_t slot = 0u, slot_end = 0u;  // position inside the shard: item = slot * kQueueShards + shard
 
     for (;;) {
         bool drained = false;
-        while (item == item_end) {
-            const uint32_t lo = shard * per_shard;
-            uint32_t hi = lo + per_shard;
-            hi = hi > total ? total : hi;
-            if (lo < hi) {
+        while (slot == slot_end) {
+            const uint32_t size = shard_size(shard);
+            if (size > 0u) {
                 uint32_t got = 0u;
                 if (lane == 0) got = atomicAdd(&wq.next[shard * kShardStride], batch);
-                const uint32_t first = lo + __builtin_amdgcn_readfirstlane(got);
-                if (first < hi) {
-                    item = first;
-                    item_end = first + batch < hi ? first + batch : hi;
+                const uint32_t first = __builtin_amdgcn_readfirstlane(got);
+                if (first < size) {
+                    slot = first;
+                    slot_end = first + batch < size ? first + batch : size;
                     break;
                 }
             }
             bool has_items = false;
             if (lane < kQueueShards) {
-                const uint32_t l = (uint32_t)lane * per_shard;
-                uint32_t h = l + per_shard;
-                h = h > total ? total : h;
                 const uint32_t taken =
                     __hip_atomic_load(&wq.next[lane * kShardStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                has_items = l < h && taken < h - l;
+                has_items = taken < shard_size((uint32_t)lane);
             }
             const unsigned long long open = __ballot(has_items);
             if (open == 0ull) {
                 drained = true;
                 break;
             }
-            // move to one of the open shards, a different one for different waves (all waves heading for the same
-            // shard would queue up on its counter)
             const uint32_t pick = wave_id % (uint32_t)__popcll(open);
             unsigned long long rest = open;
             for (uint32_t i = 0; i < pick; ++i) rest &= rest - 1ull;  // drop the lowest set bit
             shard = (uint32_t)__builtin_ctzll(rest);
         }
         if (drained) break;
+        const uint32_t item = slot * kQueueShards + shard;
+        ++slot;
         const uint32_t unit_global = wq.list[item / (uint32_t)n_chunks];
         const int chunk = (int)(item % (uint32_t)n_chunks);
-        ++item;
         const int tc = (int)(unit_global % (uint32_t)(b.T * b.C));
         const int q = (int)(unit_global / (uint32_t)(b.T * b.C));
         const int t = tc / b.C;
