@@ -519,26 +519,34 @@ __device__ __forceinline__ void reduce_large_depth(const Mask<NW>& mask, int D, 
     d_min = D - worst;
 }
 
-template <int NW>
-__device__ __forceinline__ void reduce_mask_any_depth(const Mask<NW>& mask, int D, int P, int& n_int, int& d_min)
+// Which reducer a grid shape takes.  The choice depends on the unit only, so the sampling loop is compiled once
+// per kind: each copy then carries only its own loop-invariant masks in scalar registers (with all kinds inside
+// one loop the invariants of every kind were live at once and spilled).
+enum ReducerKind {
+    kPow2Narrow = 0,   // P in {1, 2, 4}: stage counts by popcounts of stride-P combs
+    kPow2Tree = 1,     // P in {8, 16, 32}: stage counts by vertical counters
+    kPow2Words = 2,    // P in {64, 128, 256}: a pipeline is whole words
+    kAnySmall = 3,     // other P <= 8: windows and period-P combs
+    kAnyMediumFew = 4, // other P < 32, at most 7 pipelines
+    kAnyMedium = 5,    // other P < 32, more pipelines
+    kAnyLarge = 6,     // other P > 32
+};
+
+__device__ __forceinline__ int reducer_kind(int D, int P, int log2P)
 {
-    if (P <= 8) {
-        reduce_small_depth<NW>(mask, D, P, n_int, d_min);
-    } else if (P < 32) {
-        if (D <= 7) reduce_medium_depth<NW, 3>(mask, D, P, n_int, d_min);
-        else reduce_medium_depth<NW, 5>(mask, D, P, n_int, d_min);
-    } else {
-        if constexpr (NW >= 2) reduce_large_depth<NW>(mask, D, P, n_int, d_min);
-        else { n_int = D; d_min = D; }  // unreachable: more than 32 stages need more than one word
-    }
+    if (log2P >= 0 && P <= 32) return P <= 4 ? kPow2Narrow : kPow2Tree;
+    if (log2P >= 6) return kPow2Words;
+    if (P <= 8) return kAnySmall;
+    if (P < 32) return D <= 7 ? kAnyMediumFew : kAnyMedium;
+    return kAnyLarge;
 }
 
 // n_int (pipelines without a preempted instance) and d_min (fewest survivors in any stage)
 // of a D x P grid whose preempted instances are the set bits of mask; instance j = d * P + s.
-template <int NW>
-__device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, int log2P, int& n_int, int& d_min)
+template <int NW, int KIND>
+__device__ __forceinline__ void reduce_kind(const Mask<NW>& mask, int D, int P, int log2P, int& n_int, int& d_min)
 {
-    if (log2P >= 0 && P <= 32) {
+    if constexpr (KIND == kPow2Narrow || KIND == kPow2Tree) {
         // pipelines: OR-fold every aligned P-bit group onto its lowest bit
         const uint32_t comb = comb32(log2P);
         int broken = 0;
@@ -548,7 +556,7 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
             broken += __popc(y & comb);
         });
         n_int = D - broken;
-        if (P <= 4) {
+        if constexpr (KIND == kPow2Narrow) {
             // stages: popcount of the stride-P comb shifted to the stage
             int worst = 0;
             for (int s = 0; s < P; ++s) {
@@ -561,7 +569,7 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
         } else {
             d_min = D - worst_stage_tree<NW>(mask, P);
         }
-    } else if (log2P >= 6) {
+    } else if constexpr (KIND == kPow2Words) {
         // P in {64, 128, 256}: a pipeline is P/32 whole words, D <= 4
         int broken = 0, worst = 0;
         if constexpr (NW >= 2) {
@@ -587,9 +595,39 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
         }
         n_int = D - broken;
         d_min = D - worst;
+    } else if constexpr (KIND == kAnySmall) {
+        reduce_small_depth<NW>(mask, D, P, n_int, d_min);
+    } else if constexpr (KIND == kAnyMediumFew) {
+        reduce_medium_depth<NW, 3>(mask, D, P, n_int, d_min);
+    } else if constexpr (KIND == kAnyMedium) {
+        reduce_medium_depth<NW, 5>(mask, D, P, n_int, d_min);
     } else {
-        reduce_mask_any_depth<NW>(mask, D, P, n_int, d_min);
+        if constexpr (NW >= 2) reduce_large_depth<NW>(mask, D, P, n_int, d_min);
+        else { n_int = D; d_min = D; }  // unreachable: more than 32 stages need more than one word
     }
+}
+
+// Calls f(integral_constant<int, kind>) for the reducer kind of the grid shape.
+template <typename F>
+__device__ __forceinline__ void with_reducer_kind(int D, int P, int log2P, F&& f)
+{
+    switch (reducer_kind(D, P, log2P)) {
+        case kPow2Narrow: f(std::integral_constant<int, kPow2Narrow>{}); break;
+        case kPow2Tree: f(std::integral_constant<int, kPow2Tree>{}); break;
+        case kPow2Words: f(std::integral_constant<int, kPow2Words>{}); break;
+        case kAnySmall: f(std::integral_constant<int, kAnySmall>{}); break;
+        case kAnyMediumFew: f(std::integral_constant<int, kAnyMediumFew>{}); break;
+        case kAnyMedium: f(std::integral_constant<int, kAnyMedium>{}); break;
+        default: f(std::integral_constant<int, kAnyLarge>{}); break;
+    }
+}
+
+template <int NW>
+__device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, int log2P, int& n_int, int& d_min)
+{
+    with_reducer_kind(D, P, log2P, [&](auto kind) {
+        reduce_kind<NW, decltype(kind)::value>(mask, D, P, log2P, n_int, d_min);
+    });
 }
 
 // ------------------------------------------------------------------ histogram update
@@ -702,7 +740,7 @@ __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col,
 
 // One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.  zc: zones of the pool, or null for the
 // uniform draw.
-template <int NW, bool kZoned>
+template <int NW, bool kZoned, int KIND>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int M, int k, uint32_t unit,
                                                 uint32_t stream_id, const PhiloxKeys& ks, uint32_t s_begin,
                                                 uint32_t s_end, uint32_t* lds_col, uint32_t* bins_int,
@@ -715,7 +753,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
         if constexpr (kZoned) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
         else draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
         if (M > rows * cr.P) mask.keep_below(rows * cr.P);  // idle instances of the pool are not on the grid
-        reduce_mask<NW>(mask, rows, cr.P, cr.log2P, n_int, d_min);
+        reduce_kind<NW, KIND>(mask, rows, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int * group, true);
         hist_add(bins_min, d_min * group, true);
     }
@@ -813,10 +851,20 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
 
         ZoneCtx zc;
         if constexpr (kZoned) zc = zone_setup(b, q, M, zone_perm[wave], zone_mask[wave]);
-        if (M <= 32) eval_unit_chunk<1, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
-        else if (M <= 64) eval_unit_chunk<2, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
-        else if (M <= 128) eval_unit_chunk<4, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
-        else eval_unit_chunk<8, kZoned>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+        with_reducer_kind(cr.D / b.group, cr.P, cr.log2P, [&](auto kind) {
+            constexpr int K = decltype(kind)::value;
+            // kinds that need more than 32 stages cannot meet a one-word pool
+            if (M <= 32) {
+                if constexpr (K != kPow2Words && K != kAnyLarge)
+                    eval_unit_chunk<1, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+            } else if (M <= 64) {
+                eval_unit_chunk<2, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+            } else if (M <= 128) {
+                eval_unit_chunk<4, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+            } else {
+                eval_unit_chunk<8, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+            }
+        });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
