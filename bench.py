@@ -26,6 +26,30 @@ if ROOT not in sys.path:
 ALU_PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
 
 
+# HBM traffic of the sampling kernel per launch, from the rocprofv3 --pmc runs summarised under profiles/
+# (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel of known size), in bytes: (read, written).  The figures
+# belong to the kernel sources with the digest below; once a source file changes they are withheld (traffic: null)
+# until the counters are taken again.
+TRAFFIC_SOURCE_SHA256 = "136565cdd497e5cc867c203aa85e62a68d5e4e7118e7f95e8bc6640b2075803a"
+TRAFFIC_BYTES = {"sweep": (20.04e6, 125.96e6), "large": (4.63e6, 30.24e6)}
+
+
+def kernel_traffic(workload_tag: str):
+    """Measured HBM bytes per launch of the sampling kernel for this workload, or None."""
+    import glob
+    import hashlib
+    if workload_tag not in TRAFFIC_BYTES:
+        return None
+    digest = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2403_14097_amd", "csrc", "*"))):
+        with open(path, "rb") as fh:
+            digest.update(fh.read())
+    if digest.hexdigest() != TRAFFIC_SOURCE_SHA256:
+        return None
+    read, written = TRAFFIC_BYTES[workload_tag]
+    return read + written
+
+
 def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False, zoned=False):
     """Sum over units of S * A(M, k, P): the 32-bit lane operations the method itself needs.
 
@@ -229,6 +253,8 @@ def main():
         graph_ms = (time.perf_counter() - t2) / args.steps * 1e3
 
     status = pl_out.status.cpu().numpy()
+    plain = not (args.dense or args.pool_all or args.zones or args.rounds or args.queries)
+    out_tag = batch.name if plain else ""
     ms_per_step = dt / args.steps * 1e3
     achieved = alg_ops / kern_avg_s
     out = {
@@ -253,7 +279,8 @@ def main():
         "dp_ms": dp_s * 1e3,
         "sampling_kernel_ms": kern_avg_s * 1e3,
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
+                     "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
+                     "traffic": kernel_traffic(out_tag), "traffic_unit": "bytes per launch (HBM read + written)",
                      "kernel": "eval_hist_kernel", "algorithmic_lane_ops_per_launch": alg_ops,
                      "note": "algorithmic lane-ops per launch follow the per-scenario formula in DESIGN.md (textbook "
                              "operation count of the method); peak = 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz, the "
