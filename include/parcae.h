@@ -270,6 +270,9 @@ int parcae_liveput_eval(const parcae_problem *p, uint32_t *hist_int, uint32_t *h
  *   objective           DEVICE out [nq] float, or NULL
  *   status              DEVICE out [nq] int32, or NULL: PARCAE_OK, PARCAE_EINVAL
  *                       (bad DEVICE inputs) or PARCAE_EINFEASIBLE
+ * Limit: the per-candidate tables of a query are kept in the local memory of one
+ * workgroup, which holds about 1000 candidates; a longer list is refused with
+ * PARCAE_EINVAL before anything is enqueued (parcae_liveput_eval has no such limit).
  */
 int parcae_plan_from_hist(const parcae_problem *p, const uint32_t *hist_int, const uint32_t *hist_min, float *F,
                           int32_t *bp, int32_t *plan, int32_t *start, float *objective, int32_t *status,

@@ -387,6 +387,7 @@ int parcae_plan_from_hist(const parcae_problem* p, const uint32_t* hist_int, con
     if (rc != PARCAE_OK) return rc;
     if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
+    if (!plan_fits(p, lay)) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;

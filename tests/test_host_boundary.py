@@ -101,6 +101,31 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.parcae_debug_sample(ct.byref(prob), 1, 0, 0, 0, 8, fake, fake, fake, fake, need.value, None) == pk.PARCAE_EINVAL
 
 
+def test_zone_and_candidate_limits_are_checked_on_the_host():
+    lib = pk.load_library()
+    out = ct.c_size_t(0)
+    fake = 0x1000
+    prob, keep = _problem([(1, 1), (2, 1)])
+    prob.n_zones = 5                                   # more zones than the library has
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.n_zones = -1
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.n_zones = 2                                   # zones without their tables
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.zone, prob.zone_weight = fake, fake
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    # every (D, P) with D * P <= 256: about 1500 candidates, more than the planning kernels hold
+    many = [(d, p) for p in range(1, 257) for d in range(1, 256 // p + 1)]
+    assert len(many) > 1200
+    big, keep2 = _problem(many, N=256, T=2)
+    assert lib.parcae_workspace_bytes(ct.byref(big), ct.byref(out)) == pk.PARCAE_OK
+    ws = 0x100000
+    assert lib.parcae_plan_from_hist(ct.byref(big), fake, fake, None, None, fake, None, None, None, ws, out.value,
+                                     None) == pk.PARCAE_EINVAL
+    assert lib.parcae_liveput_plan(ct.byref(big), fake, fake, None, None, None, None, None, fake, None, None, None,
+                                   ws, out.value, None) == pk.PARCAE_EINVAL
+
+
 def test_product_has_no_cpu_path():
     """Without a GPU the binding raises instead of computing anything."""
     import torch
