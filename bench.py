@@ -30,8 +30,8 @@ ALU_PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
 # (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel of known size), in bytes: (read, written).  The figures
 # belong to the sampling kernel's sources (device_common.hpp, eval_kernels.hpp) with the digest below; once one of
 # them changes the figures are withheld (traffic: null) until the counters are taken again.
-TRAFFIC_SOURCE_SHA256 = "1c161543a5ad35cdbd4b37468e6f90a15595fb431ed175ffe141cc246ca6cc9d"
-TRAFFIC_BYTES = {"sweep": (20.04e6, 125.96e6), "large": (4.63e6, 30.24e6)}
+TRAFFIC_SOURCE_SHA256 = "06d81d070ccd57870750222eade0eb43e6b9953b7f6d5a7713c67d521248723f"
+TRAFFIC_BYTES = {"sweep": (20.10e6, 125.96e6), "large": (4.41e6, 30.23e6)}
 
 
 def kernel_traffic(workload_tag: str):

@@ -643,12 +643,14 @@ __device__ __forceinline__ void hist_add(uint32_t* bins, int val, bool active)
 
 constexpr int kEvalThreads = 256;
 
-// Work queue of the sampling kernel, in the workspace.  The items are split into kQueueShards contiguous
-// ranges, each with its own claim counter: atomics on ONE address complete at a fixed, low rate (about 86
-// per microsecond on this chip), which a single counter would turn into the bottleneck of small launches.
+// Work queue of the sampling kernel, in the workspace.  The items are dealt to kQueueShards shards (item g
+// belongs to shard g mod kQueueShards), each with its own claim counter: atomics on ONE address complete at a
+// fixed, low rate (about 86 per microsecond on this chip), which a single counter would turn into the
+// bottleneck of small launches.
 constexpr int kQueueShards = 32;
-constexpr uint32_t kClaimsPerWave = 32;  // claims a wave makes over a launch if all waves take equal shares (measured: 8 leaves a
-                                        // 4 % longer tail on a 1024-query batch, 128 is no better)
+// Claims a wave makes over a launch if all waves take equal shares (measured: 8 leaves a 4 % longer tail on a
+// 1024-query batch, 128 is no better).
+constexpr uint32_t kClaimsPerWave = 32;
 constexpr int kShardStride = 64;  // counters sit 256 bytes apart: atomics on one cache line serialise too
 struct WorkQueue {
     uint32_t* list;   // [n_units] global unit indices (q * T * C + t * C + c) that need sampling, any order
