@@ -164,7 +164,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU; --gpus N with N > 1 is not supported "
-              "(queries would shard across GPUs with no exchange, which this build does not launch)", file=sys.stderr)
+              "(queries would shard across GPUs with no exchange, which this program does not launch)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -281,8 +281,8 @@ def main():
                      "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
                      "traffic": kernel_traffic(out_tag), "traffic_unit": "bytes per launch (HBM read + written)",
                      "kernel": "eval_hist_kernel", "algorithmic_lane_ops_per_launch": alg_ops,
-                     "note": "algorithmic lane-ops per launch follow the per-scenario formula in DESIGN.md (textbook "
-                             "operation count of the method); peak = 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz, the "
+                     "note": "algorithmic lane-ops per launch = sum over units of S * A(M, k, P), the textbook operation count "
+                             "of the method (see algorithmic_lane_ops); peak = 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz, the "
                              "rate at which gfx950 issues simple 32-bit vector ops (measured 2.2 cycles per wave64 "
                              "instruction); 32-bit multiplies, left shifts, compares and popcounts issue at half "
                              "that rate, so a kernel with this mix cannot reach 1; measured VALU busy is in profiles/"},
