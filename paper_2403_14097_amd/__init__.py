@@ -191,7 +191,7 @@ def problem_from_arrays(n_instances, n_intervals, interval_sec, p_min, n_scenari
     import numpy as np
 
     def up(a, dt):
-        return torch.from_numpy(np.ascontiguousarray(a).astype(dt, copy=False)).to(device)
+        return torch.from_numpy(np.array(a, dtype=dt, order="C")).to(device)   # a writable, contiguous copy
 
     seed_dev = up(np.asarray(seed, dtype=np.uint64).view(np.int64), np.int64)
     sid = None if stream_id is None else up(np.asarray(stream_id, dtype=np.uint32).view(np.int32), np.int32)
