@@ -228,6 +228,7 @@ struct PlanShared {
 };
 
 constexpr int kPlanThreads = 256;
+constexpr int kStreamRegs = 2;  // registers per thread and histogram that hold the rows of the next step (512 bins)
 constexpr uint16_t kNoPred16 = 0xffffu;
 
 // per_query: the layout of plan_fused_kernel (value function, offers, depth groups); else that of transition_kernel.
@@ -628,9 +629,36 @@ __global__ void __launch_bounds__(kPlanThreads) plan_fused_kernel(
         sh.key[c] = 0ull;
     };
     for (int c = tid; c < C; c += kPlanThreads) open_step(0, c, 0.0f, a_prev, a_next);
+    // streamed: the rows of a step fit in LDS at once and in kStreamRegs registers per thread; the rows of step t + 1
+    // are read into registers while step t runs, so the memory latency is off the chain of steps
+    const bool streamed = !resident && sh.n_chunks == 1 && b.L <= kStreamRegs * kPlanThreads;
+    uint32_t next_int[kStreamRegs], next_min[kStreamRegs];
+    auto fetch_rows = [&](int t) __attribute__((always_inline)) {
+        const int64_t base = ((int64_t)q * b.T + t) * b.L;
+        static_for<kStreamRegs>([&](auto x) {
+            const int i = x.value * kPlanThreads + tid;
+            next_int[x.value] = hist_int[base + (i < b.L ? i : 0)];  // unconditional, on a clamped index
+            next_min[x.value] = hist_min[base + (i < b.L ? i : 0)];
+        });
+    };
+    if (streamed) fetch_rows(0);
     __syncthreads();
     for (int t = 0; t < b.T; ++t) {
         const int a_after = av[t + 2 <= b.T ? t + 2 : b.T];
+        if (streamed) {
+            // nobody reads the previous rows any more (barrier at the end of the previous step)
+            static_for<kStreamRegs>([&](auto x) {
+                const int i = x.value * kPlanThreads + tid;
+                if (i < b.L) {
+                    sh.tail_int[i] = next_int[x.value];
+                    sh.tail_min[i] = next_min[x.value];
+                }
+            });
+            __syncthreads();
+            for (int c = tid; c < C; c += kPlanThreads) suffix_row(sh, sh.cfg[c], sh.cfg[c].off);
+            fetch_rows(t + 1 < b.T ? t + 1 : t);
+            // the different-depth offers below do not touch the rows; the barrier before the tiles orders the sums
+        }
         if (t == 0 && cur == -2) {
             // nothing is running: every candidate can only be "reached from itself", at its re-partition cost
             for (int c2 = tid; c2 < C; c2 += kPlanThreads)
@@ -668,7 +696,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_fused_kernel(
             }
             for (int ch = 0; ch < n_chunks; ++ch) {
                 const int c_lo = resident ? 0 : sh.chunk_start[ch], c_hi = resident ? C : sh.chunk_start[ch + 1];
-                if (!resident) load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);  // barriers before and after
+                if (streamed) __syncthreads();
+                else if (!resident) load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);  // barriers before and after
                 const int first = sh.cfg[c_lo].off;
                 auto tiles = [&](auto rounds, auto batch) __attribute__((always_inline)) {
                     constexpr int kTileBatch = decltype(batch)::value;
