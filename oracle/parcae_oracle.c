@@ -43,6 +43,7 @@
 #endif
 
 #define ORC_MAX_INSTANCES 256
+#define ORC_MAX_GROUP 64 /* GPUs per instance: a grid of D x P GPUs has at most ORC_MAX_INSTANCES * ORC_MAX_GROUP of them */
 
 /* ---------------------------------------------------------------- Philox */
 
@@ -241,7 +242,7 @@ static void scenario(int D, int P, int group, int M, int k, int n_zones, const u
     if (group <= 1) {
         orc_reduce(D, P, pool_pre, n_int, d_min, NULL);
     } else {
-        uint8_t gpu[ORC_MAX_INSTANCES];
+        uint8_t gpu[ORC_MAX_INSTANCES * ORC_MAX_GROUP];
         orc_expand_groups(D, P, group, pool_pre, gpu);
         orc_reduce(D, P, gpu, n_int, d_min, NULL);
     }

@@ -601,6 +601,69 @@ def test_transfer_round_costs_in_the_replay_and_bad_values(pk):
     assert list(_np(pl.status)) == [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, 0]
 
 
+# ------------------------------------------------------------------ randomly drawn problems
+
+def _random_problem(rng):
+    """A small problem with every option drawn at random: sizes, depth list, pool, instance size, zones, round
+    costs, start state, scenario count (mostly not a power of two), queries on either side of the planner switch."""
+    group = [1, 1, 1, 2, 4][rng.randint(0, 4)]
+    n_inst = rng.randint(1, 256 if rng.randint(0, 3) == 0 else 48)
+    depth_pool = [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 13, 16, 23, 31, 32, 33, 48, 64, 65, 100, 128, 200, 256]
+    depths = sorted({depth_pool[rng.randint(0, len(depth_pool) - 1)] for _ in range(rng.randint(1, 5))})
+    depths = [p for p in depths if p <= n_inst] or [1]
+    p_min = depths[rng.randint(0, len(depths) - 1)] if rng.randint(0, 2) == 0 else 1
+    cfg = pi.candidate_list(n_inst, depths, p_min, feasible_only=rng.randint(0, 1) == 1)
+    if len(cfg) == 0:
+        cfg = pi.candidate_list(n_inst, depths, 1)
+    if len(cfg) > 120:                                   # keep the oracle quick: a random subset, order preserved
+        keep = sorted({rng.randint(0, len(cfg) - 1) for _ in range(120)})
+        cfg = cfg[keep]
+    cfg = cfg.copy()
+    cfg[:, 0] *= group                                    # D counts GPUs: multiples of the instance size
+    cfg = cfg[cfg[:, 0] <= 256]
+    nq = [1, 2, 33][rng.randint(0, 2)]
+    T = rng.randint(1, 5)
+    S = [1, 63, 64, 65, 200, 256, 300][rng.randint(0, 6)]
+    avail = [[rng.randint(0, n_inst) for _ in range(T + 1)] for _ in range(nq)]
+    thr = [rng.uniform(0.5, 3.0) for _ in range(len(cfg))]
+    cost = [[rng.uniform(0.0, 3.0), rng.uniform(3.0, 20.0), rng.uniform(20.0, 70.0)] for _ in range(len(cfg))]
+    b = pi.custom_batch(n_inst, cfg, avail, thr_per_pipeline=thr, cost=cost, interval_sec=[30.0, 60.0][rng.randint(0, 1)],
+                        p_min=p_min, n_scenarios=S, seed=rng.randint(1, 1 << 30), group_size=group)
+    for q in range(nq):
+        b.cur_config[q] = [-2, -1, rng.randint(0, len(cfg) - 1)][rng.randint(0, 2)]
+        b.stream_id[q] = rng.randint(0, 1000)
+    if rng.randint(0, 2) == 0:
+        b = b.with_zones(rng.randint(1, 4), seed=rng.randint(1, 999), max_weight=[3, 255][rng.randint(0, 1)])
+    if rng.randint(0, 2) == 0:
+        b = b.with_rounds(0.0, 25.0, seed=rng.randint(1, 999))
+    return b, rng.randint(0, 1) == 1
+
+
+def test_random_problems_match_the_oracle(pk):
+    rng = pi.SplitMix64(0xF00D)
+    for case in range(40):
+        b, pool_all = _random_problem(rng)
+        p = pk.upload(b)
+        if pool_all:
+            p.flags = pk.PARCAE_POOL_ALL
+        ev, pl = pk.parcae_liveput_plan(p)
+        W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+        _sync()
+        tag = (case, b.n_instances, b.n_configs, b.n_queries, b.n_intervals, b.n_scenarios, b.group_size, b.n_zones,
+               b.cost_round is not None, pool_all)
+        for q in sorted({0, b.n_queries - 1}):
+            r = oracle.run_query(b, q, n_threads=8, pool_all=pool_all)
+            assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int), tag
+            assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min), tag
+            assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f), tag
+            assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f), tag
+            assert np.array_equal(_np(W[q]), r.W_f), tag
+            assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F), tag
+            assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and int(pl.start[q]) == r.plan.start, tag
+            assert float(pl.objective[q]) == r.plan.objective, tag
+            assert int(pl.status[q]) == (pk.PARCAE_OK if r.plan.feasible else pk.PARCAE_EINFEASIBLE), tag
+
+
 # ------------------------------------------------------------------ receding-horizon replay
 
 def _replay_inputs(b, H, noise_seed):

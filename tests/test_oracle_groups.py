@@ -68,7 +68,9 @@ def test_histograms_against_exact_enumeration_of_instance_subsets(D, P, g, k):
 
 def test_same_as_the_instance_grid_scaled_by_the_group_size():
     """A D x P grid of g-GPU instances behaves like a (D / g) x P grid of instances, counts times g."""
-    for D, P, g, a_next, a_prev in [(8, 4, 2, 11, -1), (12, 2, 4, 4, -1), (8, 8, 2, 20, 40), (16, 4, 4, 9, 30)]:
+    # the last two grids hold more than 256 GPUs (1024 and 16384): D * P counts GPUs, only instances are capped
+    for D, P, g, a_next, a_prev in [(8, 4, 2, 11, -1), (12, 2, 4, 4, -1), (8, 8, 2, 20, 40), (16, 4, 4, 9, 30),
+                                    (128, 8, 4, 200, -1), (256, 64, 64, 100, 256)]:
         big = oracle.eval_unit(D, P, a_next, 31, 2, 17, 0, 2000, a_prev=a_prev, group=g)
         small = oracle.eval_unit(D // g, P, a_next, 31, 2, 17, 0, 2000, a_prev=a_prev)
         for b_, s_ in zip(big, small):
