@@ -713,6 +713,35 @@ def test_replay_matches_the_oracle_replay(pk, nq, pool_all, zones):
             assert abs(float(total[q]) - r.total_d) <= REL * abs(r.total_d)
 
 
+def test_replay_on_randomly_drawn_problems(pk):
+    """Replay of both kinds on problems with every option drawn at random, walks and forecasts random too."""
+    import torch
+    from oracle import replay as rp
+    rng = pi.SplitMix64(0xBEEF)
+    for case in range(16):
+        b, pool_all = _random_problem(rng)
+        nq, T, N = b.n_queries, b.n_intervals, b.n_instances
+        H = rng.randint(1, 5)
+        true = np.asarray([[rng.randint(0, N) for _ in range(H + 1)] for _ in range(nq)], np.int32)
+        win = np.zeros((H, nq, T + 1), np.int32)
+        for i in range(H):
+            for q in range(nq):
+                win[i, q, 0] = true[q, i]
+                for t in range(T):
+                    win[i, q, 1 + t] = min(N, max(0, int(true[q, min(i + 1 + t, H)]) + rng.randint(-2, 2)))
+        p = pk.upload(b)
+        if pool_all:
+            p.flags = pk.PARCAE_POOL_ALL
+        t_true, t_win = torch.from_numpy(true).cuda(), torch.from_numpy(win).cuda()
+        for mode in (pk.PARCAE_REPLAY_PROACTIVE, pk.PARCAE_REPLAY_REACTIVE):
+            chosen, reward, total = pk.parcae_replay(p, t_true, t_win if mode == pk.PARCAE_REPLAY_PROACTIVE else None, mode)
+            _sync()
+            for q in sorted({0, nq - 1}):
+                r = rp.replay(b, q, true[q], win[:, q, :], mode, n_threads=8, pool_all=pool_all)
+                assert np.array_equal(_np(chosen[q]), r.chosen), (case, mode, q)
+                assert np.array_equal(_np(reward[q]), r.reward) and float(total[q]) == r.total, (case, mode, q)
+
+
 def test_replay_suspends_and_restarts(pk):
     """Availability falls below the memory floor and comes back: nothing runs, then a cold start."""
     import torch
