@@ -171,14 +171,17 @@ size_t bp16_bytes_for(int T, int C)
     return need <= kMaxBpLds ? need : 0;
 }
 
-// Scenarios per work item of the sampling kernel (one wave processes an item, 64 scenarios at a time):
-// 1024 when there is plenty of work, down to 256 when there is little, so that every wave still gets
-// several items and a late heavy item cannot dominate the launch.
-int pick_chunk_len(int64_t n_units, int S, int64_t n_waves)
+// Scenarios per work item of the sampling kernel (one wave processes an item, 64 scenarios at a time), from
+// timings over batches of 1 to 1024 queries of every workload shape: 1024 suits nearly all of them (an item has
+// to be long enough to pay for its claim and its table loads, short enough that the last items do not leave the
+// chip half empty); very large launches gain a little from 2048, launches that cannot even give every wave two
+// rounds of 64 scenarios from 512; pools of more than 128 instances cost about twice as much per scenario, so
+// their items are half as long.  About a quarter of the units need sampling at all.
+int pick_chunk_len(int64_t n_units, int S, int n_instances, int64_t n_waves)
 {
-    int64_t want = n_units * (int64_t)S / (n_waves * 64);
-    int chunk = 1024;
-    while (chunk > 256 && chunk > want) chunk >>= 1;
+    const int64_t rounds_per_wave = n_units * (int64_t)S / 64 / 4 / n_waves;
+    int chunk = rounds_per_wave >= 1024 ? 2048 : (rounds_per_wave < 2 ? 512 : 1024);
+    if (n_instances > 128) chunk /= 2;
     return S < chunk ? S : chunk;
 }
 
@@ -200,7 +203,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return PARCAE_EHIP;
-    const int chunk_len = pick_chunk_len(n_units, b.S, (int64_t)cus * 32);
+    const int chunk_len = pick_chunk_len(n_units, b.S, b.N, (int64_t)cus * 28);
     const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
     if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counter to overshoot
     const parcae::WorkQueue wq = make_queue(lay, ws);
