@@ -491,30 +491,6 @@ __device__ __forceinline__ ColumnGrid column_grid(int C)
     return cg;
 }
 
-// Merges the per-group partial maxima of one column pass into (F_next, arg).  Called by every thread;
-// contains two barriers.
-__device__ __forceinline__ void merge_groups(const ColumnGrid& cg, int c2, int C, float best, int arg, float* red_val,
-                                             int* red_arg, float* F_next, int* arg_next)
-{
-    red_val[threadIdx.x] = best;
-    red_arg[threadIdx.x] = arg;
-    __syncthreads();
-    if (cg.g == 0 && c2 < C) {
-        float cur = F_next[c2];
-        int a = arg_next[c2];
-        for (int gg = 0; gg < cg.rg; ++gg) {
-            const float v = red_val[gg * cg.cw + cg.x];
-            if (v > cur) {
-                cur = v;
-                a = red_arg[gg * cg.cw + cg.x];
-            }
-        }
-        F_next[c2] = cur;
-        arg_next[c2] = a;
-    }
-    __syncthreads();
-}
-
 // Order-preserving map of a float to an unsigned integer (a larger float gives a larger key; no float maps to 0).
 __device__ __forceinline__ uint32_t float_key(float v)
 {
@@ -801,6 +777,8 @@ inline size_t dp_lds_bytes(int C, size_t bp16_bytes)
 // One block per query on weights held in memory: W[q][t][c][c'], c' contiguous.
 // Tiles of up to 64 x 64 candidates travel memory -> registers -> LDS two steps ahead of the step that
 // consumes them, so the T dependent steps never wait for memory; larger tiles are read in place.
+// A step: every thread scans a slice of the sources for its target column and offers its best to the target's
+// slot (see offer()); barrier; the thread of each target reads its slot, which becomes F of the next step.
 __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restrict__ W, int T, int C, int bp_in_lds,
                                                           const int32_t* __restrict__ valid, float* __restrict__ F,
                                                           int32_t* __restrict__ bp, int32_t* __restrict__ plan,
@@ -808,11 +786,8 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
                                                           int32_t* __restrict__ status, int einval, int einfeasible)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red_val[kPlanThreads];
-    __shared__ int red_arg[kPlanThreads];
-    float* Fc = reinterpret_cast<float*>(smem);
-    float* Fn = Fc + C;
-    int* argn = reinterpret_cast<int*>(Fn + C);
+    unsigned long long* key = reinterpret_cast<unsigned long long*>(smem);  // [C] offers of the step being built
+    float* Fc = reinterpret_cast<float*>(smem + 8 * (size_t)C);              // [C] value function of the previous step
     size_t o = 12 * (size_t)C;
     uint16_t* bp16 = bp_in_lds ? reinterpret_cast<uint16_t*>(smem + o) : nullptr;
     if (bp_in_lds) o += (sizeof(uint16_t) * (size_t)T * (size_t)C + 15) & ~(size_t)15;
@@ -829,6 +804,7 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
     const float* Wq = W + (int64_t)q * T * C * C;
     for (int c = threadIdx.x; c < C; c += blockDim.x) {
         Fc[c] = 0.0f;
+        key[c] = 0ull;
         if (Fq) Fq[c] = 0.0f;
     }
     const int rpg = (C + cg.rg - 1) / cg.rg;
@@ -849,14 +825,9 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
     auto stash = [&](const float (&r)[kStageRegs], float* tile) __attribute__((always_inline)) {
         static_for<kStageRegs>([&](auto i) { tile[(int)threadIdx.x + kPlanThreads * i.value] = r[i.value]; });
     };
-    // one step: tile (LDS) or Wt (memory) -> Fn, argn, back-pointers
-    auto step = [&](int t, const float* tile) __attribute__((always_inline)) {
+    // offers of step t from the tile (LDS) or from W_t in memory; the caller puts a barrier after it
+    auto offers = [&](int t, const float* tile) __attribute__((always_inline)) {
         const float* Wt = Wq + (int64_t)t * n_w;
-        for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            Fn[c2] = kNegInf;
-            argn[c2] = -1;
-        }
-        __syncthreads();
         for (int base = 0; base < C; base += cg.cw) {
             const int c2 = base + cg.x;
             float best = kNegInf;
@@ -864,14 +835,21 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
             if (c2 < C) {
                 if (tile) scan_rows_memory(tile, C, c2, r0, r1, Fc, best, arg);
                 else scan_rows_memory(Wt, C, c2, r0, r1, Fc, best, arg);
+                if (arg >= 0) offer(&key[c2], best, arg);
             }
-            merge_groups(cg, c2, C, best, arg, red_val, red_arg, Fn, argn);
         }
+    };
+    // slots -> F, back-pointers; empties the slots; the caller puts a barrier after it
+    auto close = [&](int t) __attribute__((always_inline)) {
         for (int c2 = threadIdx.x; c2 < C; c2 += blockDim.x) {
-            const int a = argn[c2];
+            const unsigned long long k = key[c2];
+            const float v = k ? key_float((uint32_t)(k >> 32)) : kNegInf;
+            const int a = k ? (int)(0xffffffffu - (uint32_t)k) : -1;
+            Fc[c2] = v;
+            key[c2] = 0ull;
             if (bpq) bpq[(int64_t)t * C + c2] = a;
             if (bp16) bp16[t * C + c2] = a < 0 ? kNoPred16 : (uint16_t)a;
-            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = Fn[c2];
+            if (Fq) Fq[(int64_t)(t + 1) * C + c2] = v;
         }
     };
 
@@ -883,23 +861,27 @@ __global__ void __launch_bounds__(kPlanThreads) dp_kernel(const float* __restric
         for (int t = 0; t < T; t += 2) {
             // even step: tile0 holds W_t, rb holds W_{t+1}; ra is free for W_{t+2}
             fetch(t + 2, ra);
-            step(t, tile0);
+            offers(t, tile0);
             stash(rb, tile1);
             __syncthreads();
-            { float* tmp = Fc; Fc = Fn; Fn = tmp; }
+            close(t);
+            __syncthreads();
             if (t + 1 >= T) break;
             // odd step: tile1 holds W_{t+1}, ra holds W_{t+2}; rb is free for W_{t+3}
             fetch(t + 3, rb);
-            step(t + 1, tile1);
+            offers(t + 1, tile1);
             stash(ra, tile0);
             __syncthreads();
-            { float* tmp = Fc; Fc = Fn; Fn = tmp; }
+            close(t + 1);
+            __syncthreads();
         }
     } else {
+        __syncthreads();
         for (int t = 0; t < T; ++t) {
-            step(t, nullptr);
+            offers(t, nullptr);
             __syncthreads();
-            float* tmp = Fc; Fc = Fn; Fn = tmp;
+            close(t);
+            __syncthreads();
         }
     }
     if (threadIdx.x == 0)
