@@ -277,6 +277,13 @@ def main():
         "dp_cells_per_sec": cells / dp_s,
         "dp_ms": dp_s * 1e3,
         "sampling_kernel_ms": kern_avg_s * 1e3,
+        # The plan is a chain of T dependent steps per query: bound by the latency of a step (a handful of dependent
+        # LDS round trips and two barriers), not by a throughput roofline.  For reference: its rate against the ALU
+        # peak at 15 lane-ops per cell (weights formed on the fly) and against HBM at 8 bytes per cell (weights
+        # written and read once, the few-query path).
+        "dp_roofline": {"bound": "latency", "steps_in_chain": T, "us_per_step": dp_s * 1e6 / T,
+                        "alu_frac_at_15_ops_per_cell": cells / dp_s * 15 / ALU_PEAK_LANE_OPS,
+                        "hbm_frac_at_8_bytes_per_cell": cells / dp_s * 8 / 8e12},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
                      "traffic": kernel_traffic(out_tag), "traffic_unit": "bytes per launch (HBM read + written)",
