@@ -210,11 +210,11 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        prob.event_before_sampling, prob.event_after_sampling = pairs[i]
+        prob.profile_events = (pairs[i][0], pairs[i][1], None, None)
         pk.parcae_liveput_plan(prob, ev_out, pl_out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    prob.event_before_sampling = prob.event_after_sampling = None
+    prob.profile_events = None
     kern_ms = [events.elapsed_ms(a, b) for a, b in pairs]
     for a, b in pairs:
         events.destroy(a)

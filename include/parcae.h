@@ -91,7 +91,21 @@ typedef struct parcae_config {
     int32_t P; /* pipeline stages         */
 } parcae_config;
 
+/*
+ * Profiling hooks (HOST struct, optional).  Each member is a hipEvent_t passed as void*, or NULL.  The
+ * library records the event on the call's stream at the named point; it never waits for one.
+ */
+typedef struct parcae_profile {
+    void *event_before_sampling; /* right before the scenario sampling kernel is launched */
+    void *event_after_sampling;  /* right after it                                        */
+    void *event_before_plan;     /* right before the first kernel of the dynamic program  */
+    void *event_after_plan;      /* right after its last kernel                           */
+} parcae_profile;
+
 typedef struct parcae_problem {
+    uint32_t struct_size; /* sizeof(parcae_problem) of the caller's build: the structure only ever
+                             grows at its end, a library reads no member past this size (absent
+                             members count as 0 / NULL) and refuses a size below the first release's */
     int32_t n_queries;   /* nq >= 1                                                     */
     int32_t n_instances; /* N, 1..PARCAE_MAX_INSTANCES                                  */
     int32_t n_intervals; /* T >= 1 look-ahead intervals (the paper's I)                 */
@@ -109,9 +123,6 @@ typedef struct parcae_problem {
     const int32_t *cur_config;    /* DEVICE [nq] or NULL (= -1): index of the
                                      configuration running now, -1 = any,
                                      PARCAE_COLD_START = nothing is running            */
-    void *event_before_sampling;  /* hipEvent_t or NULL: recorded on the stream right
-                                     before the scenario sampling kernel is launched   */
-    void *event_after_sampling;   /* hipEvent_t or NULL: recorded right after it       */
     int32_t group_size;           /* g, GPUs per instance, 0 or 1 = single-GPU instances,
                                      at most 64; see "Multi-GPU instances" below         */
     int32_t n_zones;              /* 0 = every instance equally likely to be preempted;
@@ -122,6 +133,7 @@ typedef struct parcae_problem {
     const float *cost_round;      /* DEVICE [nq][C] or NULL (= 0): seconds per further
                                      state-transfer round of an inter-stage migration INTO
                                      configuration c, finite, >= 0; see "Transfer rounds"  */
+    const parcae_profile *profile; /* HOST or NULL: profiling hooks, read before the call returns */
 } parcae_problem;
 
 /*
@@ -298,8 +310,10 @@ int parcae_transition_weights(const parcae_problem *p, const uint32_t *hist_int,
 /*
  * Max-plus dynamic program on transition weights held in memory (Eq. 6).
  *   W  DEVICE in [nq][T][C][C] float; entries are finite or -inf (never NaN or +inf)
- *   other arguments as in parcae_plan_from_hist; status is PARCAE_OK or
- *   PARCAE_EINFEASIBLE.  Needs no workspace.  C <= 4096.
+ *   other arguments as in parcae_plan_from_hist, except that bp may be NULL only while
+ *   2 * T * C <= 16384 (the back-pointers are then kept in the workgroup's local memory;
+ *   larger problems walk back through bp in memory and PARCAE_EINVAL is returned without it);
+ *   status is PARCAE_OK or PARCAE_EINFEASIBLE.  Needs no workspace.  C <= 4096.
  */
 int parcae_dp_plan(const float *W, int32_t n_queries, int32_t n_intervals, int32_t n_configs, float *F,
                    int32_t *bp, int32_t *plan, int32_t *start, float *objective, int32_t *status, void *stream);
@@ -337,13 +351,18 @@ int parcae_debug_sample(const parcae_problem *p, int32_t q, int32_t t, int32_t c
  *               PARCAE_REPLAY_REACTIVE
  *   chosen      DEVICE out [nq][n_steps] int32: configuration of interval i + 1, -1 = none
  *   reward      DEVICE out [nq][n_steps] float;  total  DEVICE out [nq] float
- *   workspace   DEVICE, 256-byte aligned, >= parcae_replay_workspace_bytes()
+ *   status      DEVICE out [nq] int32, or NULL: PARCAE_OK, or PARCAE_EINVAL if the query's tables, its
+ *               cur_config (which must lie in [-2, C)), an entry of its true walk or of any of its windows
+ *               breaks the rules above (its outputs are then computed from clamped inputs, a cur_config
+ *               past the list counting as "nothing is running", and carry no meaning)
+ *   workspace   DEVICE, 256-byte aligned, >= parcae_replay_workspace_bytes() for the same mode
+ * The reactive mode never plans: it needs no planner workspace and has no limit on the candidate count.
  */
 #define PARCAE_REPLAY_PROACTIVE 0
 #define PARCAE_REPLAY_REACTIVE 1
-int parcae_replay_workspace_bytes(const parcae_problem *p, int32_t n_steps, size_t *bytes);
+int parcae_replay_workspace_bytes(const parcae_problem *p, int32_t n_steps, int32_t mode, size_t *bytes);
 int parcae_replay(const parcae_problem *p, int32_t n_steps, const int32_t *true_avail, const int32_t *windows,
-                  int32_t mode, int32_t *chosen, float *reward, float *total, void *workspace,
+                  int32_t mode, int32_t *chosen, float *reward, float *total, int32_t *status, void *workspace,
                   size_t workspace_bytes, void *stream);
 
 /* Static, NUL-terminated description of a return code (HOST). */

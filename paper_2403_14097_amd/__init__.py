@@ -48,17 +48,23 @@ class parcae_config(ct.Structure):
     _fields_ = [("D", ct.c_int32), ("P", ct.c_int32)]
 
 
+class parcae_profile(ct.Structure):
+    _fields_ = [("event_before_sampling", ct.c_void_p), ("event_after_sampling", ct.c_void_p),
+                ("event_before_plan", ct.c_void_p), ("event_after_plan", ct.c_void_p)]
+
+
 class parcae_problem(ct.Structure):
     _fields_ = [
+        ("struct_size", ct.c_uint32),
         ("n_queries", ct.c_int32), ("n_instances", ct.c_int32), ("n_intervals", ct.c_int32),
         ("n_configs", ct.c_int32), ("n_scenarios", ct.c_int32), ("p_min", ct.c_int32),
         ("interval_sec", ct.c_float), ("flags", ct.c_uint32),
         ("configs", ct.POINTER(parcae_config)),
         ("avail", ct.c_void_p), ("thr", ct.c_void_p), ("cost", ct.c_void_p), ("seed", ct.c_void_p),
         ("stream_id", ct.c_void_p), ("cur_config", ct.c_void_p),
-        ("event_before_sampling", ct.c_void_p), ("event_after_sampling", ct.c_void_p),
         ("group_size", ct.c_int32), ("n_zones", ct.c_int32),
         ("zone", ct.c_void_p), ("zone_weight", ct.c_void_p), ("cost_round", ct.c_void_p),
+        ("profile", ct.POINTER(parcae_profile)),
     ]
 
 
@@ -85,8 +91,8 @@ def load_library() -> ct.CDLL:
     lib.parcae_transition_weights.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.parcae_dp_plan.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.parcae_debug_sample.argtypes = [pp, i32, i32, i32, u32, u32, vp, vp, vp, vp, sz, vp]
-    lib.parcae_replay_workspace_bytes.argtypes = [pp, i32, ct.POINTER(sz)]
-    lib.parcae_replay.argtypes = [pp, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.parcae_replay_workspace_bytes.argtypes = [pp, i32, i32, ct.POINTER(sz)]
+    lib.parcae_replay.argtypes = [pp, i32, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.parcae_strerror.argtypes = [ct.c_int]
     lib.parcae_strerror.restype = ct.c_char_p
     lib.parcae_version.restype = ct.c_int
@@ -143,8 +149,9 @@ class Problem:
     zone: "object" = None         # uint8 [nq, N] device, zone of every instance
     zone_weight: "object" = None  # int32 view of uint32 [nq, PARCAE_MAX_ZONES] device
     cost_round: "object" = None   # float32 [nq, C] device: seconds per further transfer round, or None
-    event_before_sampling: Optional[int] = None   # raw hipEvent_t handles, recorded around the sampling kernel
-    event_after_sampling: Optional[int] = None
+    profile_events: Optional[tuple] = None   # raw hipEvent_t handles (before sampling, after sampling, before plan,
+                                             # after plan; each an int or None) for the library to record
+    _profile: object = field(default=None, repr=False)
     _cfg_arr: object = field(default=None, repr=False)
     _workspace: object = field(default=None, repr=False)
 
@@ -166,12 +173,17 @@ class Problem:
             for i, (d, p) in enumerate(self.configs):
                 arr[i].D, arr[i].P = int(d), int(p)
             self._cfg_arr = arr
+        prof = None
+        if self.profile_events is not None:
+            self._profile = parcae_profile(*self.profile_events)   # kept alive by the Problem
+            prof = ct.pointer(self._profile)
         return parcae_problem(
-            self.n_queries, self.n_instances, self.n_intervals, self.n_configs, self.n_scenarios, self.p_min,
-            self.interval_sec, int(self.flags), ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
+            ct.sizeof(parcae_problem), self.n_queries, self.n_instances, self.n_intervals, self.n_configs,
+            self.n_scenarios, self.p_min, self.interval_sec, int(self.flags),
+            ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
-            _ptr(self.cur_config), self.event_before_sampling, self.event_after_sampling, int(self.group_size),
-            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight), _ptr(self.cost_round))
+            _ptr(self.cur_config), int(self.group_size),
+            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight), _ptr(self.cost_round), prof)
 
     def workspace(self):
         """Device workspace of the size the library asks for (allocated once per Problem)."""
@@ -349,8 +361,9 @@ def parcae_debug_sample(p: Problem, q: int, t: int, c: int, s0: int, ns: int):
     return masks, n_int, d_min
 
 
-def parcae_replay(p: Problem, true_avail, windows, mode: int = PARCAE_REPLAY_PROACTIVE):
-    """Replay every query over H = true_avail.shape[1] - 1 steps; returns (chosen [nq, H], reward [nq, H], total [nq])."""
+def parcae_replay(p: Problem, true_avail, windows, mode: int = PARCAE_REPLAY_PROACTIVE, with_status: bool = False):
+    """Replay every query over H = true_avail.shape[1] - 1 steps; returns (chosen [nq, H], reward [nq, H], total [nq])
+    and, with_status, the per-query status [nq] as a fourth element."""
     torch = _require_gpu()
     dev = p.thr.device
     nq, H = int(true_avail.shape[0]), int(true_avail.shape[1]) - 1
@@ -363,12 +376,14 @@ def parcae_replay(p: Problem, true_avail, windows, mode: int = PARCAE_REPLAY_PRO
     total = torch.empty(nq, dtype=torch.float32, device=dev)
     cs = p.c_struct()
     need = ct.c_size_t(0)
-    _check(load_library().parcae_replay_workspace_bytes(ct.byref(cs), H, ct.byref(need)), "parcae_replay_workspace_bytes")
+    status = torch.empty(nq, dtype=torch.int32, device=dev) if with_status else None
+    _check(load_library().parcae_replay_workspace_bytes(ct.byref(cs), H, int(mode), ct.byref(need)),
+           "parcae_replay_workspace_bytes")
     ws = torch.empty(need.value + 256, dtype=torch.uint8, device=dev)
     ptr = ws.data_ptr()
     pad = (-ptr) % 256
     _check(load_library().parcae_replay(ct.byref(cs), H, _ptr(true_avail), _ptr(windows), int(mode), _ptr(chosen),
-                                        _ptr(reward), _ptr(total), ptr + pad, ws.numel() - pad, _stream_handle()),
-           "parcae_replay")
+                                        _ptr(reward), _ptr(total), _ptr(status), ptr + pad, ws.numel() - pad,
+                                        _stream_handle()), "parcae_replay")
     torch.cuda.current_stream().synchronize()   # the workspace tensor must outlive the enqueued work
-    return chosen, reward, total
+    return (chosen, reward, total, status) if with_status else (chosen, reward, total)

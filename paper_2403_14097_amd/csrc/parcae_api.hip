@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstddef>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -48,8 +49,26 @@ int pick_plan_cap(int C, const Layout& lay, size_t bp16_bytes, bool per_query)
     return cap >= lay.max_row ? (int)cap : -1;
 }
 
-// Host-visible shape checks; fills the packed candidate table.
-int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* lay)
+// The caller's structure may be older (shorter) or newer (longer) than this build's: copies what both sides know,
+// zero-fills the rest.  False if the pointer is null or the size is below the members every release has.
+constexpr size_t kMinProblemSize = offsetof(parcae_problem, cost_round) + sizeof(const float*);
+bool load_problem(const parcae_problem* in, parcae_problem* out)
+{
+    if (!in || in->struct_size < kMinProblemSize) return false;
+    std::memset(out, 0, sizeof(*out));
+    std::memcpy(out, in, in->struct_size < sizeof(*out) ? in->struct_size : sizeof(*out));
+    out->struct_size = (uint32_t)sizeof(*out);
+    return true;
+}
+
+int record(void* event, hipStream_t st)
+{
+    if (!event) return PARCAE_OK;
+    return hipEventRecord(static_cast<hipEvent_t>(event), st) == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+// Host-visible shape checks; fills the packed candidate table (table may be null; table_cap = its capacity).
+int check_problem(const parcae_problem* p, CfgRec* table, size_t table_cap, Layout* lay)
 {
     if (!p || !p->configs || !p->avail || !p->thr || !p->cost || !p->seed) return PARCAE_EINVAL;
     if (p->n_queries < 1 || p->n_intervals < 1 || p->n_configs < 1) return PARCAE_EINVAL;
@@ -64,7 +83,7 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
     const int group = p->group_size > 1 ? p->group_size : 1;
     int64_t L = 0;
     int max_row = 0;
-    if (table) table->resize((size_t)p->n_configs);
+    if (table && (size_t)p->n_configs > table_cap) return PARCAE_EINVAL;
     for (int c = 0; c < p->n_configs; ++c) {
         const parcae_config g = p->configs[c];
         if (g.D < 1 || g.P < 1 || g.D > PARCAE_MAX_INSTANCES || g.D % group != 0) return PARCAE_EINVAL;
@@ -79,7 +98,7 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
                 lg = 0;
                 while ((1 << lg) < g.P) ++lg;
             }
-            (*table)[(size_t)c] = CfgRec{g.D, g.P, (int32_t)L, lg};
+            table[c] = CfgRec{g.D, g.P, (int32_t)L, lg};
         }
         L += g.D + 1;
         max_row = g.D + 1 > max_row ? g.D + 1 : max_row;
@@ -104,6 +123,13 @@ int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* l
         lay->total = lay->f_off + align_up(f_bytes);
     }
     return PARCAE_OK;
+}
+
+int check_problem(const parcae_problem* p, std::vector<CfgRec>* table, Layout* lay)
+{
+    if (!table) return check_problem(p, nullptr, 0, lay);
+    if (p && p->n_configs >= 1) table->resize((size_t)p->n_configs);
+    return check_problem(p, table->data(), table->size(), lay);
 }
 
 int check_workspace(const Layout& lay, const void* ws, size_t bytes)
@@ -143,13 +169,13 @@ __global__ void __launch_bounds__(128) table_slice_kernel(TableSlice slice, int 
 }
 
 // Writes the candidate table into the workspace and checks the device inputs of every query.
-int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
 {
     CfgRec* dst = reinterpret_cast<CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
-    for (size_t first = 0; first < table.size(); first += kTableSlice) {
+    for (size_t first = 0; first < table_len; first += kTableSlice) {
         TableSlice slice;
-        const int count = (int)((table.size() - first < (size_t)kTableSlice) ? table.size() - first : kTableSlice);
-        std::memcpy(slice.rec, table.data() + first, sizeof(CfgRec) * (size_t)count);
+        const int count = (int)((table_len - first < (size_t)kTableSlice) ? table_len - first : kTableSlice);
+        std::memcpy(slice.rec, table + first, sizeof(CfgRec) * (size_t)count);
         if (count < kTableSlice) std::memset(slice.rec + count, 0, sizeof(CfgRec) * (size_t)(kTableSlice - count));
         table_slice_kernel<<<dim3(1), dim3(128), 0, st>>>(slice, count, dst + first);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
@@ -157,6 +183,11 @@ int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batc
     int32_t* valid = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
     parcae::validate_kernel<<<dim3((unsigned)b.nq), dim3(256), 0, st>>>(b, valid);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+{
+    return stage_inputs(table.data(), table.size(), lay, b, ws, st);
 }
 
 int32_t* valid_ptr(const Layout& lay, void* ws)
@@ -221,9 +252,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     int64_t eval_blocks = (int64_t)cus * 8;
     const int64_t max_useful = (n_units * n_chunks + 3) / 4;
     if (eval_blocks > max_useful) eval_blocks = max_useful;
-    if (p->event_before_sampling &&
-        hipEventRecord(static_cast<hipEvent_t>(p->event_before_sampling), st) != hipSuccess)
-        return PARCAE_EHIP;
+    if (p->profile && record(p->profile->event_before_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
     if (b.n_zones > 0)
         parcae::eval_hist_kernel<true><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
             b, wq, n_chunks, chunk_len, hist_int, hist_min);
@@ -231,9 +260,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
         parcae::eval_hist_kernel<false><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
             b, wq, n_chunks, chunk_len, hist_int, hist_min);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
-    if (p->event_after_sampling &&
-        hipEventRecord(static_cast<hipEvent_t>(p->event_after_sampling), st) != hipSuccess)
-        return PARCAE_EHIP;
+    if (p->profile && record(p->profile->event_after_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
 
     if (liveput || teff || gain) {
         parcae::finalise_kernel<<<dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, st>>>(b, hist_int, hist_min,
@@ -252,7 +279,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
 int launch_dp(const float* W, int nq, int T, int C, const int32_t* valid, float* F, float* F_scratch, int32_t* bp,
               int32_t* plan, int32_t* start, float* objective, int32_t* status, hipStream_t st)
 {
-    const bool spread = C > kSingleBlockMaxConfigs && nq < kFusedMinQueries && (F || F_scratch);
+    const bool spread = C > kSingleBlockMaxConfigs && nq < kFusedMinQueries && (F || F_scratch) && bp;
     if (!spread) {
         const size_t b16 = bp16_bytes_for(T, C);
         const size_t lds = parcae::dp_lds_bytes(C, b16);
@@ -330,7 +357,8 @@ bool plan_fits(const parcae_problem* p, const Layout& lay)
 
 extern "C" {
 
-int parcae_version(void) { return 100; }
+
+int parcae_version(void) { return 200; }
 
 const char* parcae_strerror(int code)
 {
@@ -355,8 +383,11 @@ int64_t parcae_hist_len(const parcae_config* configs, int32_t n_configs)
     return L;
 }
 
-int parcae_workspace_bytes(const parcae_problem* p, size_t* bytes)
+int parcae_workspace_bytes(const parcae_problem* problem, size_t* bytes)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     if (!bytes) return PARCAE_EINVAL;
     Layout lay;
     const int rc = check_problem(p, nullptr, &lay);
@@ -365,9 +396,12 @@ int parcae_workspace_bytes(const parcae_problem* p, size_t* bytes)
     return PARCAE_OK;
 }
 
-int parcae_liveput_eval(const parcae_problem* p, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
+int parcae_liveput_eval(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
                         float* gain, int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(p, &table, &lay);
@@ -380,10 +414,13 @@ int parcae_liveput_eval(const parcae_problem* p, uint32_t* hist_int, uint32_t* h
     return launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, status, st);
 }
 
-int parcae_plan_from_hist(const parcae_problem* p, const uint32_t* hist_int, const uint32_t* hist_min, float* F,
+int parcae_plan_from_hist(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* F,
                           int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(p, &table, &lay);
@@ -397,10 +434,13 @@ int parcae_plan_from_hist(const parcae_problem* p, const uint32_t* hist_int, con
     return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
 }
 
-int parcae_liveput_plan(const parcae_problem* p, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
+int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
                         float* gain, float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective,
                         int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(p, &table, &lay);
@@ -416,9 +456,12 @@ int parcae_liveput_plan(const parcae_problem* p, uint32_t* hist_int, uint32_t* h
     return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
 }
 
-int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int, const uint32_t* hist_min, float* W,
+int parcae_transition_weights(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* W,
                               void* workspace, size_t workspace_bytes, void* stream)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(p, &table, &lay);
@@ -439,7 +482,8 @@ int parcae_transition_weights(const parcae_problem* p, const uint32_t* hist_int,
 int parcae_dp_plan(const float* W, int32_t n_queries, int32_t n_intervals, int32_t n_configs, float* F, int32_t* bp,
                    int32_t* plan, int32_t* start, float* objective, int32_t* status, void* stream)
 {
-    if (!W || !bp || !plan) return PARCAE_EINVAL;
+    if (!W || !plan) return PARCAE_EINVAL;
+    if (!bp && bp16_bytes_for(n_intervals, n_configs) == 0) return PARCAE_EINVAL;  // no room in LDS: the walk back needs bp in memory
     if (n_queries < 1 || n_intervals < 1 || n_configs < 1 || n_configs > kMaxConfigsDp) return PARCAE_EINVAL;
     if ((int64_t)n_queries * n_intervals >= (int64_t)1 << 31 || n_queries > 65535 * 32) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -452,14 +496,16 @@ struct ReplayLayout {
     size_t hist_int_off, hist_min_off, plan_off, hist1_int_off, hist1_min_off, state_off, total;
 };
 
-ReplayLayout replay_layout(const parcae_problem* p, const Layout& lay)
+// The replay's own buffers sit behind the workspace of the calls it makes.  The reactive baseline never plans: it
+// needs the evaluation part of that workspace only (everything before the planner's weights) and no plan buffers.
+ReplayLayout replay_layout(const parcae_problem* p, const Layout& lay, bool plans)
 {
     const size_t nq = (size_t)p->n_queries, T = (size_t)p->n_intervals, L = (size_t)lay.L;
     ReplayLayout r;
-    r.hist_int_off = lay.total;
-    r.hist_min_off = r.hist_int_off + align_up(sizeof(uint32_t) * nq * T * L);
-    r.plan_off = r.hist_min_off + align_up(sizeof(uint32_t) * nq * T * L);
-    r.hist1_int_off = r.plan_off + align_up(sizeof(int32_t) * nq * T);
+    r.hist_int_off = plans ? lay.total : lay.w_off;
+    r.hist_min_off = r.hist_int_off + (plans ? align_up(sizeof(uint32_t) * nq * T * L) : 0);
+    r.plan_off = r.hist_min_off + (plans ? align_up(sizeof(uint32_t) * nq * T * L) : 0);
+    r.hist1_int_off = r.plan_off + (plans ? align_up(sizeof(int32_t) * nq * T) : 0);
     r.hist1_min_off = r.hist1_int_off + align_up(sizeof(uint32_t) * nq * L);
     r.state_off = r.hist1_min_off + align_up(sizeof(uint32_t) * nq * L);
     r.total = r.state_off + align_up(sizeof(int32_t) * nq);
@@ -471,40 +517,48 @@ parcae_problem replay_problem(const parcae_problem* p, const int32_t* windows)
 {
     parcae_problem q = *p;
     q.avail = windows;
-    q.event_before_sampling = nullptr;
-    q.event_after_sampling = nullptr;
+    q.profile = nullptr;
     return q;
 }
 
 }  // namespace
 
-int parcae_replay_workspace_bytes(const parcae_problem* p, int32_t n_steps, size_t* bytes)
+int parcae_replay_workspace_bytes(const parcae_problem* problem, int32_t n_steps, int32_t mode, size_t* bytes)
 {
-    if (!p || !bytes || n_steps < 1) return PARCAE_EINVAL;
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
+    if (!bytes || n_steps < 1) return PARCAE_EINVAL;
+    if (mode != PARCAE_REPLAY_PROACTIVE && mode != PARCAE_REPLAY_REACTIVE) return PARCAE_EINVAL;
     int32_t dummy = 0;
     const parcae_problem q = replay_problem(p, p->avail ? p->avail : &dummy);
     Layout lay;
     const int rc = check_problem(&q, nullptr, &lay);
     if (rc != PARCAE_OK) return rc;
-    *bytes = replay_layout(&q, lay).total;
+    *bytes = replay_layout(&q, lay, mode == PARCAE_REPLAY_PROACTIVE).total;
     return PARCAE_OK;
 }
 
-int parcae_replay(const parcae_problem* p, int32_t n_steps, const int32_t* true_avail, const int32_t* windows,
-                  int32_t mode, int32_t* chosen, float* reward, float* total, void* workspace, size_t workspace_bytes,
-                  void* stream)
+int parcae_replay(const parcae_problem* problem, int32_t n_steps, const int32_t* true_avail, const int32_t* windows,
+                  int32_t mode, int32_t* chosen, float* reward, float* total, int32_t* status, void* workspace,
+                  size_t workspace_bytes, void* stream)
 {
-    if (!p || !true_avail || !chosen || !reward || !total || n_steps < 1) return PARCAE_EINVAL;
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
+    if (!true_avail || !chosen || !reward || !total || n_steps < 1) return PARCAE_EINVAL;
     if (mode != PARCAE_REPLAY_PROACTIVE && mode != PARCAE_REPLAY_REACTIVE) return PARCAE_EINVAL;
-    if (mode == PARCAE_REPLAY_PROACTIVE && !windows) return PARCAE_EINVAL;
+    const bool plans = mode == PARCAE_REPLAY_PROACTIVE;
+    if (plans && !windows) return PARCAE_EINVAL;
     if ((int64_t)p->n_queries * ((int64_t)n_steps + 1) >= (int64_t)1 << 31) return PARCAE_EINVAL;
+    if ((int64_t)p->n_queries * n_steps * ((int64_t)p->n_intervals + 1) >= (int64_t)1 << 40) return PARCAE_EINVAL;
     const parcae_problem q = replay_problem(p, windows ? windows : true_avail);
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(&q, &table, &lay);
     if (rc != PARCAE_OK) return rc;
-    if (!plan_fits(&q, lay)) return PARCAE_EINVAL;
-    const ReplayLayout rl = replay_layout(&q, lay);
+    if (plans && !plan_fits(&q, lay)) return PARCAE_EINVAL;
+    const ReplayLayout rl = replay_layout(&q, lay, plans);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < rl.total)
         return PARCAE_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -516,21 +570,25 @@ int parcae_replay(const parcae_problem* p, int32_t n_steps, const int32_t* true_
     uint32_t* hist1_min = reinterpret_cast<uint32_t*>(base + rl.hist1_min_off);
     int32_t* state = reinterpret_cast<int32_t*>(base + rl.state_off);
 
+    // tables and starting configuration are checked once; the availability entries of the whole true walk and of
+    // every window by a kernel of their own (the table check sees one row of the walk only)
     Batch b = make_batch(&q, lay, workspace);
-    if (mode == PARCAE_REPLAY_REACTIVE) {  // no windows: the staging check reads the true walk instead
-        b.avail = true_avail;
-        b.avail_stride = n_steps + 1;
-        b.T = 1;
-    }
+    b.avail = true_avail;
+    b.avail_stride = n_steps + 1;
+    b.T = 1;
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
     b = make_batch(&q, lay, workspace);
+    parcae::replay_validate_kernel<<<dim3((unsigned)b.nq), dim3(256), 0, st>>>(b.nq, n_steps, b.T, b.N, true_avail,
+                                                                              plans ? windows : nullptr,
+                                                                              valid_ptr(lay, workspace));
+    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     const unsigned qblocks = (unsigned)((b.nq + 255) / 256);
-    parcae::replay_init_kernel<<<dim3(qblocks), dim3(256), 0, st>>>(b.nq, p->cur_config, state, total);
+    parcae::replay_init_kernel<<<dim3(qblocks), dim3(256), 0, st>>>(b.nq, b.C, p->cur_config, state, total);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
 
     for (int i = 0; i < n_steps; ++i) {
         const int32_t* window = nullptr;
-        if (mode == PARCAE_REPLAY_PROACTIVE) {
+        if (plans) {
             Batch bi = b;
             window = windows + (int64_t)i * b.nq * (b.T + 1);
             bi.avail = window;
@@ -558,13 +616,21 @@ int parcae_replay(const parcae_problem* p, int32_t n_steps, const int32_t* true_
                                                                          reward, total);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     }
+    if (status) {
+        parcae::status_from_valid_kernel<<<dim3(qblocks), dim3(256), 0, st>>>(b.nq, valid_ptr(lay, workspace), status,
+                                                                               PARCAE_EINVAL);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
     return PARCAE_OK;
 }
 
-int parcae_debug_sample(const parcae_problem* p, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,
+int parcae_debug_sample(const parcae_problem* problem, int32_t q, int32_t t, int32_t c, uint32_t s0, uint32_t ns,
                         uint32_t* masks, int32_t* n_int, int32_t* d_min, void* workspace, size_t workspace_bytes,
                         void* stream)
 {
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
     std::vector<CfgRec> table;
     Layout lay;
     int rc = check_problem(p, &table, &lay);

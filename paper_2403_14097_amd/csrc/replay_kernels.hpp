@@ -26,15 +26,41 @@ __device__ __forceinline__ int replay_widest(const Batch& b, int depth, int a)
     return arg;
 }
 
-// state[q] = configuration running now (negative inputs mean nothing is running), total[q] = 0.
-__global__ void __launch_bounds__(256) replay_init_kernel(int nq, const int32_t* __restrict__ cur_config,
+// state[q] = configuration running now, total[q] = 0.  Negative inputs mean nothing is running; an index past the
+// candidate list (flagged as invalid input by the checks) is treated the same way, so that no later kernel indexes
+// the candidate table with it.
+__global__ void __launch_bounds__(256) replay_init_kernel(int nq, int C, const int32_t* __restrict__ cur_config,
                                                           int32_t* __restrict__ state, float* __restrict__ total)
 {
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     const int c = cur_config ? cur_config[q] : -1;
-    state[q] = c < 0 ? kNothingRunning : c;
+    state[q] = (c < 0 || c >= C) ? kNothingRunning : c;
     total[q] = 0.0f;
+}
+
+// Clears valid[q] when an entry of the true walk [nq][n_steps + 1] or of a forecast window [n_steps][nq][T + 1]
+// (windows may be null) lies outside [0, N].  One block per query; valid[q] was set by the input checks before.
+__global__ void __launch_bounds__(256) replay_validate_kernel(int nq, int n_steps, int T, int N,
+                                                              const int32_t* __restrict__ true_avail,
+                                                              const int32_t* __restrict__ windows,
+                                                              int32_t* __restrict__ valid)
+{
+    const int q = blockIdx.x;
+    int bad = 0;
+    for (int i = threadIdx.x; i <= n_steps; i += blockDim.x) {
+        const int a = true_avail[(int64_t)q * (n_steps + 1) + i];
+        bad |= (a < 0 || a > N) ? 1 : 0;
+    }
+    if (windows) {
+        const int per_step = T + 1;
+        for (int x = threadIdx.x; x < n_steps * per_step; x += blockDim.x) {
+            const int i = x / per_step, t = x - i * per_step;
+            const int a = windows[((int64_t)i * nq + q) * per_step + t];
+            bad |= (a < 0 || a > N) ? 1 : 0;
+        }
+    }
+    if (bad) valid[q] = 0;  // every writer stores the same value
 }
 
 // One thread per query: target of step i (first configuration of the plan, or the fastest fitting candidate

@@ -176,6 +176,11 @@ def test_many_queries_take_the_per_query_planning_kernel(pk):
     for f in ("F", "bp", "plan", "start", "objective", "status"):
         assert np.array_equal(_np(getattr(pl2, f)), _np(getattr(pl, f))), f
     assert np.array_equal(_np(lean.plan), _np(pl.plan)) and np.array_equal(_np(lean.objective), _np(pl.objective))
+    # no back-pointer output at all: they fit in local memory here (2 * 30 * 30 bytes)
+    bare = pk.alloc_plan_out(p, full=False)
+    pk.parcae_dp_plan(W, bare)
+    _sync()
+    assert np.array_equal(_np(bare.plan), _np(pl.plan)) and np.array_equal(_np(bare.start), _np(pl.start))
 
 
 def test_per_query_planning_kernel_with_rows_that_do_not_fit_in_lds_at_once(pk):
@@ -740,6 +745,37 @@ def test_replay_on_randomly_drawn_problems(pk):
                 r = rp.replay(b, q, true[q], win[:, q, :], mode, n_threads=8, pool_all=pool_all)
                 assert np.array_equal(_np(chosen[q]), r.chosen), (case, mode, q)
                 assert np.array_equal(_np(reward[q]), r.reward) and float(total[q]) == r.total, (case, mode, q)
+
+
+def test_replay_flags_bad_walks_windows_and_start_configurations(pk):
+    """Bad DEVICE data in the replay inputs is reported per query and never used as an index: a starting
+    configuration past the candidate list, a true-walk entry above N, a window entry below 0 in a late step."""
+    import torch
+    from oracle import replay as rp
+    nq, H = 5, 4
+    spec = pi.WorkloadSpec("replay", nq, 32, 12, 60.0, (2, 4, 8), 2, 4, 8, 0.1, False, 2, 128)
+    b = pi.make_batch(spec, seed=31)
+    b_plan = b.take(range(nq))
+    b_plan.n_intervals = 6
+    b_plan.avail = np.ascontiguousarray(b.avail[:, :7])
+    true, win = _replay_inputs(b, H, 3)
+    win = np.ascontiguousarray(win[:, :, :7])
+    good_true, good_win = true.copy(), win.copy()
+    b_plan.cur_config[1] = b_plan.n_configs + 5            # past the list
+    true[2, 3] = 33                                         # above N
+    win[3, 3, 5] = -1                                       # below 0, last step's window
+    p = pk.upload(b_plan)
+    for mode in (pk.PARCAE_REPLAY_PROACTIVE, pk.PARCAE_REPLAY_REACTIVE):
+        chosen, reward, total, status = pk.parcae_replay(
+            p, torch.from_numpy(true).cuda(), torch.from_numpy(win).cuda() if mode == pk.PARCAE_REPLAY_PROACTIVE else None,
+            mode, with_status=True)
+        _sync()
+        want = [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL if mode == pk.PARCAE_REPLAY_PROACTIVE else 0, 0]
+        assert _np(status).tolist() == want, mode
+        for q in (0, 4):                                   # the clean queries are unaffected
+            r = rp.replay(b_plan, q, good_true[q], good_win[:, q, :], mode, n_threads=4)
+            assert np.array_equal(_np(chosen[q]), r.chosen) and np.array_equal(_np(reward[q]), r.reward), (mode, q)
+        assert np.all(_np(chosen) >= -1) and np.all(_np(chosen) < b_plan.n_configs)
 
 
 def test_replay_suspends_and_restarts(pk):

@@ -26,7 +26,7 @@ def test_header_symbols_are_exported():
 
 
 def test_version_and_strerror():
-    assert pk.parcae_version() >= 100
+    assert pk.parcae_version() >= 200
     assert pk.strerror(0) == "ok"
     for code in (pk.PARCAE_EINVAL, pk.PARCAE_EWORKSPACE, pk.PARCAE_EHIP, pk.PARCAE_EINFEASIBLE, -99):
         assert isinstance(pk.strerror(code), str) and pk.strerror(code)
@@ -42,8 +42,9 @@ def _problem(configs, nq=1, N=8, T=4, S=16, tau=60.0, p_min=1, flags=0, fake_ptr
     arr = (pk.parcae_config * len(configs))()
     for i, (d, p) in enumerate(configs):
         arr[i].D, arr[i].P = d, p
-    prob = pk.parcae_problem(nq, N, T, len(configs), S, p_min, tau, flags, ct.cast(arr, ct.POINTER(pk.parcae_config)),
-                             fake_ptr, fake_ptr, fake_ptr, fake_ptr, None, None, None, None, group)
+    prob = pk.parcae_problem(ct.sizeof(pk.parcae_problem), nq, N, T, len(configs), S, p_min, tau, flags,
+                             ct.cast(arr, ct.POINTER(pk.parcae_config)),
+                             fake_ptr, fake_ptr, fake_ptr, fake_ptr, None, None, group)
     return prob, arr
 
 
@@ -76,6 +77,26 @@ def test_workspace_bytes_and_shape_errors():
         assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
 
 
+def test_structure_size_field():
+    """The problem structure carries its own size: an older (shorter) caller is accepted as long as it has the
+    members of the first release, a newer (longer) one is read up to what this build knows."""
+    lib = pk.load_library()
+    out = ct.c_size_t(0)
+    prob, keep = _problem([(1, 1), (2, 1)])
+    full = ct.sizeof(pk.parcae_problem)
+    assert prob.struct_size == full
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    prob.struct_size = pk.parcae_problem.profile.offset      # a caller built before the profiling hooks existed
+    prob.profile = ct.cast(0xdead0000, ct.POINTER(pk.parcae_profile))   # must not be read
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    prob.profile = None
+    prob.struct_size = full + 64                              # a newer caller
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    for bad in (0, 4, pk.parcae_problem.cost_round.offset):
+        prob.struct_size = bad
+        assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+
+
 def test_entry_points_reject_bad_arguments_before_any_launch():
     """NULL outputs, a missing or misaligned or short workspace: an error code and nothing is enqueued."""
     lib = pk.load_library()
@@ -90,6 +111,8 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.parcae_transition_weights(ct.byref(prob), fake, fake, None, fake, need.value, None) == pk.PARCAE_EINVAL
     assert lib.parcae_dp_plan(None, 1, 1, 1, None, fake, fake, None, None, None, None) == pk.PARCAE_EINVAL
     assert lib.parcae_dp_plan(fake, 1, 1, 5000, None, fake, fake, None, None, None, None) == pk.PARCAE_EINVAL
+    # no back-pointer output: only while they fit in the workgroup's local memory (2 * T * C <= 16384 bytes)
+    assert lib.parcae_dp_plan(fake, 1, 100, 100, None, None, fake, None, None, None, None) == pk.PARCAE_EINVAL
     # workspace problems
     for ws, nbytes in ((None, need.value), (fake + 4, need.value), (fake, need.value - 1)):
         assert lib.parcae_liveput_eval(ct.byref(prob), fake, fake, None, None, None, None, ws, nbytes, None) == pk.PARCAE_EWORKSPACE
@@ -124,6 +147,25 @@ def test_zone_and_candidate_limits_are_checked_on_the_host():
                                      None) == pk.PARCAE_EINVAL
     assert lib.parcae_liveput_plan(ct.byref(big), fake, fake, None, None, None, None, None, fake, None, None, None,
                                    ws, out.value, None) == pk.PARCAE_EINVAL
+
+
+def test_reactive_replay_needs_no_planner():
+    """The reactive baseline never plans: no candidate limit, no planner part in its workspace."""
+    lib = pk.load_library()
+    many = [(d, p) for p in range(1, 257) for d in range(1, 256 // p + 1)]
+    big, keep = _problem(many, N=256, T=3)
+    pro, rea = ct.c_size_t(0), ct.c_size_t(0)
+    assert lib.parcae_replay_workspace_bytes(ct.byref(big), 4, pk.PARCAE_REPLAY_PROACTIVE, ct.byref(pro)) == pk.PARCAE_OK
+    assert lib.parcae_replay_workspace_bytes(ct.byref(big), 4, pk.PARCAE_REPLAY_REACTIVE, ct.byref(rea)) == pk.PARCAE_OK
+    assert rea.value < pro.value
+    assert lib.parcae_replay_workspace_bytes(ct.byref(big), 4, 7, ct.byref(rea)) == pk.PARCAE_EINVAL
+    fake, ws = 0x1000, 0x100000
+    # proactive: the candidate list does not fit the planning kernels; refused before anything is enqueued
+    assert lib.parcae_replay(ct.byref(big), 4, fake, fake, pk.PARCAE_REPLAY_PROACTIVE, fake, fake, fake, None, ws,
+                             pro.value, None) == pk.PARCAE_EINVAL
+    # a short workspace is refused for either mode
+    assert lib.parcae_replay(ct.byref(big), 4, fake, None, pk.PARCAE_REPLAY_REACTIVE, fake, fake, fake, None, ws,
+                             rea.value - 1, None) == pk.PARCAE_EWORKSPACE
 
 
 def test_product_has_no_cpu_path():
