@@ -301,6 +301,24 @@ int parcae_liveput_plan(const parcae_problem *p, uint32_t *hist_int, uint32_t *h
                         void *stream);
 
 /*
+ * parcae_liveput_plan for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is an array
+ * inside the library (PARCAE_STATIC_WORKSPACE_BYTES per GPU, held until the process ends); the call
+ * allocates nothing on the host or the device and calls no allocating routine.  Inputs, outputs and
+ * results are those of parcae_liveput_plan, bit for bit.
+ * Limits: at most PARCAE_STATIC_MAX_CONFIGS candidates (PARCAE_EINVAL beyond), and
+ * parcae_workspace_bytes(p) <= PARCAE_STATIC_WORKSPACE_BYTES (PARCAE_EWORKSPACE beyond; nothing is
+ * enqueued then).  All calls on one GPU share that GPU's array: calls that may overlap in time on the
+ * same GPU (different streams, different threads) race and must be serialised by the caller.  The
+ * array keeps the last call's contents; every call clears what it needs itself.
+ */
+#define PARCAE_STATIC_WORKSPACE_BYTES (16u << 20)
+#define PARCAE_STATIC_MAX_CONFIGS 1024
+int parcae_liveput_plan_static(const parcae_problem *p, uint32_t *hist_int, uint32_t *hist_min, float *liveput,
+                               float *teff, float *gain, float *F, int32_t *bp, int32_t *plan, int32_t *start,
+                               float *objective, int32_t *status, void *stream);
+
+/*
  * Transition weights written out (Eq. 4, section 6.2).
  *   W  DEVICE out [nq][T][C][C] float; row c (source), column c' (target) contiguous
  */

@@ -30,11 +30,14 @@ PARCAE_POOL_ALL = 1
 PARCAE_COLD_START = -2
 PARCAE_REPLAY_PROACTIVE = 0
 PARCAE_REPLAY_REACTIVE = 1
+PARCAE_STATIC_WORKSPACE_BYTES = 16 << 20
+PARCAE_STATIC_MAX_CONFIGS = 1024
 
 EXPORTED_SYMBOLS = (
     "parcae_workspace_bytes", "parcae_hist_len", "parcae_liveput_eval", "parcae_plan_from_hist",
     "parcae_liveput_plan", "parcae_transition_weights", "parcae_dp_plan", "parcae_debug_sample",
     "parcae_strerror", "parcae_version", "parcae_replay", "parcae_replay_workspace_bytes",
+    "parcae_liveput_plan_static",
 )
 
 
@@ -89,6 +92,7 @@ def load_library() -> ct.CDLL:
     lib.parcae_plan_from_hist.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.parcae_liveput_plan.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.parcae_transition_weights.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.parcae_liveput_plan_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.parcae_dp_plan.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.parcae_debug_sample.argtypes = [pp, i32, i32, i32, u32, u32, vp, vp, vp, vp, sz, vp]
     lib.parcae_replay_workspace_bytes.argtypes = [pp, i32, i32, ct.POINTER(sz)]
@@ -320,6 +324,17 @@ def parcae_liveput_plan(p: Problem, ev: Optional[EvalOut] = None, out: Optional[
                                               _ptr(ev.teff), _ptr(ev.gain), _ptr(out.F), _ptr(out.bp), _ptr(out.plan),
                                               _ptr(out.start), _ptr(out.objective), _ptr(out.status), ws, nbytes,
                                               _stream_handle()), "parcae_liveput_plan")
+    return ev, out
+
+
+def parcae_liveput_plan_static(p: Problem, ev: EvalOut, out: PlanOut):
+    """parcae_liveput_plan on the library's built-in workspace; the output buffers must be passed in (this call
+    allocates nothing)."""
+    cs = p.c_struct()
+    _check(load_library().parcae_liveput_plan_static(ct.byref(cs), _ptr(ev.hist_int), _ptr(ev.hist_min), _ptr(ev.liveput),
+                                                     _ptr(ev.teff), _ptr(ev.gain), _ptr(out.F), _ptr(out.bp),
+                                                     _ptr(out.plan), _ptr(out.start), _ptr(out.objective),
+                                                     _ptr(out.status), _stream_handle()), "parcae_liveput_plan_static")
     return ev, out
 
 

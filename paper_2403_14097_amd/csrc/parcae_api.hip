@@ -2,6 +2,7 @@
 // The semantics of every entry point are stated in include/parcae.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstddef>
 #include <cstdint>
@@ -353,10 +354,31 @@ bool plan_fits(const parcae_problem* p, const Layout& lay)
     return pick_plan_cap(p->n_configs, lay, 0, !lay.stepwise) >= 0;
 }
 
+// ---- workspace of the entry point that allocates nothing: one array per GPU, held until the process ends.
+// `scratch` is only a host-side handle here; its device address on the current GPU comes from
+// hipGetSymbolAddress, once per device, and is what every kernel and every pointer computation uses.
+static __device__ __align__(256) unsigned char scratch[PARCAE_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxStaticDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxStaticDevices];
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxStaticDevices) return PARCAE_EHIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PARCAE_EHIP;
+        if ((reinterpret_cast<uintptr_t>(ptr) % kAlign) != 0) return PARCAE_EHIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // every thread would store the same address
+    }
+    *out = ptr;
+    return PARCAE_OK;
+}
+
 }  // namespace
 
 extern "C" {
-
 
 int parcae_version(void) { return 200; }
 
@@ -451,6 +473,30 @@ int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint3
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
     if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
+        return rc;
+    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+}
+
+int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput,
+                               float* teff, float* gain, float* F, int32_t* bp, int32_t* plan, int32_t* start,
+                               float* objective, int32_t* status, void* stream)
+{
+    parcae_problem local;
+    if (!load_problem(problem, &local)) return PARCAE_EINVAL;
+    const parcae_problem* p = &local;
+    CfgRec table[PARCAE_STATIC_MAX_CONFIGS];  // on the stack: this entry point allocates nothing, on either side
+    Layout lay;
+    int rc = check_problem(p, table, PARCAE_STATIC_MAX_CONFIGS, &lay);
+    if (rc != PARCAE_OK) return rc;
+    if (!hist_int || !hist_min || !plan) return PARCAE_EINVAL;
+    if (lay.total > sizeof(scratch)) return PARCAE_EWORKSPACE;  // larger problems take parcae_liveput_plan
+    if (!plan_fits(p, lay)) return PARCAE_EINVAL;
+    void* workspace = nullptr;
+    if ((rc = static_scratch(&workspace)) != PARCAE_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Batch b = make_batch(p, lay, workspace);
+    if ((rc = stage_inputs(table, (size_t)p->n_configs, lay, b, workspace, st)) != PARCAE_OK) return rc;
     if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
         return rc;
     return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);

@@ -168,6 +168,29 @@ def test_reactive_replay_needs_no_planner():
                              rea.value - 1, None) == pk.PARCAE_EWORKSPACE
 
 
+def test_static_entry_point_limits_are_checked_before_anything_else():
+    """The entry point with the built-in workspace refuses problems beyond its stated limits on the host."""
+    lib = pk.load_library()
+    fake = 0x1000
+    out = ct.c_size_t(0)
+    # 1024 queries of a long horizon: the workspace would exceed the built-in array
+    big, keep = _problem([(d, 4) for d in range(1, 17)], nq=4096, N=64, T=64)
+    assert lib.parcae_workspace_bytes(ct.byref(big), ct.byref(out)) == pk.PARCAE_OK
+    assert out.value > pk.PARCAE_STATIC_WORKSPACE_BYTES
+    assert lib.parcae_liveput_plan_static(ct.byref(big), fake, fake, None, None, None, None, None, fake, None, None,
+                                          None, None) == pk.PARCAE_EWORKSPACE
+    # more candidates than its fixed table holds
+    many = [(d, p) for p in range(1, 257) for d in range(1, 256 // p + 1)]
+    assert len(many) > pk.PARCAE_STATIC_MAX_CONFIGS
+    wide, keep2 = _problem(many, N=256, T=2)
+    assert lib.parcae_liveput_plan_static(ct.byref(wide), fake, fake, None, None, None, None, None, fake, None, None,
+                                          None, None) == pk.PARCAE_EINVAL
+    # required outputs
+    ok, keep3 = _problem([(1, 1), (2, 1)])
+    assert lib.parcae_liveput_plan_static(ct.byref(ok), fake, fake, None, None, None, None, None, None, None, None,
+                                          None, None) == pk.PARCAE_EINVAL
+
+
 def test_product_has_no_cpu_path():
     """Without a GPU the binding raises instead of computing anything."""
     import torch
