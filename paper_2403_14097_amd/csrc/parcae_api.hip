@@ -2,6 +2,7 @@
 // The semantics of every entry point are stated in include/parcae.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstddef>
@@ -13,6 +14,7 @@
 #include "device_common.hpp"
 #include "eval_kernels.hpp"
 #include "plan_kernels.hpp"
+#include "plan_wave.hpp"
 #include "replay_kernels.hpp"
 
 namespace {
@@ -169,8 +171,10 @@ __global__ void __launch_bounds__(128) table_slice_kernel(TableSlice slice, int 
     if (i < count) dst[i] = slice.rec[i];
 }
 
-// Writes the candidate table into the workspace and checks the device inputs of every query.
-int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+// Writes the candidate table into the workspace and, if asked, checks the device inputs of every query
+// (valid[q] in the workspace; the wave planner checks its own query and needs no such launch).
+int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const Batch& b, void* ws, hipStream_t st,
+                 bool validate = true)
 {
     CfgRec* dst = reinterpret_cast<CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     for (size_t first = 0; first < table_len; first += kTableSlice) {
@@ -181,14 +185,16 @@ int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const
         table_slice_kernel<<<dim3(1), dim3(128), 0, st>>>(slice, count, dst + first);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     }
+    if (!validate) return PARCAE_OK;
     int32_t* valid = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
     parcae::validate_kernel<<<dim3((unsigned)b.nq), dim3(256), 0, st>>>(b, valid);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
 
-int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st,
+                 bool validate = true)
 {
-    return stage_inputs(table.data(), table.size(), lay, b, ws, st);
+    return stage_inputs(table.data(), table.size(), lay, b, ws, st, validate);
 }
 
 int32_t* valid_ptr(const Layout& lay, void* ws)
@@ -299,12 +305,87 @@ int launch_dp(const float* W, int nq, int T, int C, const int32_t* valid, float*
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
 }
 
-int launch_plan(const Batch& b, const Layout& lay, void* ws, const uint32_t* hist_int, const uint32_t* hist_min,
-                float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective, int32_t* status,
-                hipStream_t st)
+// Launch shape of the wave planner (candidate lists of at most 64 entries): threads per query, steps per chunk,
+// whether the 16-bit back-pointers of all steps stay in local memory.  False if the problem does not fit.
+struct WaveLaunch {
+    int threads, steps_per_chunk, bp_in_lds;
+    size_t lds;
+};
+
+bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g, int cus, WaveLaunch* out)
+{
+    // few queries: more waves per query share the work that is parallel (weights, back-pointers)
+    int threads = nq >= 3 * cus ? 64 : (2 * nq >= 3 * cus ? 128 : (2 * nq >= cus ? 256 : 512));
+    while ((int64_t)parcae::kWaveRowRegs * threads < L && threads < 512) threads *= 2;  // a step's rows must fit the prefetch registers
+    if ((int64_t)parcae::kWaveRowRegs * threads < L) return false;
+    int resident = (nq + cus - 1) / cus;  // workgroups that should share a compute unit
+    resident = resident < 1 ? 1 : (resident > 8 ? 8 : resident);
+    const size_t budget = std::min(kMaxPlanLds, kLdsPerCu / (size_t)resident - kPlanStaticLds);
+    const size_t per_step = parcae::wave_step_lds(C, (int)L, g);
+    for (int attempt = 0; attempt < 4; ++attempt) {
+        const bool bp16 = (attempt & 1) == 0 && bp16_bytes_for(T, C) != 0;
+        const size_t room = attempt < 2 ? budget : kMaxPlanLds;
+        const size_t fixed = parcae::wave_fixed_lds(C, T, g, bp16);
+        if (fixed + per_step > room) continue;
+        int64_t tc = (int64_t)((room - fixed) / per_step);
+        const int64_t by_regs = (int64_t)parcae::kWaveRowRegs * threads / L;
+        tc = std::min(std::min(tc, (int64_t)parcae::kWave - 1), std::min(by_regs, (int64_t)T));  // lane i keeps the availability of step i
+        if (tc < 1) continue;
+        out->threads = threads;
+        out->steps_per_chunk = (int)tc;
+        out->bp_in_lds = bp16 ? 1 : 0;
+        out->lds = fixed + (size_t)tc * per_step;
+        return true;
+    }
+    return false;
+}
+
+int compute_units(int* cus)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || *cus < 1)
+        return PARCAE_EHIP;
+    return PARCAE_OK;
+}
+
+// Whether the plan of this problem goes to the wave planner (which checks the device inputs itself).
+bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layout& lay)
+{
+    int cus = 0;
+    if (p->n_configs > parcae::kWaveMaxConfigs || compute_units(&cus) != PARCAE_OK) return false;
+    WaveLaunch wl;
+    return pick_wave_launch(p->n_queries, p->n_intervals, p->n_configs, lay.L,
+                            parcae::wave_geometry(table, p->n_configs), cus, &wl);
+}
+
+int launch_plan(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
+                const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective,
+                int32_t* status, hipStream_t st)
 {
     unsigned char* base = static_cast<unsigned char*>(ws);
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
+    if (b.C <= parcae::kWaveMaxConfigs) {
+        int cus = 0;
+        if (compute_units(&cus) != PARCAE_OK) return PARCAE_EHIP;
+        const parcae::WaveGeom g = parcae::wave_geometry(table, b.C);
+        WaveLaunch wl;
+        if (pick_wave_launch(b.nq, b.T, b.C, lay.L, g, cus, &wl)) {
+            parcae::WaveTable wt;
+            parcae::wave_fill_table(table, b.C, wt);
+            // back-pointers that do not stay in local memory are walked through memory: the caller's, else the workspace's
+            int32_t* bp_arg = wl.bp_in_lds ? bp : bp_use;
+            if (b.cost_round)
+                parcae::plan_wave_kernel<true><<<dim3((unsigned)b.nq), dim3((unsigned)wl.threads), wl.lds, st>>>(
+                    b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
+                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+            else
+                parcae::plan_wave_kernel<false><<<dim3((unsigned)b.nq), dim3((unsigned)wl.threads), wl.lds, st>>>(
+                    b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
+                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+            return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+        }
+    }
     if (lay.stepwise) {
         // few queries: every (query, step) writes its weights in parallel, then the DP runs on them
         const int cap = pick_plan_cap(b.C, lay, 0, false);
@@ -452,8 +533,10 @@ int parcae_plan_from_hist(const parcae_problem* problem, const uint32_t* hist_in
     if (!plan_fits(p, lay)) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
-    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    // the wave planner takes the candidate table as a kernel argument and checks the inputs itself: one launch
+    if (!takes_wave_planner(p, table.data(), lay) && (rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK)
+        return rc;
+    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
 }
 
 int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
@@ -472,10 +555,11 @@ int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint3
     if (!plan_fits(p, lay)) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    if ((rc = stage_inputs(table, lay, b, workspace, st, !takes_wave_planner(p, table.data(), lay))) != PARCAE_OK)
+        return rc;
     if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
         return rc;
-    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
 }
 
 int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput,
@@ -496,10 +580,12 @@ int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int
     if ((rc = static_scratch(&workspace)) != PARCAE_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, (size_t)p->n_configs, lay, b, workspace, st)) != PARCAE_OK) return rc;
+    if ((rc = stage_inputs(table, (size_t)p->n_configs, lay, b, workspace, st, !takes_wave_planner(p, table, lay))) !=
+        PARCAE_OK)
+        return rc;
     if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
         return rc;
-    return launch_plan(b, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    return launch_plan(b, table, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
 }
 
 int parcae_transition_weights(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* W,
@@ -643,7 +729,7 @@ int parcae_replay(const parcae_problem* problem, int32_t n_steps, const int32_t*
             if ((rc = launch_eval(&q, bi, lay, workspace, hist_int, hist_min, nullptr, nullptr, nullptr, nullptr, st)) !=
                 PARCAE_OK)
                 return rc;
-            if ((rc = launch_plan(bi, lay, workspace, hist_int, hist_min, nullptr, nullptr, plan, nullptr, nullptr,
+            if ((rc = launch_plan(bi, table.data(), lay, workspace, hist_int, hist_min, nullptr, nullptr, plan, nullptr, nullptr,
                                   nullptr, st)) != PARCAE_OK)
                 return rc;
         }

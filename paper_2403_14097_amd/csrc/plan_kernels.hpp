@@ -79,6 +79,48 @@ __device__ __forceinline__ float teff_with_inter(uint32_t n0, uint32_t n01, uint
 
 // ------------------------------------------------------------------ input checks
 
+// Whether this thread finds a broken rule among the device inputs of query q; the threads of a block split the
+// tables between them (thread `tid` of `nthreads`), so the verdict is the OR over the block.  cfg = candidate table.
+__device__ __forceinline__ int query_inputs_bad(const Batch& b, const CfgRec* cfg, int q, int tid, int nthreads)
+{
+    int my_bad = 0;
+    for (int i = tid; i <= b.T; i += nthreads) {
+        const int a = b.avail[(int64_t)q * b.avail_stride + i];
+        if (a < 0 || a > b.N) my_bad = 1;
+    }
+    // throughputs: every entry finite and not negative (one flat pass over the table), the first entry of a row 0
+    const float* th = b.thr + (int64_t)q * b.L;
+    for (int i = tid; i < b.L; i += nthreads) {
+        const float v = th[i];
+        if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
+    }
+    for (int c = tid; c < b.C; c += nthreads) {
+        if (!(th[cfg[c].off] == 0.0f)) my_bad = 1;
+        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+        const float c0 = co[0], c1 = co[1], c2 = co[2];
+        if (!(c0 >= 0.0f) || !(c0 <= c1) || !(c1 <= c2) || !(c2 < __builtin_inff())) my_bad = 1;
+    }
+    if (tid == 0 && b.cur_config) {
+        const int cur = b.cur_config[q];
+        if (cur < -2 || cur >= b.C) my_bad = 1;
+    }
+    if (b.cost_round) {
+        for (int c = tid; c < b.C; c += nthreads) {
+            const float v = b.cost_round[(int64_t)q * b.C + c];
+            if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
+        }
+    }
+    if (b.n_zones > 0) {
+        for (int j = tid; j < b.N; j += nthreads)
+            if ((int)b.zone[(int64_t)q * b.N + j] >= b.n_zones) my_bad = 1;
+        if (tid < b.n_zones) {
+            const uint32_t w = b.zone_weight[(int64_t)q * kMaxZones + tid];
+            if (w < 1u || w > 255u) my_bad = 1;
+        }
+    }
+    return my_bad;
+}
+
 // valid[q] = 1 if the query's device inputs obey the documented ranges, else 0.  One block per query.
 __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restrict__ valid)
 {
@@ -86,42 +128,7 @@ __global__ void __launch_bounds__(256) validate_kernel(Batch b, int32_t* __restr
     const int q = blockIdx.x;
     if (threadIdx.x == 0) bad = 0;
     __syncthreads();
-    int my_bad = 0;
-    for (int i = threadIdx.x; i <= b.T; i += blockDim.x) {
-        const int a = b.avail[(int64_t)q * b.avail_stride + i];
-        if (a < 0 || a > b.N) my_bad = 1;
-    }
-    for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
-        const CfgRec cr = b.cfg[c];
-        const float* th = b.thr + (int64_t)q * b.L + cr.off;
-        if (!(th[0] == 0.0f)) my_bad = 1;
-        for (int d = 1; d <= cr.D; ++d) {
-            const float v = th[d];
-            if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
-        }
-        const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
-        const float c0 = co[0], c1 = co[1], c2 = co[2];
-        if (!(c0 >= 0.0f) || !(c0 <= c1) || !(c1 <= c2) || !(c2 < __builtin_inff())) my_bad = 1;
-    }
-    if (threadIdx.x == 0 && b.cur_config) {
-        const int cur = b.cur_config[q];
-        if (cur < -2 || cur >= b.C) my_bad = 1;
-    }
-    if (b.cost_round) {
-        for (int c = threadIdx.x; c < b.C; c += blockDim.x) {
-            const float v = b.cost_round[(int64_t)q * b.C + c];
-            if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
-        }
-    }
-    if (b.n_zones > 0) {
-        for (int j = threadIdx.x; j < b.N; j += blockDim.x)
-            if ((int)b.zone[(int64_t)q * b.N + j] >= b.n_zones) my_bad = 1;
-        if ((int)threadIdx.x < b.n_zones) {
-            const uint32_t w = b.zone_weight[(int64_t)q * kMaxZones + threadIdx.x];
-            if (w < 1u || w > 255u) my_bad = 1;
-        }
-    }
-    if (my_bad) atomicOr(&bad, 1);
+    if (query_inputs_bad(b, b.cfg, q, (int)threadIdx.x, (int)blockDim.x)) atomicOr(&bad, 1);
     __syncthreads();
     if (threadIdx.x == 0) valid[q] = bad ? 0 : 1;
 }
