@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the liveput optimizer's hot path on one MI355X.
 
-One step = one pass of the whole path (validate inputs, clear and sample histograms, liveput tables,
-look-ahead dynamic program, walk back) over one batch of synthetic planning queries whose inputs are
-already resident in HBM.  Prints ONE JSON line.
+One step = one pass of the whole path (clear and sample histograms, liveput tables, look-ahead dynamic program
+with its input checks, walk back) over one batch of synthetic planning queries whose inputs are already resident
+in HBM.  Prints ONE JSON line: the headline workload (the 1024-query what-if sweep unless --workload says
+otherwise) and, under "other_workloads", the GPU legs of the other measured shapes.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload sweep|large|medium|small|tiny]
 """
@@ -12,7 +13,6 @@ from __future__ import annotations
 import argparse
 import ctypes as ct
 import json
-import math
 import os
 import sys
 import time
@@ -24,29 +24,35 @@ if ROOT not in sys.path:
 # Plain 32-bit vector ALU peak: 256 compute units x 4 SIMDs x 32 lanes per cycle x 2.4 GHz = 78.6 T lane-op/s,
 # i.e. the chip's fp32 vector rate of 157.3 TFLOP/s with a fused multiply-add counted as ONE lane operation.
 ALU_PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
+HBM_PEAK_BYTES = 8e12
+
+# Counters of the sampling kernel per launch from the rocprofv3 --pmc runs summarised under profiles/:
+# HBM bytes (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel of known size) and executed vector
+# instructions (SQ_INSTS_VALU, wave instructions; x 64 = lane operations).  They belong to the sampling kernel's
+# sources and launch shape (the files below); once one of them changes the figures are withheld (null) until the
+# counters are taken again.
+COUNTER_SOURCES = ("device_common.hpp", "eval_kernels.hpp", "eval_launch.hpp")
+COUNTER_SOURCE_SHA256 = ""
+COUNTERS = {
+    # workload tag: (HBM bytes read, HBM bytes written, SQ_INSTS_VALU)
+}
 
 
-# HBM traffic of the sampling kernel per launch, from the rocprofv3 --pmc runs summarised under profiles/
-# (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel of known size), in bytes: (read, written).  The figures
-# belong to the sampling kernel's sources and its launch configuration (device_common.hpp, eval_kernels.hpp,
-# parcae_api.hip) with the digest below; once one of them changes the figures are withheld (traffic: null) until the counters are taken again.
-TRAFFIC_SOURCE_SHA256 = "e0584ee78caf92f051ac1330014c164013b7b0c5338292ca73d000bf710b300b"
-TRAFFIC_BYTES = {"sweep": (20.52e6, 70.57e6), "large": (5.22e6, 15.55e6)}
-
-
-def kernel_traffic(workload_tag: str):
-    """Measured HBM bytes per launch of the sampling kernel for this workload, or None."""
+def counter_digest() -> str:
     import hashlib
-    if workload_tag not in TRAFFIC_BYTES:
-        return None
     digest = hashlib.sha256()
-    for name in ("device_common.hpp", "eval_kernels.hpp", "parcae_api.hip"):
+    for name in COUNTER_SOURCES:
         with open(os.path.join(ROOT, "paper_2403_14097_amd", "csrc", name), "rb") as fh:
             digest.update(fh.read())
-    if digest.hexdigest() != TRAFFIC_SOURCE_SHA256:
-        return None
-    read, written = TRAFFIC_BYTES[workload_tag]
-    return read + written
+    return digest.hexdigest()
+
+
+def kernel_counters(workload_tag: str):
+    """(HBM bytes per launch, executed VALU wave-instructions per launch) of the sampling kernel, or (None, None)."""
+    if workload_tag not in COUNTERS or counter_digest() != COUNTER_SOURCE_SHA256:
+        return None, None
+    read, written, valu = COUNTERS[workload_tag]
+    return read + written, valu
 
 
 def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False, zoned=False):
@@ -135,7 +141,119 @@ def cpu_baseline(batch, budget_queries: int, pool_all: bool = False, max_threads
     scen = nq * units * s_cpu
     return {"value": scen / dt, "unit": "evals/s", "cores": threads, "kind": "oracle",
             "sample": f"first {nq} of {batch.n_queries} queries, first {s_cpu} of {batch.n_scenarios} scenarios per "
-                      f"unit, sampling + tables + plan, {dt:.2f} s"}
+                      f"unit (the oracle samples every unit, also those the GPU path writes in closed form), "
+                      f"sampling + tables + plan, {dt:.2f} s"}
+
+
+def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, pool_all=False, zones=0, rounds=False,
+            graph=False):
+    """GPU legs of one workload: whole steps (wall clock), the sampling kernel and the plan (HIP events recorded by
+    the library around them), the plan alone from stored histograms.  Returns (result dict, batch)."""
+    import torch
+    batch = pi.workload(name, dense=dense, n_queries=queries)
+    if zones:
+        batch = batch.with_zones(zones)
+    if rounds:
+        batch = batch.with_rounds()
+    prob = pk.upload(batch, device="cuda:0")
+    if pool_all:
+        prob.flags = pk.PARCAE_POOL_ALL
+    ev_out = pk.alloc_eval_out(prob)
+    pl_out = pk.alloc_plan_out(prob)
+    nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
+    scenarios = nq * T * C * S
+    cells = nq * T * C * C
+    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S, pool_all, zones > 0)
+
+    quads = [tuple(events.create() for _ in range(4)) for _ in range(steps)]
+    for _ in range(warmup):
+        pk.parcae_liveput_plan(prob, ev_out, pl_out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        prob.profile_events = quads[i]
+        pk.parcae_liveput_plan(prob, ev_out, pl_out)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    prob.profile_events = None
+    kern_s = sum(events.elapsed_ms(q[0], q[1]) for q in quads) / steps / 1e3
+    plan_in_step_s = sum(events.elapsed_ms(q[2], q[3]) for q in quads) / steps / 1e3
+
+    # the plan alone, from the histograms already in memory: device time between the library's own events around
+    # it, and wall clock per call with the calls enqueued back to back
+    reps = max(5, steps)
+    for _ in range(2):
+        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
+    torch.cuda.synchronize()
+    pairs = [(events.create(), events.create()) for _ in range(reps)]
+    t1 = time.perf_counter()
+    for i in range(reps):
+        prob.profile_events = (None, None, pairs[i][0], pairs[i][1])
+        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
+    torch.cuda.synchronize()
+    dp_wall_s = (time.perf_counter() - t1) / reps
+    prob.profile_events = None
+    dp_s = sorted(events.elapsed_ms(a, b) for a, b in pairs)[len(pairs) // 2] / 1e3   # median: a single launch is short
+    for q in quads:
+        for e in q:
+            events.destroy(e)
+    for a, b in pairs:
+        events.destroy(a)
+        events.destroy(b)
+
+    graph_ms = None
+    if graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            pk.parcae_liveput_plan(prob, ev_out, pl_out)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            pk.parcae_liveput_plan(prob, ev_out, pl_out)
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t2) / steps * 1e3
+
+    status = pl_out.status.cpu().numpy()
+    tag = batch.name + ("+pool-all" if pool_all else "") + (f"+zones{zones}" if zones else "") + ("+rounds" if rounds else "")
+    plain = not (dense or pool_all or zones or rounds)
+    counter_tag = (batch.name + (f"x{nq}" if queries else "")) if plain else ""
+    traffic, valu_insts = kernel_counters(counter_tag)
+    achieved = alg_ops / kern_s
+    # the plan reads both histograms once and writes F and the back-pointers: its algorithmic HBM bytes
+    dp_bytes = nq * T * batch.hist_len * 8 + nq * (T + 1) * C * 4 + nq * T * C * 4
+    res = {
+        "workload": tag, "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T, "n_configs": C,
+        "n_scenarios": S, "scenarios_per_step": scenarios, "sampled_scenarios_per_step": nontrivial,
+        "dp_cells_per_step": cells, "infeasible_queries": int((status != 0).sum()),
+        "ms_per_step": dt * 1e3, "sampling_kernel_ms": kern_s * 1e3, "plan_ms_in_step": plan_in_step_s * 1e3,
+        "dp_ms": dp_s * 1e3, "dp_wall_ms_per_call": dp_wall_s * 1e3,
+        "sampled_evals_per_sec": nontrivial / dt, "all_units_evals_per_sec": scenarios / dt,
+        "dp_cells_per_sec": cells / dp_s,
+        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
+                     "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
+                     "issue_frac": None if valu_insts is None else valu_insts * 64 / kern_s / ALU_PEAK_LANE_OPS,
+                     "model_ops": alg_ops, "executed_valu_wave_instructions": valu_insts,
+                     "traffic": traffic, "traffic_unit": "bytes per launch (HBM read + written)",
+                     "kernel": "eval_hist_kernel"},
+        # The plan is T dependent steps per query, so it cannot reach a throughput peak; what bounds a batch is the
+        # HBM traffic it cannot avoid (histograms read once, F and back-pointers written once).
+        "dp_roofline": {"bound": "hbm", "achieved": dp_bytes / dp_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
+                        "frac": dp_bytes / dp_s / HBM_PEAK_BYTES, "algorithmic_bytes": dp_bytes,
+                        "steps_in_chain": T, "us_per_step": dp_s * 1e6 / T,
+                        "alu_frac_at_15_ops_per_cell": cells / dp_s * 15 / ALU_PEAK_LANE_OPS},
+    }
+    if graph_ms is not None:
+        res["graph_replay_ms_per_step"] = graph_ms
+    del prob, ev_out, pl_out
+    torch.cuda.empty_cache()
+    return res, batch
 
 
 def main():
@@ -155,6 +273,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="also time replays of a HIP graph that captured one whole call (reported as "
                          "graph_replay_ms_per_step next to the eager figures; the call enqueues kernels only)")
+    ap.add_argument("--no-others", action="store_true", help="skip the other measured workloads (other_workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
     ap.add_argument("--cpu-threads", type=int, default=None, help="threads the CPU baseline may use (default: all)")
@@ -167,7 +286,6 @@ def main():
               "(queries would shard across GPUs with no exchange, which this program does not launch)", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import paper_2403_14097_amd as pk
@@ -179,21 +297,6 @@ def main():
     torch.cuda.set_device(0)
     pk.load_library()
 
-    batch = pi.workload(args.workload, dense=args.dense, n_queries=args.queries)
-    if args.zones:
-        batch = batch.with_zones(args.zones)
-    if args.rounds:
-        batch = batch.with_rounds()
-    prob = pk.upload(batch, device="cuda:0")
-    if args.pool_all:
-        prob.flags = pk.PARCAE_POOL_ALL
-    ev_out = pk.alloc_eval_out(prob)
-    pl_out = pk.alloc_plan_out(prob)
-    nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
-    scenarios = nq * T * C * S
-    cells = nq * T * C * C
-    alg_ops, nontrivial = algorithmic_lane_ops(batch.configs, batch.avail, S, args.pool_all, args.zones > 0)
-
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -203,100 +306,58 @@ def main():
         del src, dst
 
     events = HipEvents()
-    pairs = [(events.create(), events.create()) for _ in range(args.steps)]
-
-    for _ in range(args.warmup):
-        pk.parcae_liveput_plan(prob, ev_out, pl_out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        prob.profile_events = (pairs[i][0], pairs[i][1], None, None)
-        pk.parcae_liveput_plan(prob, ev_out, pl_out)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prob.profile_events = None
-    kern_ms = [events.elapsed_ms(a, b) for a, b in pairs]
-    for a, b in pairs:
-        events.destroy(a)
-        events.destroy(b)
-    kern_avg_s = sum(kern_ms) / len(kern_ms) / 1e3
-
-    # the DP alone, from the histograms already in memory (same timed-region rules)
-    for _ in range(2):
-        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dp_reps = max(3, args.steps)
-    for _ in range(dp_reps):
-        pk.parcae_plan_from_hist(prob, ev_out.hist_int, ev_out.hist_min, pl_out)
-    torch.cuda.synchronize()
-    dp_s = (time.perf_counter() - t1) / dp_reps
-
-    graph_ms = None
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            pk.parcae_liveput_plan(prob, ev_out, pl_out)
-        side.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            pk.parcae_liveput_plan(prob, ev_out, pl_out)
-        for _ in range(args.warmup):
-            graph.replay()
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t2) / args.steps * 1e3
-
-    status = pl_out.status.cpu().numpy()
-    plain = not (args.dense or args.pool_all or args.zones or args.rounds or args.queries)
-    out_tag = batch.name if plain else ""
-    ms_per_step = dt / args.steps * 1e3
-    achieved = alg_ops / kern_avg_s
+    head, batch = measure(pk, pi, events, args.workload, args.steps, args.warmup, dense=args.dense, queries=args.queries,
+                          pool_all=args.pool_all, zones=args.zones, rounds=args.rounds, graph=args.graph)
     out = {
         "metric": "liveput_evals_per_sec",
-        "value": scenarios / (dt / args.steps),
+        # scenarios that go through the sampler and the reducer, per second of the whole step; the units whose
+        # scenarios all fall into one bin are written in closed form and are NOT counted here (all_units_evals_per_sec
+        # counts them)
+        "value": head["sampled_evals_per_sec"],
         "unit": "evals/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "u32+f32",
         "data": "synthetic",
-        "config": {"workload": batch.name + ("+pool-all" if args.pool_all else "") + (f"+zones{args.zones}" if args.zones else "") + ("+rounds" if args.rounds else ""), "n_queries": nq, "n_instances": batch.n_instances, "n_intervals": T,
-                   "n_configs": C, "n_scenarios": S, "scenarios_per_step": scenarios,
-                   "nontrivial_scenarios_per_step": nontrivial, "dp_cells_per_step": cells,
-                   "infeasible_queries": int((status != 0).sum())},
-        "nontrivial_evals_per_sec": nontrivial / (dt / args.steps),
-        "dp_cells_per_sec": cells / dp_s,
-        "dp_ms": dp_s * 1e3,
-        "sampling_kernel_ms": kern_avg_s * 1e3,
-        # The plan is a chain of T dependent steps per query: bound by the latency of a step (a handful of dependent
-        # LDS round trips and two barriers), not by a throughput roofline.  For reference: its rate against the ALU
-        # peak at 15 lane-ops per cell (weights formed on the fly) and against HBM at 8 bytes per cell (weights
-        # written and read once, the few-query path).
-        "dp_roofline": {"bound": "latency", "steps_in_chain": T, "us_per_step": dp_s * 1e6 / T,
-                        "alu_frac_at_15_ops_per_cell": cells / dp_s * 15 / ALU_PEAK_LANE_OPS,
-                        "hbm_frac_at_8_bytes_per_cell": cells / dp_s * 8 / 8e12},
-        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
-                     "traffic": kernel_traffic(out_tag), "traffic_unit": "bytes per launch (HBM read + written)",
-                     "kernel": "eval_hist_kernel", "algorithmic_lane_ops_per_launch": alg_ops,
-                     "note": "algorithmic lane-ops per launch = sum over units of S * A(M, k, P), the textbook operation count "
-                             "of the method (see algorithmic_lane_ops); peak = 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz, the "
-                             "rate at which gfx950 issues simple 32-bit vector ops (measured 2.2 cycles per wave64 "
-                             "instruction); 32-bit multiplies, left shifts, compares and popcounts issue at half "
-                             "that rate, so a kernel with this mix cannot reach 1; measured VALU busy is in profiles/"},
+        "config": {k: head[k] for k in ("workload", "n_queries", "n_instances", "n_intervals", "n_configs", "n_scenarios",
+                                        "scenarios_per_step", "sampled_scenarios_per_step", "dp_cells_per_step",
+                                        "infeasible_queries")},
+        "all_units_evals_per_sec": head["all_units_evals_per_sec"],
+        "dp_cells_per_sec": head["dp_cells_per_sec"],
+        "dp_ms": head["dp_ms"],
+        "dp_wall_ms_per_call": head["dp_wall_ms_per_call"],
+        "plan_ms_in_step": head["plan_ms_in_step"],
+        "sampling_kernel_ms": head["sampling_kernel_ms"],
+        "dp_roofline": head["dp_roofline"],
+        "roofline": head["roofline"],
     }
-    if graph_ms is not None:
-        out["graph_replay_ms_per_step"] = graph_ms
+    out["roofline"]["note"] = (
+        "frac = model_ops / kernel time / peak: model_ops is the textbook operation count of the method, the sum over "
+        "units of S * A(M, k, P) (see algorithmic_lane_ops); issue_frac = executed vector instructions x 64 lanes / "
+        "kernel time / peak, from SQ_INSTS_VALU of the rocprofv3 run summarised in profiles/ (null when the kernel "
+        "has changed since); the kernel issues fused forms (64-bit multiply-add, three-input logic, bit-sliced "
+        "counters), so it executes fewer operations than the model counts; peak = 256 CUs x 4 SIMDs x 32 lanes/cycle "
+        "x 2.4 GHz, the rate of simple 32-bit vector ops; multiplies, shifts, compares and popcounts issue at half "
+        "that rate")
+    if "graph_replay_ms_per_step" in head:
+        out["graph_replay_ms_per_step"] = head["graph_replay_ms_per_step"]
+
+    plain_sweep = args.workload == "sweep" and not (args.dense or args.pool_all or args.zones or args.rounds or args.queries)
+    if plain_sweep and not args.no_others:
+        others = []
+        for name, nq, k in (("large", None, 10), ("medium", 256, 5), ("large", 256, 2), ("medium", None, 20)):
+            res, _ = measure(pk, pi, events, name, k, 2, queries=nq)
+            res["workload"] = name + (f" x {nq} seeds" if nq else "")
+            others.append(res)
+        out["other_workloads"] = others
+
     if not args.no_cpu_baseline:
+        nq, T, C, S = batch.n_queries, batch.n_intervals, batch.n_configs, batch.n_scenarios
         per_query = T * C * S
         threads_hint = args.cpu_threads or (os.cpu_count() or 1)
         budget = args.cpu_queries or max(1, min(nq, int(6e7 * min(threads_hint, 16) // max(per_query, 1)) or 1))

@@ -13,6 +13,7 @@
 #include "../../include/parcae.h"
 #include "device_common.hpp"
 #include "eval_kernels.hpp"
+#include "eval_launch.hpp"
 #include "plan_kernels.hpp"
 #include "plan_wave.hpp"
 #include "replay_kernels.hpp"
@@ -209,20 +210,6 @@ size_t bp16_bytes_for(int T, int C)
     return need <= kMaxBpLds ? need : 0;
 }
 
-// Scenarios per work item of the sampling kernel (one wave processes an item, 64 scenarios at a time), from
-// timings over batches of 1 to 1024 queries of every workload shape: 1024 suits nearly all of them (an item has
-// to be long enough to pay for its claim and its table loads, short enough that the last items do not leave the
-// chip half empty); very large launches gain a little from 2048, launches that cannot even give every wave two
-// rounds of 64 scenarios from 512; pools of more than 128 instances cost about twice as much per scenario, so
-// their items are half as long.  About a quarter of the units need sampling at all.
-int pick_chunk_len(int64_t n_units, int S, int n_instances, int64_t n_waves)
-{
-    const int64_t rounds_per_wave = n_units * (int64_t)S / 64 / 4 / n_waves;
-    int chunk = rounds_per_wave >= 1024 ? 2048 : (rounds_per_wave < 2 ? 512 : 1024);
-    if (n_instances > 128) chunk /= 2;
-    return S < chunk ? S : chunk;
-}
-
 parcae::WorkQueue make_queue(const Layout& lay, void* ws)
 {
     unsigned char* base = static_cast<unsigned char*>(ws);
@@ -241,7 +228,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return PARCAE_EHIP;
-    const int chunk_len = pick_chunk_len(n_units, b.S, b.N, (int64_t)cus * 28);
+    const int chunk_len = parcae::pick_chunk_len(n_units, b.S, b.N, (int64_t)cus * parcae::kEvalWavesPerCu);
     const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
     if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counter to overshoot
     const parcae::WorkQueue wq = make_queue(lay, ws);
@@ -255,10 +242,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
                                 dim3(parcae::kBuildThreads), 0, st>>>(b, wq);
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
 
-    // persistent waves: enough blocks to fill every compute unit, never more than there are items
-    int64_t eval_blocks = (int64_t)cus * 8;
-    const int64_t max_useful = (n_units * n_chunks + 3) / 4;
-    if (eval_blocks > max_useful) eval_blocks = max_useful;
+    const int64_t eval_blocks = parcae::eval_grid_blocks(cus, n_units * n_chunks);
     if (p->profile && record(p->profile->event_before_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
     if (b.n_zones > 0)
         parcae::eval_hist_kernel<true><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
@@ -314,8 +298,13 @@ struct WaveLaunch {
 
 bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g, int cus, WaveLaunch* out)
 {
-    // few queries: more waves per query share the work that is parallel (weights, back-pointers)
-    int threads = nq >= 3 * cus ? 64 : (2 * nq >= 3 * cus ? 128 : (2 * nq >= cus ? 256 : 512));
+    // A handful of queries with long candidate lists: one workgroup per query leaves the chip empty while it works
+    // through the weights and back-pointers of every step, and writing the weights out with a workgroup per
+    // (query, step) is quicker (measured: one query of 60 candidates and 60 steps 0.23 ms here, 0.14 ms there).
+    if (nq < kFusedMinQueries && C > 32) return false;
+    // four waves per query share the work that is parallel (weights, back-pointers) and hide each other's waits on
+    // local memory; very large batches take two, a handful of queries eight
+    int threads = nq >= 8 * cus ? 128 : (nq > cus ? 256 : 512);
     while ((int64_t)parcae::kWaveRowRegs * threads < L && threads < 512) threads *= 2;  // a step's rows must fit the prefetch registers
     if ((int64_t)parcae::kWaveRowRegs * threads < L) return false;
     int resident = (nq + cus - 1) / cus;  // workgroups that should share a compute unit
@@ -359,9 +348,24 @@ bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layo
                             parcae::wave_geometry(table, p->n_configs), cus, &wl);
 }
 
+int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
+                        const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start,
+                        float* objective, int32_t* status, hipStream_t st);
+
+// The dynamic program, bracketed by the caller's profiling events if there are any.
 int launch_plan(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
                 const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective,
-                int32_t* status, hipStream_t st)
+                int32_t* status, hipStream_t st, const parcae_profile* prof = nullptr)
+{
+    if (prof && record(prof->event_before_plan, st) != PARCAE_OK) return PARCAE_EHIP;
+    const int rc = launch_plan_kernels(b, table, lay, ws, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    if (rc != PARCAE_OK) return rc;
+    return prof ? record(prof->event_after_plan, st) : PARCAE_OK;
+}
+
+int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
+                        const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start,
+                        float* objective, int32_t* status, hipStream_t st)
 {
     unsigned char* base = static_cast<unsigned char*>(ws);
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
@@ -536,7 +540,8 @@ int parcae_plan_from_hist(const parcae_problem* problem, const uint32_t* hist_in
     // the wave planner takes the candidate table as a kernel argument and checks the inputs itself: one launch
     if (!takes_wave_planner(p, table.data(), lay) && (rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK)
         return rc;
-    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st,
+                       p->profile);
 }
 
 int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput, float* teff,
@@ -559,7 +564,8 @@ int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint3
         return rc;
     if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
         return rc;
-    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st,
+                       p->profile);
 }
 
 int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput,
@@ -585,7 +591,7 @@ int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int
         return rc;
     if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
         return rc;
-    return launch_plan(b, table, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    return launch_plan(b, table, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st, p->profile);
 }
 
 int parcae_transition_weights(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* W,

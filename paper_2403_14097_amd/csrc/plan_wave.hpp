@@ -21,7 +21,7 @@
 namespace parcae {
 
 constexpr int kWaveMaxConfigs = 64;
-constexpr int kWaveRowRegs = 24;  // histogram words per thread and histogram that hold the rows of the next chunk
+constexpr int kWaveRowRegs = 8;  // histogram words per thread and histogram that hold the rows of the next chunk
 
 // The candidate table as the kernel takes it (by value, as a kernel argument): the candidates, and per candidate
 // its depth group [lo, hi), the slot of the group in the group-aligned layout and the first cell of the group.
@@ -37,13 +37,14 @@ struct WaveGeom {
     int ws;      // floats per target row of the same-depth weights: gp + 4 (keeps 16-byte reads of neighbouring rows on different banks)
     int cpad;    // slots of the value function in its group-aligned layout, with gp slots of padding at the end
     int ncells;  // same-depth (source, target) pairs of one step
+    uint32_t inv_ncells, inv_C;  // floor(2^32 / d) + 1: (x * inv) >> 32 == x / d for the index ranges of the kernel
 };
 
 __host__ __device__ inline int round_up4(int x) { return (x + 3) & ~3; }
 
 __host__ __device__ inline WaveGeom wave_geometry(const CfgRec* rec, int C)
 {
-    WaveGeom g{0, 0, 0, 0};
+    WaveGeom g{0, 0, 0, 0, 0u, 0u};
     int widest = 0, slots = 0;
     for (int i = 0; i < C;) {
         int j = i + 1;
@@ -57,8 +58,15 @@ __host__ __device__ inline WaveGeom wave_geometry(const CfgRec* rec, int C)
     g.gp = round_up4(widest);
     g.ws = g.gp + 4;
     g.cpad = slots + g.gp;
+    // exact for x < 2^18 and 2 <= d <= 2^12 (x * d < 2^32): at most 63 steps of 4096 pairs or 64 candidates per
+    // chunk; d = 1 has no 32-bit reciprocal and is divided by directly (see fast_div)
+    g.inv_ncells = g.ncells > 1 ? (uint32_t)(((uint64_t)1 << 32) / (uint32_t)g.ncells) + 1u : 0u;
+    g.inv_C = C > 1 ? (uint32_t)(((uint64_t)1 << 32) / (uint32_t)C) + 1u : 0u;
     return g;
 }
+
+// x / d by the reciprocal above (inv == 0 stands for d == 1).
+__device__ __forceinline__ int fast_div(int x, uint32_t inv) { return inv ? (int)__umulhi((uint32_t)x, inv) : x; }
 
 inline void wave_fill_table(const CfgRec* rec, int C, WaveTable& tb)
 {
@@ -86,17 +94,19 @@ inline void wave_fill_table(const CfgRec* rec, int C, WaveTable& tb)
 __host__ __device__ inline size_t wave_fixed_lds(int C, int T, const WaveGeom& g, bool bp_in_lds)
 {
     size_t o = sizeof(CfgRec) * (size_t)C;         // cfg
+    o += 16 * (size_t)C;                            // target record: full, e[3]
     o += 4 * (size_t)C * 8;                         // full, e[3], rnd[3], R
     o += 4 * (size_t)C * 2;                         // group span, slot of the candidate
-    o += 4 * ((size_t)T + 2);                       // availability
-    o += 2 * (size_t)round_up4(g.ncells);           // cell list
+    o += 4 * (((size_t)T + 3) & ~(size_t)1);        // availability (even count: the cell list needs 8-byte alignment)
+    o += 8 * (size_t)g.ncells;                      // cell list
+    o += (size_t)round_up4(g.cpad);                 // candidate of every slot
     o = (o + 15) & ~(size_t)15;
     if (bp_in_lds) o += (2 * (size_t)T * (size_t)C + 15) & ~(size_t)15;
     return o + 32;  // alignment of the per-chunk arrays
 }
 __host__ __device__ inline size_t wave_step_lds(int C, int L, const WaveGeom& g)
 {
-    return 8 * (size_t)L + 4 * (size_t)C * g.ws + 4 * (size_t)g.cpad + 4 * (size_t)C;
+    return 8 * (size_t)L + 4 * (size_t)C * g.ws + 4 * (size_t)g.cpad + 4 * (size_t)C + (size_t)round_up4(C);
 }
 
 struct WaveShared {
@@ -105,13 +115,18 @@ struct WaveShared {
     uint32_t* span;      // [C] candidates of the depth of c: first | (one past last) << 8 | slot of the first << 16
     int* slot;           // [C] slot of candidate c in the group-aligned layout of the value function
     int* av;             // [T + 1] availability, clamped to [0, N]
-    uint16_t* cell;      // [ncells] same-depth pairs: source | target << 8
+    float4* tgt;         // [C] what a weight needs of its target: full throughput, max(0, tau - cost) of the three classes
+    uint2* cell;         // [ncells] same-depth pairs (source c, target c2), ready-made indices:
+                         //   x = bin of c's row at the width of c2 (off + min(D2, D)) | first bin of c's row << 16
+                         //   y = c2 | (c2 * ws + c - lo) << 8 | c << 24 | (D2 <= D) << 31
+    uint8_t* cand;       // [cpad] candidate of every slot of the group-aligned layout, 0xff for padding
     uint16_t* bp16;      // [T][C] back-pointers, or null
     uint32_t* tail_int;  // [Tc][L]
     uint32_t* tail_min;  // [Tc][L]
     float* wsame;        // [Tc][C][ws]
     float* feff;         // [Tc][cpad]
     float* fnew;         // [Tc][C]
+    uint8_t* oflag;      // [Tc][C] the new value is reached from another depth (possibly among others)
 };
 
 __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, int T, int Tc, const WaveGeom& g,
@@ -119,14 +134,16 @@ __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, in
 {
     size_t o = 0;
     w.ps.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
+    w.tgt = reinterpret_cast<float4*>(smem + o); o += 16 * (size_t)C;
     w.ps.full = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
     w.ps.e = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
     w.ps.rnd = reinterpret_cast<float*>(smem + o); o += 12 * (size_t)C;
     w.R = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)C;
     w.span = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)C;
     w.slot = reinterpret_cast<int*>(smem + o); o += 4 * (size_t)C;
-    w.av = reinterpret_cast<int*>(smem + o); o += 4 * ((size_t)T + 2);
-    w.cell = reinterpret_cast<uint16_t*>(smem + o); o += 2 * (size_t)round_up4(g.ncells);
+    w.av = reinterpret_cast<int*>(smem + o); o += 4 * (((size_t)T + 3) & ~(size_t)1);
+    w.cell = reinterpret_cast<uint2*>(smem + o); o += 8 * (size_t)g.ncells;
+    w.cand = reinterpret_cast<uint8_t*>(smem + o); o += (size_t)round_up4(g.cpad);
     o = (o + 15) & ~(size_t)15;
     w.bp16 = nullptr;
     if (bp_in_lds) {
@@ -138,7 +155,8 @@ __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, in
     o = (o + 15) & ~(size_t)15;
     w.wsame = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)Tc * C * g.ws;
     w.feff = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)Tc * g.cpad;
-    w.fnew = reinterpret_cast<float*>(smem + o);
+    w.fnew = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)Tc * C;
+    w.oflag = smem + o;
     w.ps.from_ok = w.ps.to_ok = w.ps.chunk_start = nullptr;
     w.ps.F = w.ps.Feff = w.ps.R = nullptr;
     w.ps.gspan = nullptr;
@@ -153,14 +171,15 @@ __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, in
 
 // The value function holds -inf or non-negative floats (sums of non-negative weights), and on those the signed
 // order of the bit patterns is the order of the floats: the cross-lane maxima below are integer maxima, which the
-// data-parallel primitives (DPP) can feed directly.
+// data-parallel primitives (DPP) feed directly.
 constexpr int kNegInfBits = (int)0xff800000u;
+constexpr int kIntMin = (int)0x80000000u;
 
-// max(v, value of another lane); lanes without a source lane keep v.
+// max(v, value of another lane); lanes without a source lane see the identity of max and keep v.
 template <int kCtrl, int kRowMask>
 __device__ __forceinline__ int dpp_max(int v)
 {
-    const int moved = __builtin_amdgcn_update_dpp(v, v, kCtrl, kRowMask, 0xf, false);
+    const int moved = __builtin_amdgcn_update_dpp(kIntMin, v, kCtrl, kRowMask, 0xf, false);
     return moved > v ? moved : v;
 }
 
@@ -176,6 +195,21 @@ __device__ __forceinline__ int wave_prefix_max(int v)
     return v;
 }
 
+// Inclusive suffix maximum: lane i gets the maximum of lanes i..63.  Inside a row of 16 lanes by shifts; the rows
+// above a lane's own row come in through three lane reads (the data-parallel primitives broadcast upwards only).
+__device__ __forceinline__ int wave_suffix_max(int v, int lane)
+{
+    v = dpp_max<0x101, 0xf>(v);  // row_shl:1
+    v = dpp_max<0x102, 0xf>(v);  // row_shl:2
+    v = dpp_max<0x104, 0xf>(v);  // row_shl:4
+    v = dpp_max<0x108, 0xf>(v);  // row_shl:8
+    const int r1 = __builtin_amdgcn_readlane(v, 16), r2 = __builtin_amdgcn_readlane(v, 32);
+    const int r3 = __builtin_amdgcn_readlane(v, 48);
+    const int r23 = r2 > r3 ? r2 : r3, r123 = r1 > r23 ? r1 : r23;
+    const int above = lane < 16 ? r123 : (lane < 32 ? r23 : (lane < 48 ? r3 : kIntMin));
+    return above > v ? above : v;
+}
+
 __device__ __forceinline__ int lane_value(int v, int src_lane)
 {
     return __builtin_amdgcn_ds_bpermute(src_lane << 2, v);
@@ -187,9 +221,33 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// Suffix sums inside a histogram row of D + 1 bins that starts at bin o (slot 0 keeps the raw bin 0), eight bins at
+// a time with every load before the first use; the last, partial batch runs on clamped indices with its updates
+// predicated, so that there is no one-bin-at-a-time tail.
+__device__ __forceinline__ void suffix_row_batched(uint32_t* tail_int, uint32_t* tail_min, int o, int D)
+{
+    uint32_t ri = 0u, rm = 0u;
+    for (int j = D; j >= 1; j -= 8) {
+        uint32_t vi[8], vm[8];
+        static_for<8>([&](auto x) {
+            const int at = j - x.value >= 1 ? j - x.value : 1;
+            vi[x.value] = tail_int[o + at];
+            vm[x.value] = tail_min[o + at];
+        });
+        static_for<8>([&](auto x) {
+            if (j - x.value >= 1) {
+                ri += vi[x.value];
+                rm += vm[x.value];
+                tail_int[o + j - x.value] = ri;
+                tail_min[o + j - x.value] = rm;
+            }
+        });
+    }
+}
+
 // One workgroup (1 to 8 waves) per query.
 template <bool kRounds>
-__global__ void __launch_bounds__(512) plan_wave_kernel(
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) plan_wave_kernel(
     Batch b, WaveTable table, WaveGeom g, int Tc, int bp_in_lds, const uint32_t* __restrict__ hist_int,
     const uint32_t* __restrict__ hist_min, float* __restrict__ F, int32_t* __restrict__ bp,
     int32_t* __restrict__ plan, int32_t* __restrict__ start, float* __restrict__ objective,
@@ -203,7 +261,11 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
     const int q = blockIdx.x;
     const int tid = (int)threadIdx.x, nthreads = (int)blockDim.x;
     const int lane = tid & (kWave - 1);
-    const bool chain_wave = tid < kWave;
+    // the chain runs on one wave; which one rotates with the query, so that the chains of the workgroups that share a
+    // compute unit do not all sit on the same SIMD
+    const int n_waves = nthreads / kWave;
+    const int chain_first = (q % n_waves) * kWave;
+    const bool chain_wave = tid >= chain_first && tid < chain_first + kWave;
     const int64_t hist_base = (int64_t)q * T * L;
 
     // rows of a chunk: n * L consecutive words of each histogram; thread x holds words x, x + nthreads, ...
@@ -234,37 +296,47 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
 
     // ---- per-query tables
     if (tid == 0) bad_inputs = 0;
+    for (int p = tid; p < g.cpad; p += nthreads) w.cand[p] = 0xffu;  // padding slots hold no candidate
+    __syncthreads();
     for (int c = tid; c < C; c += nthreads) {
         const CfgRec cr = table.rec[c];
         w.ps.cfg[c] = cr;
         const float full = b.thr[(int64_t)q * L + cr.off + cr.D];
         const float* co = b.cost + ((int64_t)q * C + c) * 3;
+        const float e0 = max0(__fsub_rn(b.tau, co[0])), e1 = max0(__fsub_rn(b.tau, co[1]));
         const float e2 = max0(__fsub_rn(b.tau, co[2]));
+        w.tgt[c] = make_float4(full, e0, e1, e2);
         w.ps.full[c] = full;
-        w.ps.e[3 * c + 0] = max0(__fsub_rn(b.tau, co[0]));
-        w.ps.e[3 * c + 1] = max0(__fsub_rn(b.tau, co[1]));
+        w.ps.e[3 * c + 0] = e0;
+        w.ps.e[3 * c + 1] = e1;
         w.ps.e[3 * c + 2] = e2;
         w.ps.rnd[3 * c + 0] = co[1];
         w.ps.rnd[3 * c + 1] = co[2];
         w.ps.rnd[3 * c + 2] = b.cost_round ? b.cost_round[(int64_t)q * C + c] : 0.0f;
         w.R[c] = __fmul_rn(full, e2);
-        // depth group of c (candidates are sorted by depth): its pairs in the cell list
+        // depth group of c (candidates are sorted by depth): its pairs in the cell list, its slot
         const uint32_t sp = table.span[c];
         const int lo = (int)(sp & 0xffu), hi = (int)((sp >> 8) & 0xffu);
+        const int slot = (int)(sp >> 16) + c - lo;
         w.span[c] = sp;
-        w.slot[c] = (int)(sp >> 16) + c - lo;
+        w.slot[c] = slot;
+        w.cand[slot] = (uint8_t)c;
         const int size = hi - lo, cells = (int)table.cell0[c];
-        for (int i = 0; i < size; ++i) w.cell[cells + (c - lo) * size + i] = (uint16_t)(c | ((lo + i) << 8));
+        for (int i = 0; i < size; ++i) {
+            const int c2 = lo + i, D2 = table.rec[c2].D;
+            const uint32_t x = (uint32_t)(cr.off + (D2 <= cr.D ? D2 : cr.D)) | ((uint32_t)cr.off << 16);
+            const uint32_t y = (uint32_t)c2 | ((uint32_t)(c2 * g.ws + c - lo) << 8) | ((uint32_t)c << 24) |
+                               (D2 <= cr.D ? 0x80000000u : 0u);
+            w.cell[cells + (c - lo) * size + i] = make_uint2(x, y);
+        }
     }
     for (int t = tid; t <= T; t += nthreads) w.av[t] = clampi(b.avail[(int64_t)q * b.avail_stride + t], 0, b.N);
     for (int i = tid; i < Tc * C * g.ws; i += nthreads) w.wsame[i] = kNegInf;  // padding of the weight rows stays -inf
     for (int i = tid; i < Tc * g.cpad; i += nthreads) w.feff[i] = kNegInf;      // padding slots of the value function too
-    __syncthreads();
-    if (query_inputs_bad(b, w.ps.cfg, q, tid, nthreads)) atomicOr(&bad_inputs, 1);
     const int cur = b.cur_config ? b.cur_config[q] : -1;
     const bool cold = cur == -2;
 
-    // ---- lane state of the chain (wave 0; lane = candidate)
+    // ---- lane state of the chain (lane = candidate)
     const int lc = lane < C ? lane : C - 1;  // lanes past the list compute on the last candidate and store nothing
     const bool is_cand = chain_wave && lane < C;
     const CfgRec mine = table.rec[lc];
@@ -274,6 +346,13 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
     float* Fq = F ? F + (int64_t)q * (T + 1) * C : nullptr;
     int32_t* bpq = bp ? bp + (int64_t)q * T * C : nullptr;
     if (Fq && is_cand) Fq[lane] = 0.0f;
+    __syncthreads();
+    // the input checks wait on memory: the waves that do not carry the chain run them while the first chain runs
+    // (a workgroup of one wave runs them here)
+    auto check_inputs = [&](int rank, int count) __attribute__((always_inline)) {
+        if (query_inputs_bad(b, w.ps.cfg, q, rank, count)) atomicOr(&bad_inputs, 1);
+    };
+    if (n_waves == 1) check_inputs(tid, nthreads);
 
     for (int t0 = 0; t0 < T; t0 += Tc) {
         const int n = T - t0 < Tc ? T - t0 : Tc;
@@ -282,21 +361,55 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
         if (t0 + Tc < T) fetch_rows(t0 + Tc);
         // suffix sums inside every row of the chunk
         for (int row = tid; row < n * C; row += nthreads) {
-            const int ti = row / C;
+            const int ti = fast_div(row, g.inv_C);
             const CfgRec cr = w.ps.cfg[row - ti * C];
-            suffix_row(w.ps, cr, ti * L + cr.off);
+            suffix_row_batched(w.tail_int, w.tail_min, ti * L + cr.off, cr.D);
         }
         __syncthreads();
-        // phase A: weights of the same-depth transitions
-        for (int e = tid; e < n * g.ncells; e += nthreads) {
-            const int ti = e / g.ncells;
-            const uint32_t pair = w.cell[e - ti * g.ncells];
-            const int c = (int)(pair & 0xffu), c2 = (int)(pair >> 8);
-            PlanShared ps = w.ps;
-            ps.tail_int = w.tail_int + ti * L;
-            ps.tail_min = w.tail_min + ti * L;
-            const float wt = same_depth_weight<kRounds>(b, ps, 0, c, c2);
-            w.wsame[(ti * C + c2) * g.ws + (c - (int)(w.span[c2] & 0xffu))] = wt;
+        // phase A: weights of the same-depth transitions, four pairs at a time (loads of the four travel together)
+        const int n_pairs = n * g.ncells;
+        for (int e0 = tid; e0 < n_pairs; e0 += 4 * nthreads) {
+            int ti[4];
+            uint2 cell[4];
+            bool live[4];
+            static_for<4>([&](auto k) {
+                const int e = e0 + k.value * nthreads;
+                live[k.value] = e < n_pairs;
+                const int ec = live[k.value] ? e : e0;
+                ti[k.value] = fast_div(ec, g.inv_ncells);
+                cell[k.value] = w.cell[ec - ti[k.value] * g.ncells];
+            });
+            float wt[4];
+            if constexpr (kRounds) {
+                static_for<4>([&](auto k) {
+                    PlanShared ps = w.ps;
+                    ps.tail_int = w.tail_int + ti[k.value] * L;
+                    ps.tail_min = w.tail_min + ti[k.value] * L;
+                    wt[k.value] = same_depth_weight<true>(b, ps, 0, (int)((cell[k.value].y >> 24) & 0x3fu),
+                                                          (int)(cell[k.value].y & 0xffu));
+                });
+            } else {
+                uint32_t t_int[4], t_min[4], h0[4];
+                float4 tg[4];
+                static_for<4>([&](auto k) {
+                    const uint32_t* ri = w.tail_int + ti[k.value] * L;
+                    const uint32_t* rm = w.tail_min + ti[k.value] * L;
+                    t_int[k.value] = ri[cell[k.value].x & 0xffffu];
+                    t_min[k.value] = rm[cell[k.value].x & 0xffffu];
+                    h0[k.value] = rm[cell[k.value].x >> 16];
+                    tg[k.value] = w.tgt[cell[k.value].y & 0xffu];
+                });
+                static_for<4>([&](auto k) {
+                    // a target wider than the source keeps nothing (the width of a target is at least 1)
+                    const bool keep = (cell[k.value].y & 0x80000000u) != 0u;
+                    const uint32_t n0 = keep ? t_int[k.value] : 0u, n01 = keep ? t_min[k.value] : 0u;
+                    wt[k.value] = __fmul_rn(tg[k.value].x, teff_from_counts(n0, n01, h0[k.value], 1, (uint32_t)b.S, b.tau,
+                                                                            tg[k.value].y, tg[k.value].z, tg[k.value].w));
+                });
+            }
+            static_for<4>([&](auto k) {
+                if (live[k.value]) w.wsame[ti[k.value] * C * g.ws + (int)((cell[k.value].y >> 8) & 0xffffu)] = wt[k.value];
+            });
         }
         __syncthreads();
         // chain: values only
@@ -306,35 +419,55 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
             const int gslot = (int)(sp >> 16);
             const float reach = w.R[lc];
             const int n4 = g.gp / 4;
-            const int av_mine = w.av[t0 + lane <= T ? t0 + lane : T];  // lane i holds the availability of step t0 + i
+            // whether this lane's candidate may be left / entered at each step of the chunk (constraint D * P <= N of
+            // Eq. 6, memory floor, the current configuration at t = 0), one bit per step, before the dependent steps
+            unsigned long long from_bits = 0ull, to_bits = 0ull;
             for (int ti = 0; ti < n; ++ti) {
                 const int t = t0 + ti;
-                const int a_prev = b.group * __builtin_amdgcn_readlane(av_mine, ti);
-                const int a_next = b.group * __builtin_amdgcn_readlane(av_mine, ti + 1);
-                const bool from = is_cand && used <= a_prev && deep && (t > 0 || cur < 0 || lane == cur);
-                const bool to = used <= a_next && deep;
+                const bool from = used <= b.group * w.av[t] && deep && (t > 0 || cur < 0 || lane == cur);
+                const bool to = used <= b.group * w.av[t + 1] && deep;
+                from_bits |= (unsigned long long)(from && is_cand) << ti;
+                to_bits |= (unsigned long long)to << ti;
+            }
+            for (int ti = 0; ti < n; ++ti) {
+                const int t = t0 + ti;
+                const bool from = (from_bits >> ti) & 1ull;
+                const bool to = (to_bits >> ti) & 1ull;
                 const float fe = from ? Fcur : kNegInf;
                 float* frow = w.feff + ti * g.cpad;
                 if (is_cand) frow[gslot + lane - lo] = fe;
-                float fn;
+                float fn, other;
                 if (t == 0 && cold) {
-                    fn = __fadd_rn(0.0f, reach);  // nothing is running: c' comes up from nothing at its re-partition cost
+                    other = __fadd_rn(0.0f, reach);  // nothing is running: c' comes up from nothing at its re-partition cost
+                    fn = other;
                 } else {
-                    // largest value among the candidates of other depths: those before the group and those after it
-                    const int fb = __float_as_int(fe);
-                    const int pm = wave_prefix_max(fb);
-                    const int sm = wave_prefix_max(lane_value(fb, kWave - 1 - lane));
-                    const int before = lane_value(pm, lo > 0 ? lo - 1 : 0);
-                    const int after = lane_value(sm, hi < kWave ? kWave - 1 - hi : 0);
-                    const int ob = lo > 0 ? before : kNegInfBits, oa = hi < kWave ? after : kNegInfBits;
-                    fn = __fadd_rn(__int_as_float(ob > oa ? ob : oa), reach);
-                    wave_sync();  // the group's values are in local memory
-                    // same depth: 16 sources at a time, every load before the first use (indices clamped: a source
+                    wave_sync();  // the values of this step are in local memory
+                    // same depth, first 16 sources: the loads go out before anything else (indices clamped: a source
                     // taken twice does not change a maximum)
                     const float4* f4 = reinterpret_cast<const float4*>(frow + gslot);
                     const float4* w4 = reinterpret_cast<const float4*>(w.wsame + (ti * C + lc) * g.ws);
-                    for (int i0 = 0; i0 < n4; i0 += 4) {
-                        float4 f[4], x[4];
+                    float4 f[4], x[4];
+                    static_for<4>([&](auto k) {
+                        const int i = k.value < n4 ? k.value : n4 - 1;
+                        f[k.value] = f4[i];
+                        x[k.value] = w4[i];
+                    });
+                    // largest value among the candidates of other depths: those before the group and those after it
+                    const int fb = __float_as_int(fe);
+                    const int pm = wave_prefix_max(fb);
+                    const int sm = wave_suffix_max(fb, lane);
+                    const int before = lane_value(pm, lo > 0 ? lo - 1 : 0);
+                    const int after = lane_value(sm, hi < kWave ? hi : 0);
+                    const int ob = lo > 0 ? before : kNegInfBits, oa = hi < kWave ? after : kNegInfBits;
+                    other = __fadd_rn(__int_as_float(ob > oa ? ob : oa), reach);
+                    fn = other;
+                    static_for<4>([&](auto k) {
+                        const float s0 = __fadd_rn(f[k.value].x, x[k.value].x), s1 = __fadd_rn(f[k.value].y, x[k.value].y);
+                        const float s2 = __fadd_rn(f[k.value].z, x[k.value].z), s3 = __fadd_rn(f[k.value].w, x[k.value].w);
+                        fn = __builtin_fmaxf(__builtin_fmaxf(fn, s0), s1);
+                        fn = __builtin_fmaxf(__builtin_fmaxf(fn, s2), s3);
+                    });
+                    for (int i0 = 4; i0 < n4; i0 += 4) {  // depth groups of more than 16 candidates
                         static_for<4>([&](auto k) {
                             const int i = i0 + k.value < n4 ? i0 + k.value : n4 - 1;
                             f[k.value] = f4[i];
@@ -343,52 +476,92 @@ __global__ void __launch_bounds__(512) plan_wave_kernel(
                         static_for<4>([&](auto k) {
                             const float s0 = __fadd_rn(f[k.value].x, x[k.value].x), s1 = __fadd_rn(f[k.value].y, x[k.value].y);
                             const float s2 = __fadd_rn(f[k.value].z, x[k.value].z), s3 = __fadd_rn(f[k.value].w, x[k.value].w);
-                            fn = __builtin_fmaxf(fn, __builtin_fmaxf(s0, s1));
-                            fn = __builtin_fmaxf(fn, __builtin_fmaxf(s2, s3));
+                            fn = __builtin_fmaxf(__builtin_fmaxf(fn, s0), s1);
+                            fn = __builtin_fmaxf(__builtin_fmaxf(fn, s2), s3);
                         });
                     }
                 }
+                const bool from_other = to && other == fn;
                 fn = to ? fn : kNegInf;
                 if (is_cand) {
                     w.fnew[ti * C + lane] = fn;
+                    w.oflag[ti * C + lane] = from_other ? 1u : 0u;
                     if (Fq) Fq[(int64_t)(t + 1) * C + lane] = fn;
                 }
                 Fcur = fn;
             }
+        } else if (t0 == 0 && n_waves > 1) {
+            check_inputs(tid < chain_first ? tid : tid - kWave, nthreads - kWave);
         }
         __syncthreads();
-        // phase C: back-pointers
-        for (int item = tid; item < n * C; item += nthreads) {
-            const int ti = item / C, c2 = item - ti * C;
+        // phase C: back-pointers.  The sources sit in slot order, which is candidate order, so the smallest matching
+        // slot is the smallest matching candidate; scans run downwards and keep the last match.
+        for (int item0 = 0; item0 < n * C; item0 += nthreads) {
+            const int item = item0 + tid;
+            const bool live = item < n * C;
+            const int it = live ? item : 0;
+            const int ti = fast_div(it, g.inv_C), c2 = it - ti * C;
             const int t = t0 + ti;
-            const float fn = w.fnew[ti * C + c2];
-            int arg = -1;
-            if (fn > kNegInf) {
-                if (t == 0 && cold) {
-                    arg = c2;
-                } else {
-                    const uint32_t sp = w.span[c2];
-                    const int lo = (int)(sp & 0xffu), hi = (int)((sp >> 8) & 0xffu);
-                    const float reach = w.R[c2];
-                    const float* frow = w.feff + ti * g.cpad;
-                    int best = kWaveMaxConfigs;
-                    // other depths, descending: the last match kept is the smallest
-                    for (int c = C - 1; c >= 0; --c) {
-                        const float v = __fadd_rn(frow[w.slot[c]], reach);
-                        if ((c < lo || c >= hi) && v == fn) best = c;
-                    }
-                    // same depth
-                    const float* fg = frow + (int)(sp >> 16);
-                    const float* wr = w.wsame + (ti * C + c2) * g.ws;
-                    int best_in = kWaveMaxConfigs;
-                    for (int i = hi - lo - 1; i >= 0; --i)
-                        if (__fadd_rn(fg[i], wr[i]) == fn) best_in = lo + i;
-                    best = best_in < best ? best_in : best;
-                    arg = best < kWaveMaxConfigs ? best : -1;
+            const float fn = w.fnew[it];
+            const bool reached = live && fn > kNegInf;
+            const bool cold_step = t == 0 && cold;
+            const uint32_t sp = w.span[c2];
+            const int gslot = (int)(sp >> 16);
+            const int gsize4 = round_up4((int)((sp >> 8) & 0xffu) - (int)(sp & 0xffu));
+            const float4* frow4 = reinterpret_cast<const float4*>(w.feff + ti * g.cpad);
+            int best = 0x7fffffff;
+            // other depths: only where the chain saw the new value come from another depth (rare after the first step)
+            const bool want_other = reached && !cold_step && w.oflag[it] != 0u;
+            if (__any(want_other)) {
+                const float reach = w.R[c2];
+                const int n_blocks = (g.cpad - g.gp) / 4;
+                for (int p0 = n_blocks - 1; p0 >= 0; p0 -= 4) {
+                    float4 f[4];
+                    static_for<4>([&](auto k) { f[k.value] = frow4[p0 - k.value >= 0 ? p0 - k.value : 0]; });
+                    static_for<4>([&](auto k) {
+                        const int p = (p0 - k.value >= 0 ? p0 - k.value : 0) * 4;
+                        const bool own = (unsigned)(p - gslot) < (unsigned)gsize4;  // blocks of four slots never straddle groups
+                        if (!own) {
+                            if (__fadd_rn(f[k.value].w, reach) == fn) best = p + 3;
+                            if (__fadd_rn(f[k.value].z, reach) == fn) best = p + 2;
+                            if (__fadd_rn(f[k.value].y, reach) == fn) best = p + 1;
+                            if (__fadd_rn(f[k.value].x, reach) == fn) best = p;
+                        }
+                    });
                 }
+                best = want_other ? best : 0x7fffffff;
             }
-            if (bpq) bpq[(int64_t)t * C + c2] = arg;
-            if (w.bp16) w.bp16[t * C + c2] = arg < 0 ? kNoPred16 : (uint16_t)arg;
+            // same depth
+            {
+                const float4* fg4 = frow4 + gslot / 4;
+                const float4* wr4 = reinterpret_cast<const float4*>(w.wsame + (ti * C + c2) * g.ws);
+                int best_in = 0x7fffffff;
+                for (int i0 = g.gp / 4 - 1; i0 >= 0; i0 -= 4) {
+                    float4 f[4], x[4];
+                    static_for<4>([&](auto k) {
+                        const int i = i0 - k.value >= 0 ? i0 - k.value : 0;
+                        f[k.value] = fg4[i];
+                        x[k.value] = wr4[i];
+                    });
+                    static_for<4>([&](auto k) {
+                        const int i = (i0 - k.value >= 0 ? i0 - k.value : 0) * 4;
+                        if (__fadd_rn(f[k.value].w, x[k.value].w) == fn) best_in = i + 3;
+                        if (__fadd_rn(f[k.value].z, x[k.value].z) == fn) best_in = i + 2;
+                        if (__fadd_rn(f[k.value].y, x[k.value].y) == fn) best_in = i + 1;
+                        if (__fadd_rn(f[k.value].x, x[k.value].x) == fn) best_in = i;
+                    });
+                }
+                if (best_in != 0x7fffffff && gslot + best_in < best) best = gslot + best_in;
+            }
+            int arg = -1;
+            if (reached) {
+                if (cold_step) arg = c2;
+                else if (best != 0x7fffffff) arg = (int)w.cand[best];
+            }
+            if (live) {
+                if (bpq) bpq[(int64_t)t * C + c2] = arg;
+                if (w.bp16) w.bp16[t * C + c2] = arg < 0 ? kNoPred16 : (uint16_t)arg;
+            }
         }
         __syncthreads();
     }
