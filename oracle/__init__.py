@@ -18,16 +18,30 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "parcae_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+_LIB_SANITIZED = os.path.join(_HERE, "liboracle_asan.so")
+SANITIZE_ENV = "PARCAE_ORACLE_SANITIZE"   # "1": load the build with AddressSanitizer and UndefinedBehaviorSanitizer
 _lib: Optional[ct.CDLL] = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (no fused multiply-add, OpenMP for the unit loop)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add, OpenMP for the unit loop).
+
+    sanitize=True builds liboracle_asan.so instead: the same source under -fsanitize=address,undefined (any
+    finding aborts).  A process that loads it must have gcc's libasan preloaded (see sanitizer_runtime())."""
+    out = _LIB_SANITIZED if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+                 if sanitize else ["-O2"])
+        cmd = ["gcc", "-std=c11", *flags, "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", out, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return out
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime, to be put first in LD_PRELOAD of a process that loads the sanitized build."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
 
 
 def _p(a: np.ndarray, ty):
@@ -37,8 +51,8 @@ def _p(a: np.ndarray, ty):
 def lib() -> ct.CDLL:
     global _lib
     if _lib is None:
-        build()
-        _lib = ct.CDLL(_LIB)
+        sanitized = os.environ.get(SANITIZE_ENV) == "1"
+        _lib = ct.CDLL(build(sanitize=sanitized))
         _lib.orc_word.restype = ct.c_uint32
         _lib.orc_word.argtypes = [ct.c_uint64, ct.c_uint32, ct.c_uint32, ct.c_uint32, ct.c_uint32]
         _lib.orc_word_at.restype = ct.c_uint32
@@ -129,8 +143,9 @@ def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int,
 
 
 def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1,
-              pool_all: bool = False, group: int = 1, zone=None, weight=None):
-    """Histograms [T][L] of one query over scenarios [s_begin, s_end)."""
+              pool_all: bool = False, group: int = 1, zone=None, weight=None, want=None):
+    """Histograms [T][L] of one query over scenarios [s_begin, s_end).  want: optional uint8 [T, C]; only the units
+    with a non-zero entry are evaluated, the rows of the others stay zero."""
     nz, zp, wp, _keep = _zones(zone, weight)
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -138,10 +153,12 @@ def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, 
     C, T, L = configs.shape[0], avail.shape[0] - 1, int(thr_off[-1])
     hi = np.zeros((T, L), dtype=np.uint32)
     hm = np.zeros((T, L), dtype=np.uint32)
-    lib().orc_eval_hist(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
-                        _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
-                        ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
-                        ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group), nz, zp, wp)
+    wanted = None if want is None else np.ascontiguousarray(want, dtype=np.uint8).reshape(T * C)
+    lib().orc_eval_hist_some(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
+                             _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
+                             ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
+                             ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group), nz, zp, wp,
+                             None if wanted is None else _p(wanted, ct.c_uint8))
     return hi, hm
 
 

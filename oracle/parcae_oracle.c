@@ -304,10 +304,26 @@ void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, int n_zones,
  * draws the preemptions among all avail[t] instances instead of the used ones.
  * n_zones > 0: zone[N] and weight[n_zones] select the non-uniform draw.
  */
+void orc_eval_hist_some(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
+                        uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
+                        uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
+                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want);
+
 void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                    uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
                    uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
                    int n_zones, const uint8_t *zone, const uint32_t *weight)
+{
+    orc_eval_hist_some(T, C, configs, thr_off, avail, seed, stream_id, s_begin, s_end, hist_int, hist_min, n_threads,
+                       pool_all, group, n_zones, zone, weight, NULL);
+}
+
+/* The same for the units (t, c) with want[t * C + c] != 0 only (all units if want is NULL); the rows of the other
+ * units are left at zero.  For checks that cover the units without preemption by their known single bin. */
+void orc_eval_hist_some(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
+                        uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
+                        uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
+                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want)
 {
     const int L = thr_off[C];
     memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
@@ -317,6 +333,7 @@ void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off,
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads > 0 ? n_threads : 1)
 #endif
     for (int u = 0; u < T * C; ++u) {
+        if (want && !want[u]) continue;
         int t = u / C, c = u % C;
         int D = configs[2 * c], P = configs[2 * c + 1];
         int M, k;

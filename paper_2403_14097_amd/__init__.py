@@ -16,6 +16,8 @@ from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libparcae_hip.so")
+if os.environ.get("PARCAE_HOST_SANITIZE") == "1":   # host code under the sanitizers (see build.build_host_sanitized)
+    LIB_PATH = os.path.join(_HERE, "libparcae_hip_asan.so")
 
 PARCAE_OK = 0
 PARCAE_EINVAL = -1

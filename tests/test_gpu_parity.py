@@ -133,7 +133,7 @@ def test_full_workload_parity(pk, name):
 
 
 @pytest.mark.parametrize("name,S,dense", [("medium", 1500, False), ("medium", 777, True), ("large", 640, False),
-                                          ("large", 200, True)])
+                                          ("large", 200, True), ("large", 4096, False)])
 def test_prefix_parity_on_larger_workloads(pk, name, S, dense):
     """Scenario s does not depend on the scenario count, so a prefix of a big workload is a full parity case.
     S values are ragged (not multiples of the wave or block size)."""
@@ -303,6 +303,60 @@ def test_full_size_sweep_sampled(pk):
         _plan_check_from_gpu_histograms(pk, b, int(q), ev, pl)
     for q in (0, 1023):
         _check_query_against_oracle(pk, b, q, ev, pl, b.n_scenarios)
+
+
+def _closed_form_rows(b, q, k, S):
+    """Histogram [T, L] of query q holding only the units whose scenarios are all alike by the definition of the
+    draw: nothing preempted (k = 0: every pipeline intact, bin D) or everything preempted (k = M: bin 0)."""
+    T, L = b.n_intervals, b.hist_len
+    out = np.zeros((T, L), np.uint32)
+    used = b.configs[:, 0] * b.configs[:, 1]
+    for c in range(b.n_configs):
+        none = k[q, :, c] == 0
+        out[none, b.thr_off[c] + b.configs[c, 0]] = S
+        out[k[q, :, c] == used[c], b.thr_off[c]] = S
+    return out
+
+
+def test_full_size_sweep_every_unit_of_every_query(pk):
+    """The 1024-query sweep in the benchmark's launch configuration, whole: both histograms of every unit of every
+    query against the oracle (units that the definition makes trivial, k = 0 or k = M by the oracle's own pool
+    rule, against their single bin; every other unit sampled by the oracle, also those the library writes in
+    closed form), then tables, value function, back-pointers and plan of every query."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    b = pi.workload("sweep")
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    S, nq = b.n_scenarios, b.n_queries
+    hi_all, hm_all = _np(ev.hist_int, np.uint32), _np(ev.hist_min, np.uint32)
+    used = b.configs[:, 0] * b.configs[:, 1]
+    k = np.maximum(0, used[None, None, :] - b.avail[:, 1:, None])          # pool of used instances (section 4.2)
+    want = ((k > 0) & (k < used[None, None, :])).astype(np.uint8)
+    assert 0.3 < want.mean() < 0.5
+
+    def check(q):
+        oi, om = oracle.eval_hist(b.configs, b.thr_off, b.avail[q], int(b.seed[q]), int(b.stream_id[q]), 0, S, 1,
+                                  want=want[q])
+        easy = _closed_form_rows(b, q, k, S)
+        return bool(np.array_equal(hi_all[q], oi + easy) and np.array_equal(hm_all[q], om + easy))
+
+    workers = max(1, min(16, os.cpu_count() or 1))
+    with ThreadPoolExecutor(workers) as pool:          # the C oracle runs outside the interpreter lock
+        ok = list(pool.map(check, range(nq)))
+    assert all(ok), [q for q, good in enumerate(ok) if not good][:10]
+    assert np.all(_np(pl.status) == 0)
+
+    def check_plan(q):
+        _plan_check_from_gpu_histograms(pk, b, q, ev, pl)
+        return True
+
+    ev_np = type(ev)(*[None if t is None else t.cpu() for t in (ev.hist_int, ev.hist_min, ev.liveput, ev.teff, ev.gain, ev.status)])
+    pl_np = type(pl)(*[None if t is None else t.cpu() for t in (pl.F, pl.bp, pl.plan, pl.start, pl.objective, pl.status)])
+    ev, pl = ev_np, pl_np                               # host copies: the per-query checks slice them 1024 times
+    with ThreadPoolExecutor(workers) as pool:
+        assert all(pool.map(check_plan, range(nq)))
 
 
 # ------------------------------------------------------------------ whole-cluster preemption pool
@@ -656,7 +710,7 @@ def test_random_problems_match_the_oracle(pk):
         _sync()
         tag = (case, b.n_instances, b.n_configs, b.n_queries, b.n_intervals, b.n_scenarios, b.group_size, b.n_zones,
                b.cost_round is not None, pool_all)
-        for q in sorted({0, b.n_queries - 1}):
+        for q in range(b.n_queries):
             r = oracle.run_query(b, q, n_threads=8, pool_all=pool_all)
             assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int), tag
             assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min), tag
