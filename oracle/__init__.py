@@ -83,12 +83,25 @@ def sample_preempted(M: int, k: int, seed: int, stream_id: int, unit: int, s: in
 
 
 def _zones(zone, weight):
-    """(n_zones, zone pointer, weight pointer, keep-alive arrays) for the C calls; uniform when zone is None."""
+    """(n_zones, zone pointer, weight pointer, keep-alive arrays) for the C calls; uniform when zone is None.
+    weight == "instances": `zone` holds a hazard weight per instance (n_zones = -1 in the C calls)."""
     if zone is None:
         return ct.c_int(0), None, None, ()
     z = np.ascontiguousarray(zone, dtype=np.uint8)
+    if isinstance(weight, str) and weight == "instances":
+        return ct.c_int(-1), _p(z, ct.c_uint8), None, (z,)
     w = np.ascontiguousarray(weight, dtype=np.uint32)
     return ct.c_int(int(w.size)), _p(z, ct.c_uint8), _p(w, ct.c_uint32), (z, w)
+
+
+def sample_preempted_weighted(M: int, k: int, weight, seed: int, stream_id: int, unit: int, s: int) -> np.ndarray:
+    """Successive weighted sampling without replacement with a hazard weight (1..255) per instance."""
+    out = np.zeros(M, dtype=np.uint8)
+    w = np.ascontiguousarray(weight, dtype=np.uint8)
+    assert w.size >= M and (M == 0 or w[:M].min() >= 1)
+    lib().orc_sample_preempted_weighted(ct.c_int(M), ct.c_int(k), _p(w, ct.c_uint8), ct.c_uint64(seed),
+                                        ct.c_uint32(stream_id), ct.c_uint32(unit), ct.c_uint32(s), _p(out, ct.c_uint8))
+    return out
 
 
 def word_at(seed: int, stream_id: int, unit: int, s: int, prefix: int, i: int) -> int:
@@ -129,23 +142,26 @@ def debug_sample(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: i
 
 
 def eval_unit(D: int, P: int, a_next: int, seed: int, stream_id: int, unit: int, s_begin: int, s_end: int,
-              a_prev: int = -1, group: int = 1, zone=None, weight=None):
-    """Histograms [D + 1] of one unit (unit = t * C + c) over scenarios [s_begin, s_end)."""
+              a_prev: int = -1, group: int = 1, zone=None, weight=None, with_occ: bool = False):
+    """Histograms [D + 1] of one unit (unit = t * C + c) over scenarios [s_begin, s_end); with_occ adds the
+    stage-occupancy statistic as a third array."""
     hi = np.zeros(D + 1, dtype=np.uint32)
     hm = np.zeros(D + 1, dtype=np.uint32)
+    ho = np.zeros(D + 1, dtype=np.uint32) if with_occ else None
     nz, zp, wp, _keep = _zones(zone, weight)
     lib().orc_eval_unit(ct.c_int(D), ct.c_int(P), ct.c_int(group), ct.c_int(a_prev), ct.c_int(a_next), nz, zp, wp,
                         ct.c_uint64(seed),
                         ct.c_uint32(stream_id),
                         ct.c_uint32(unit), ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32),
-                        _p(hm, ct.c_uint32))
-    return hi, hm
+                        _p(hm, ct.c_uint32), None if ho is None else _p(ho, ct.c_uint32))
+    return (hi, hm, ho) if with_occ else (hi, hm)
 
 
 def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, s_end: int, n_threads: int = 1,
-              pool_all: bool = False, group: int = 1, zone=None, weight=None, want=None):
+              pool_all: bool = False, group: int = 1, zone=None, weight=None, want=None, with_occ: bool = False):
     """Histograms [T][L] of one query over scenarios [s_begin, s_end).  want: optional uint8 [T, C]; only the units
-    with a non-zero entry are evaluated, the rows of the others stay zero."""
+    with a non-zero entry are evaluated, the rows of the others stay zero.  with_occ adds the stage-occupancy
+    statistic as a third array."""
     nz, zp, wp, _keep = _zones(zone, weight)
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -153,13 +169,15 @@ def eval_hist(configs, thr_off, avail, seed: int, stream_id: int, s_begin: int, 
     C, T, L = configs.shape[0], avail.shape[0] - 1, int(thr_off[-1])
     hi = np.zeros((T, L), dtype=np.uint32)
     hm = np.zeros((T, L), dtype=np.uint32)
+    ho = np.zeros((T, L), dtype=np.uint32) if with_occ else None
     wanted = None if want is None else np.ascontiguousarray(want, dtype=np.uint8).reshape(T * C)
     lib().orc_eval_hist_some(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                              _p(avail, ct.c_int32), ct.c_uint64(seed), ct.c_uint32(stream_id),
                              ct.c_uint32(s_begin), ct.c_uint32(s_end), _p(hi, ct.c_uint32), _p(hm, ct.c_uint32),
                              ct.c_int(n_threads), ct.c_int(1 if pool_all else 0), ct.c_int(group), nz, zp, wp,
-                             None if wanted is None else _p(wanted, ct.c_uint8))
-    return hi, hm
+                             None if wanted is None else _p(wanted, ct.c_uint8),
+                             None if ho is None else _p(ho, ct.c_uint32))
+    return (hi, hm, ho) if with_occ else (hi, hm)
 
 
 @dataclass
@@ -179,8 +197,16 @@ def _rounds(cost_round):
     return _p(r, ct.c_float), r
 
 
+def _moves(cost_move, hist_occ):
+    if cost_move is None:
+        return None, None, ()
+    m = np.ascontiguousarray(cost_move, dtype=np.float32)
+    o = np.ascontiguousarray(hist_occ, dtype=np.uint32)
+    return _p(m, ct.c_float), _p(o, ct.c_uint32), (m, o)
+
+
 def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, hist_min,
-             pool_all: bool = False, group: int = 1, cost_round=None) -> Tables:
+             pool_all: bool = False, group: int = 1, cost_round=None, cost_move=None, hist_occ=None) -> Tables:
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
     avail = np.ascontiguousarray(avail, dtype=np.int32)
@@ -192,16 +218,17 @@ def finalise(configs, thr_off, avail, thr, cost, tau: float, S: int, hist_int, h
     out = Tables(np.zeros((3, T, C)), np.zeros((T, C)), np.zeros((T, C)),
                  np.zeros((3, T, C), np.float32), np.zeros((T, C), np.float32), np.zeros((T, C), np.float32))
     rp, _keep = _rounds(cost_round)
+    mp, op, _keep2 = _moves(cost_move, hist_occ)
     lib().orc_finalise(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                        _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), rp, ct.c_float(tau),
                        ct.c_uint32(S), ct.c_int(1 if pool_all else 0), ct.c_int(group), _p(hi, ct.c_uint32),
                        _p(hm, ct.c_uint32), _p(out.liveput_d, ct.c_double), _p(out.teff_d, ct.c_double), _p(out.gain_d, ct.c_double),
-                       _p(out.liveput_f, ct.c_float), _p(out.teff_f, ct.c_float), _p(out.gain_f, ct.c_float))
+                       _p(out.liveput_f, ct.c_float), _p(out.teff_f, ct.c_float), _p(out.gain_f, ct.c_float), mp, op)
     return out
 
 
 def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: int, cur_config: int,
-               hist_int, hist_min, group: int = 1, cost_round=None):
+               hist_int, hist_min, group: int = 1, cost_round=None, cost_move=None, hist_occ=None):
     """W[T][C][C] in double and in fixed-order float."""
     configs = np.ascontiguousarray(configs, dtype=np.int32)
     thr_off = np.ascontiguousarray(thr_off, dtype=np.int32)
@@ -214,10 +241,11 @@ def transition(configs, thr_off, avail, thr, cost, tau: float, S: int, p_min: in
     W_d = np.zeros((T, C, C), dtype=np.float64)
     W_f = np.zeros((T, C, C), dtype=np.float32)
     rp, _keep = _rounds(cost_round)
+    mp, op, _keep2 = _moves(cost_move, hist_occ)
     lib().orc_transition(ct.c_int(T), ct.c_int(C), _p(configs, ct.c_int32), _p(thr_off, ct.c_int32),
                          _p(avail, ct.c_int32), _p(thr, ct.c_float), _p(cost, ct.c_float), rp, ct.c_float(tau),
                          ct.c_uint32(S), ct.c_int(p_min), ct.c_int(cur_config), ct.c_int(group),
-                         _p(hi, ct.c_uint32), _p(hm, ct.c_uint32), _p(W_d, ct.c_double), _p(W_f, ct.c_float))
+                         _p(hi, ct.c_uint32), _p(hm, ct.c_uint32), _p(W_d, ct.c_double), _p(W_f, ct.c_float), mp, op)
     return W_d, W_f
 
 
@@ -264,14 +292,25 @@ class QueryResult:
     W_f: np.ndarray
     plan: Plan
     objective_d: float
+    hist_occ: Optional[np.ndarray] = None
 
 
 def batch_zones(batch, q: int):
-    """(zone[N], weight[n_zones]) of query q, or (None, None) when the batch draws uniformly."""
+    """(zone[N], weight[n_zones]) of query q, (weight per instance [N], "instances") when the batch carries
+    per-instance hazard weights, or (None, None) when it draws uniformly."""
+    per_instance = getattr(batch, "inst_weight", None)
+    if per_instance is not None:
+        return per_instance[q], "instances"
     zone = getattr(batch, "zone", None)
     if zone is None:
         return None, None
     return zone[q], batch.zone_weight[q][: int(batch.n_zones)]
+
+
+def batch_moves(batch, q: int):
+    """cost_move[C] of query q, or None."""
+    m = getattr(batch, "cost_move", None)
+    return None if m is None else m[q]
 
 
 def batch_rounds(batch, q: int):
@@ -286,13 +325,16 @@ def run_query(batch, q: int, n_scenarios: Optional[int] = None, n_threads: int =
     group = int(getattr(batch, "group_size", 1))
     S = batch.n_scenarios if n_scenarios is None else int(n_scenarios)
     zone, weight = batch_zones(batch, q)
-    hi, hm = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
-                       0, S, n_threads, pool_all, group, zone, weight)
+    moves = batch_moves(batch, q)
+    hists = eval_hist(batch.configs, batch.thr_off, batch.avail[q], int(batch.seed[q]), int(batch.stream_id[q]),
+                      0, S, n_threads, pool_all, group, zone, weight, with_occ=moves is not None)
+    hi, hm = hists[0], hists[1]
+    ho = hists[2] if moves is not None else None
     rounds = batch_rounds(batch, q)
     tab = finalise(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                   batch.interval_sec, S, hi, hm, pool_all, group, rounds)
+                   batch.interval_sec, S, hi, hm, pool_all, group, rounds, moves, ho)
     if not want_plan:
-        return QueryResult(hi, hm, tab, None, None, None, float("nan"))
+        return QueryResult(hi, hm, tab, None, None, None, float("nan"), ho)
     W_d, W_f = transition(batch.configs, batch.thr_off, batch.avail[q], batch.thr[q], batch.cost[q],
-                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm, group, rounds)
-    return QueryResult(hi, hm, tab, W_d, W_f, dp_f32(W_f), dp_f64(W_d))
+                          batch.interval_sec, S, batch.p_min, int(batch.cur_config[q]), hi, hm, group, rounds, moves, ho)
+    return QueryResult(hi, hm, tab, W_d, W_f, dp_f32(W_f), dp_f64(W_d), ho)

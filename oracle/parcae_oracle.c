@@ -24,9 +24,10 @@
  *   word i is output lane i mod 4.
  *   Subset: R. Floyd's sampling (Bentley & Floyd, CACM 1987) of the smaller
  *   of the preempted / surviving sets, bounded integers by multiply-shift.
- *   Non-uniform preemption (optional): zones with integer hazard weights,
- *   successive weighted sampling without replacement, see
- *   orc_sample_preempted_zoned.
+ *   Non-uniform preemption (optional): integer hazard weights per instance
+ *   (orc_sample_preempted_weighted) or per zone of instances
+ *   (orc_sample_preempted_zoned), successive weighted sampling without
+ *   replacement in both cases.
  *
  * Precision: every floating-point result is produced twice, in double
  * (the reference value) and in float with one fixed operation order and no
@@ -172,6 +173,33 @@ void orc_sample_preempted_zoned(int M, int k, int n_zones, const uint8_t *zone, 
     }
 }
 
+/*
+ * Preempted set when every instance has its own hazard weight (section 5.1: the equal-probability assumption can be
+ * replaced by more accurate estimations when the provider tells more about preemptions).  weight[j] in [1, 255] for
+ * the instances j < M of the pool.  The k preempted instances leave one after the other; each time one of the
+ * instances still there goes, with probability proportional to its weight (successive weighted sampling without
+ * replacement).  Draw i uses word i of sequence 0xFFFE: total = sum of the weights still there,
+ * r = (word * total) >> 32 in [0, total), and the instance that goes is the first one, in ascending order, at which
+ * the running sum of the weights still there exceeds r.  Exactly k words; no complement trick (the survivors of
+ * such a process are not distributed like its victims).
+ */
+void orc_sample_preempted_weighted(int M, int k, const uint8_t *weight, uint64_t seed, uint32_t stream_id,
+                                   uint32_t unit, uint32_t s, uint8_t *preempted)
+{
+    memset(preempted, 0, (size_t)M);
+    for (int i = 0; i < k; ++i) {
+        uint32_t total = 0u, running = 0u;
+        for (int j = 0; j < M; ++j) if (!preempted[j]) total += weight[j];
+        uint32_t w = orc_word_at(seed, stream_id, unit, s, 0xFFFEu, (uint32_t)i);
+        uint32_t r = (uint32_t)(((uint64_t)w * (uint64_t)total) >> 32);
+        for (int j = 0; j < M; ++j) {
+            if (preempted[j]) continue;
+            running += weight[j];
+            if (r < running) { preempted[j] = 1; break; }
+        }
+    }
+}
+
 /* ---------------------------------------------------------------- reducer */
 
 /*
@@ -230,22 +258,37 @@ void orc_expand_groups(int D, int P, int group, const uint8_t *instance_preempte
     }
 }
 
-/* One scenario of a unit: which instances of the pool go (pool_pre[M]) and what is left of the D x P grid. */
+/* One scenario of a unit: which instances of the pool go (pool_pre[M]) and what is left of the D x P grid
+ * (occ[P], the survivors of every stage, may be NULL).  n_zones < 0 says that `zone` holds a hazard weight per
+ * instance instead of a zone index (and `weight` is unused). */
 static void scenario(int D, int P, int group, int M, int k, int n_zones, const uint8_t *zone,
                      const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
-                     uint32_t s, uint8_t *pool_pre, int *n_int, int *d_min)
+                     uint32_t s, uint8_t *pool_pre, int *n_int, int *d_min, int *occ)
 {
-    if (n_zones > 0 && zone && weight)
+    if (n_zones < 0 && zone)
+        orc_sample_preempted_weighted(M, k, zone, seed, stream_id, unit, s, pool_pre);
+    else if (n_zones > 0 && zone && weight)
         orc_sample_preempted_zoned(M, k, n_zones, zone, weight, seed, stream_id, unit, s, pool_pre);
     else
         orc_sample_preempted(M, k, seed, stream_id, unit, s, pool_pre);
     if (group <= 1) {
-        orc_reduce(D, P, pool_pre, n_int, d_min, NULL);
+        orc_reduce(D, P, pool_pre, n_int, d_min, occ);
     } else {
         uint8_t gpu[ORC_MAX_INSTANCES * ORC_MAX_GROUP];
         orc_expand_groups(D, P, group, pool_pre, gpu);
-        orc_reduce(D, P, gpu, n_int, d_min, NULL);
+        orc_reduce(D, P, gpu, n_int, d_min, occ);
     }
+}
+
+/* Stage-occupancy statistic of one scenario into bins_occ[D + 1]: bins_occ[j] += number of stages with exactly j
+ * survivors, for scenarios in which every stage still has one (d_min >= 1: the scenarios that live migration can
+ * serve; a lost stage means a rollback, section 7).  From it the number of instances that must receive the state
+ * of a stage to bring every stage to w holders, sum over stages of max(0, w - occ_s), follows for every w at once:
+ * summed over the scenarios it is the sum over j < w of bins_occ[j] * (w - j). */
+static void count_stage_occupancy(int P, int d_min, const int *occ, uint32_t *bins_occ)
+{
+    if (d_min < 1) return;
+    for (int s = 0; s < P; ++s) bins_occ[occ[s]] += 1u;
 }
 
 /*
@@ -254,7 +297,8 @@ static void scenario(int D, int P, int group, int M, int k, int n_zones, const u
  * instances D*P and up are idle ones) and the two per-scenario integers.
  * a_prev < 0 selects the used-instance pool.  With group > 1 the mask is over instances
  * of `group` GPUs each, n_int and d_min count GPU pipelines.  n_zones > 0 with zone[] (zone of every
- * instance of the pool) and weight[] draws by orc_sample_preempted_zoned, otherwise uniformly.
+ * instance of the pool) and weight[] draws by orc_sample_preempted_zoned; n_zones < 0 with zone[] holding a
+ * hazard weight per instance draws by orc_sample_preempted_weighted; otherwise uniformly.
  */
 void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, int n_zones, const uint8_t *zone,
                       const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
@@ -265,7 +309,7 @@ void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, int n_zon
     unit_pool(D, P, group, a_prev, a_next, &M, &k);
     for (uint32_t x = 0; x < ns; ++x) {
         int ni, dm;
-        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s0 + x, pre, &ni, &dm);
+        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s0 + x, pre, &ni, &dm, NULL);
         for (int w = 0; w < 8; ++w) masks[x * 8u + (uint32_t)w] = 0u;
         for (int j = 0; j < M; ++j)
             if (pre[j]) masks[x * 8u + (uint32_t)(j / 32)] |= (1u << (j % 32));
@@ -275,23 +319,26 @@ void orc_debug_sample(int D, int P, int group, int a_prev, int a_next, int n_zon
 }
 
 /*
- * Histograms of a single unit over scenarios [s_begin, s_end): bins [D + 1] each, overwritten.
+ * Histograms of a single unit over scenarios [s_begin, s_end): bins [D + 1] each, overwritten
+ * (bins_occ, the stage-occupancy statistic, may be NULL).
  * a_prev < 0 selects the used-instance pool.
  * unit = t * C + c is the value that enters the random-word counter.
  */
 void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, int n_zones, const uint8_t *zone,
                    const uint32_t *weight, uint64_t seed, uint32_t stream_id, uint32_t unit,
-                   uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min)
+                   uint32_t s_begin, uint32_t s_end, uint32_t *bins_int, uint32_t *bins_min, uint32_t *bins_occ)
 {
     uint8_t pre[ORC_MAX_INSTANCES];
+    int occ[ORC_MAX_INSTANCES];
     int M, k;
     unit_pool(D, P, group, a_prev, a_next, &M, &k);
-    for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; }
+    for (int j = 0; j <= D; ++j) { bins_int[j] = 0u; bins_min[j] = 0u; if (bins_occ) bins_occ[j] = 0u; }
     for (uint32_t s = s_begin; s < s_end; ++s) {
         int ni, dm;
-        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s, pre, &ni, &dm);
+        scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, unit, s, pre, &ni, &dm, occ);
         bins_int[ni] += 1u;
         bins_min[dm] += 1u;
+        if (bins_occ) count_stage_occupancy(P, dm, occ, bins_occ);
     }
 }
 
@@ -307,7 +354,8 @@ void orc_eval_unit(int D, int P, int group, int a_prev, int a_next, int n_zones,
 void orc_eval_hist_some(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                         uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
                         uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
-                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want);
+                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want,
+                        uint32_t *hist_occ);
 
 void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                    uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
@@ -315,19 +363,23 @@ void orc_eval_hist(int T, int C, const int32_t *configs, const int32_t *thr_off,
                    int n_zones, const uint8_t *zone, const uint32_t *weight)
 {
     orc_eval_hist_some(T, C, configs, thr_off, avail, seed, stream_id, s_begin, s_end, hist_int, hist_min, n_threads,
-                       pool_all, group, n_zones, zone, weight, NULL);
+                       pool_all, group, n_zones, zone, weight, NULL, NULL);
 }
 
 /* The same for the units (t, c) with want[t * C + c] != 0 only (all units if want is NULL); the rows of the other
- * units are left at zero.  For checks that cover the units without preemption by their known single bin. */
+ * units are left at zero.  For checks that cover the units without preemption by their known single bin.
+ * hist_occ ([T][off[C]], may be NULL): the stage-occupancy statistic, hist_occ[t][off[c] + j] = stages with j
+ * survivors summed over the scenarios that lost no whole stage (see count_stage_occupancy). */
 void orc_eval_hist_some(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                         uint64_t seed, uint32_t stream_id, uint32_t s_begin, uint32_t s_end,
                         uint32_t *hist_int, uint32_t *hist_min, int n_threads, int pool_all, int group,
-                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want)
+                        int n_zones, const uint8_t *zone, const uint32_t *weight, const uint8_t *want,
+                        uint32_t *hist_occ)
 {
     const int L = thr_off[C];
     memset(hist_int, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
     memset(hist_min, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
+    if (hist_occ) memset(hist_occ, 0, sizeof(uint32_t) * (size_t)T * (size_t)L);
     (void)n_threads;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads > 0 ? n_threads : 1)
@@ -338,14 +390,17 @@ void orc_eval_hist_some(int T, int C, const int32_t *configs, const int32_t *thr
         int D = configs[2 * c], P = configs[2 * c + 1];
         int M, k;
         uint8_t pre[ORC_MAX_INSTANCES];
+        int occ[ORC_MAX_INSTANCES];
         unit_pool(D, P, group, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
         uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
         uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+        uint32_t *ho = hist_occ ? hist_occ + (size_t)t * L + thr_off[c] : NULL;
         for (uint32_t s = s_begin; s < s_end; ++s) {
             int ni, dm;
-            scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, (uint32_t)u, s, pre, &ni, &dm);
+            scenario(D, P, group, M, k, n_zones, zone, weight, seed, stream_id, (uint32_t)u, s, pre, &ni, &dm, occ);
             hi[ni] += 1u;
             hm[dm] += 1u;
+            if (ho) count_stage_occupancy(P, dm, occ, ho);
         }
     }
 }
@@ -386,9 +441,20 @@ static void class_counts(const uint32_t *hi, const uint32_t *hm, int D, int widt
  * co[1] + round_sec * (r - 1), capped by the re-partition cost co[2] (one can always re-partition instead).
  * Float order: ((n0 * tau + n1 * e_intra) + inter) + n3 * e_repartition, inter = sum over r = 1..8 ascending of
  * (float)count_r * e_r, each product and sum rounded separately; one division by S.
+ *
+ * move_sec > 0 (section 8.4 again, the other reading of "varies according to the preemptions": the transfer cost
+ * grows with the number of instances that must receive state; alpha-beta with alpha = co[1], beta = move_sec): an
+ * inter-stage migration of a scenario to `width` costs co[1] + move_sec * moves, moves = sum over stages of
+ * max(0, width - survivors of the stage).  The caller guarantees co[1] + move_sec * (width - 1) * P <= min(tau, co[2])
+ * (the dearest inter-stage migration still beats a re-partition and fits the interval), so no cap and no clamp ever
+ * binds and the expectation is linear in the move counts: with ho = the stage-occupancy statistic of the unit,
+ * total_moves = sum over 1 <= j < width, j <= D of ho[j] * (width - j) over all its scenarios (scenarios that need no
+ * inter-stage migration contribute none), inter = n2 * e_inter - move_sec * total_moves.
+ * Float: inter = (float)n2 * e_inter - move_sec * (float)total_moves (64-bit count, each operation rounded).
+ * At most one of round_sec and move_sec may be non-zero.
  */
-static void effective_seconds(const uint32_t *hi, const uint32_t *hm, int D, int width, uint32_t S, float tau,
-                              const float *co, float round_sec, double *out_d, float *out_f)
+static void effective_seconds(const uint32_t *hi, const uint32_t *hm, const uint32_t *ho, int D, int width, uint32_t S,
+                              float tau, const float *co, float round_sec, float move_sec, double *out_d, float *out_f)
 {
     uint32_t n[4];
     class_counts(hi, hm, D, width, S, n);
@@ -400,7 +466,14 @@ static void effective_seconds(const uint32_t *hi, const uint32_t *hm, int D, int
     }
     double inter_d;
     float inter_f;
-    if (round_sec == 0.0f) {
+    if (move_sec != 0.0f && ho) {
+        uint64_t total_moves = 0;
+        for (int j = 1; j <= D && j < width; ++j) total_moves += (uint64_t)ho[j] * (uint64_t)(width - j);
+        inter_d = (double)n[2] * e_d[1] - (double)move_sec * (double)total_moves;
+        float fixed = (float)n[2] * e_f[1];
+        float moved = move_sec * (float)total_moves;
+        inter_f = fixed - moved;
+    } else if (round_sec == 0.0f) {
         inter_d = (double)n[2] * e_d[1];
         inter_f = (float)n[2] * e_f[1];
     } else {
@@ -441,6 +514,8 @@ static void effective_seconds(const uint32_t *hi, const uint32_t *hm, int D, int
  * boundary; gain = throughput after migration times teff.
  * cost_round: [C] seconds per further state-transfer round of an inter-stage
  * migration into each configuration, or NULL (see effective_seconds).
+ * cost_move with hist_occ: [C] seconds per instance that must receive state, and
+ * the stage-occupancy statistic [T][off[C]]; or both NULL.
  * Outputs: liveput [3][T][C], teff [T][C], gain [T][C], each in double (*_d)
  * and in the fixed float order (*_f).
  */
@@ -448,7 +523,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
                   const float *thr, const float *cost, const float *cost_round, float tau, uint32_t S, int pool_all,
                   int group, const uint32_t *hist_int, const uint32_t *hist_min,
                   double *liveput_d, double *teff_d, double *gain_d,
-                  float *liveput_f, float *teff_f, float *gain_f)
+                  float *liveput_f, float *teff_f, float *gain_f, const float *cost_move, const uint32_t *hist_occ)
 {
     const int L = thr_off[C];
     for (int t = 0; t < T; ++t) {
@@ -458,6 +533,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
             unit_pool(D, P, group, pool_all ? avail[t] : -1, avail[t + 1], &M, &k);
             const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
             const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+            const uint32_t *ho = hist_occ ? hist_occ + (size_t)t * L + thr_off[c] : NULL;
             const float *th = thr + thr_off[c];
             const float *co = cost + 3 * c;
 
@@ -483,7 +559,8 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
 
             double td;
             float tf;
-            effective_seconds(hi, hm, D, d_star, S, tau, co, cost_round ? cost_round[c] : 0.0f, &td, &tf);
+            effective_seconds(hi, hm, ho, D, d_star, S, tau, co, cost_round ? cost_round[c] : 0.0f,
+                              cost_move ? cost_move[c] : 0.0f, &td, &tf);
             teff_d[o] = td;
             teff_f[o] = tf;
             gain_d[o] = (double)th[d_star] * td;
@@ -509,7 +586,7 @@ void orc_finalise(int T, int C, const int32_t *configs, const int32_t *thr_off, 
 void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off, const int32_t *avail,
                     const float *thr, const float *cost, const float *cost_round, float tau, uint32_t S, int p_min,
                     int cur_config, int group, const uint32_t *hist_int, const uint32_t *hist_min, double *W_d,
-                    float *W_f)
+                    float *W_f, const float *cost_move, const uint32_t *hist_occ)
 {
     const int L = thr_off[C];
     for (int t = 0; t < T; ++t) {
@@ -519,6 +596,7 @@ void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off
             int from_ok = (D * P <= gpus * avail[t]) && (P >= p_min) && (t > 0 || cur_config < 0 || c == cur_config);
             const uint32_t *hi = hist_int + (size_t)t * L + thr_off[c];
             const uint32_t *hm = hist_min + (size_t)t * L + thr_off[c];
+            const uint32_t *ho = hist_occ ? hist_occ + (size_t)t * L + thr_off[c] : NULL;
             for (int c2 = 0; c2 < C; ++c2) {
                 int D2 = configs[2 * c2], P2 = configs[2 * c2 + 1];
                 int to_ok = (D2 * P2 <= gpus * avail[t + 1]) && (P2 >= p_min);
@@ -550,7 +628,8 @@ void orc_transition(int T, int C, const int32_t *configs, const int32_t *thr_off
                 /* a target wider than the source (D2 > D) sums over no bins: nothing is kept or re-routed */
                 double td;
                 float tf;
-                effective_seconds(hi, hm, D, D2, S, tau, co, cost_round ? cost_round[c2] : 0.0f, &td, &tf);
+                effective_seconds(hi, hm, ho, D, D2, S, tau, co, cost_round ? cost_round[c2] : 0.0f,
+                                  cost_move ? cost_move[c2] : 0.0f, &td, &tf);
                 W_d[o] = (double)full * td;
                 W_f[o] = full * tf;
             }

@@ -131,6 +131,7 @@ def replay(batch, q, true_avail, windows, mode=PROACTIVE, n_threads=1, pool_all=
     H = len(windows)
     zone, weight = batch_zones(batch, q)
     rounds = batch_rounds(batch, q)
+    assert getattr(batch, "cost_move", None) is None, "the replay does not take a cost per moved instance"
     cur = int(batch.cur_config[q])
     chosen = np.zeros(H, np.int32)
     reward = np.zeros(H, np.float32)

@@ -101,6 +101,9 @@ class ProblemBatch:
     n_zones > 0: preemption is not uniform; zone uint8 [nq, N] is the zone of every instance,
     zone_weight uint32 [nq, 4] the hazard weight of every zone (entries at and above n_zones unused).
     cost_round float32 [nq, C] (optional): seconds per further state-transfer round of an inter-stage migration.
+    inst_weight uint8 [nq, N] (optional): hazard weight (1..255) of every instance, for preemption that is not
+    uniform instance by instance.
+    cost_move float32 [nq, C] (optional): seconds per instance that must receive state in an inter-stage migration.
     """
 
     name: str
@@ -123,6 +126,8 @@ class ProblemBatch:
     zone: np.ndarray | None = None
     zone_weight: np.ndarray | None = None
     cost_round: np.ndarray | None = None   # float32 [nq, C] seconds per further state-transfer round, or None
+    inst_weight: np.ndarray | None = None  # uint8 [nq, N] hazard weight of every instance, or None
+    cost_move: np.ndarray | None = None    # float32 [nq, C] seconds per instance that must receive state, or None
 
     @property
     def n_queries(self) -> int:
@@ -148,7 +153,9 @@ class ProblemBatch:
             dict(self.meta), self.group_size, self.n_zones,
             None if self.zone is None else np.ascontiguousarray(self.zone[idx]),
             None if self.zone_weight is None else np.ascontiguousarray(self.zone_weight[idx]),
-            None if self.cost_round is None else np.ascontiguousarray(self.cost_round[idx]))
+            None if self.cost_round is None else np.ascontiguousarray(self.cost_round[idx]),
+            None if self.inst_weight is None else np.ascontiguousarray(self.inst_weight[idx]),
+            None if self.cost_move is None else np.ascontiguousarray(self.cost_move[idx]))
 
     def with_rounds(self, lo: float = 2.0, hi: float = 8.0, seed: int = 11) -> "ProblemBatch":
         """Same inputs with a per-candidate cost of every further state-transfer round of an inter-stage
@@ -161,6 +168,44 @@ class ProblemBatch:
             for c in range(self.n_configs):
                 rounds[q, c] = np.float32(rng.uniform(lo, hi))
         out.cost_round = rounds
+        return out
+
+    def with_weights(self, seed: int = 13, max_weight: int = 8, heavy_share: float = 0.15) -> "ProblemBatch":
+        """Same inputs with a hazard weight per instance: most instances draw their weight from U{1..max_weight},
+        a share of them (instances on a market about to be reclaimed, say) gets up to sixteen times that, capped
+        at 255.  Stand-in for per-instance preemption estimates (section 5.1)."""
+        out = self.take(range(self.n_queries))
+        nq, N = self.n_queries, self.n_instances
+        weight = np.ones((nq, N), dtype=np.uint8)
+        for q in range(nq):
+            rng = SplitMix64(_mix64(BASE_SEED ^ (seed * 0x2545F491 + q)))
+            for j in range(N):
+                w = rng.randint(1, max_weight)
+                if rng.uniform(0.0, 1.0) < heavy_share:
+                    w = min(255, w * rng.randint(2, 16))
+                weight[q, j] = w
+        out.inst_weight = weight
+        out.n_zones, out.zone, out.zone_weight = 0, None, None
+        return out
+
+    def with_moves(self, seed: int = 17) -> "ProblemBatch":
+        """Same inputs with a per-candidate cost of every instance that must receive state in an inter-stage
+        migration (alpha-beta model of section 8.4 with alpha = the inter-stage cost): drawn so that the dearest
+        inter-stage migration of the candidate, all stages down to one holder, costs between the inter-stage cost
+        and min(interval, re-partition cost)."""
+        out = self.take(range(self.n_queries))
+        move = np.zeros((self.n_queries, self.n_configs), dtype=np.float32)
+        tau = np.float32(self.interval_sec)
+        for q in range(self.n_queries):
+            rng = SplitMix64(_mix64(BASE_SEED ^ (seed * 0x9E3779B1 + q)))
+            for c in range(self.n_configs):
+                d, p = int(self.configs[c, 0]), int(self.configs[c, 1])
+                worst = (d - 1) * p
+                room = float(min(tau, self.cost[q, c, 2])) - float(self.cost[q, c, 1])
+                u = rng.uniform(0.0, 0.95)
+                move[q, c] = np.float32(u * max(room, 0.0) / worst) if worst > 0 else np.float32(u)
+        out.cost_move = move
+        out.cost_round = None
         return out
 
     def with_zones(self, n_zones: int, seed: int = 7, max_weight: int = 8) -> "ProblemBatch":

@@ -147,3 +147,65 @@ def zone_count_distribution(sizes, weights, k):
                     nxt[g] = nxt.get(g, 0.0) + p * weights[z] * left[z] / total
         dist = nxt
     return dist
+
+
+def word_at(seed, stream_id, unit, s, prefix, i):
+    """Word i of sequence `prefix` of a scenario: block index prefix * 2^16 + i // 4 in counter word 1."""
+    return philox4x32_10([s, ((prefix << 16) + i // 4) & M32, unit, stream_id], [seed & M32, seed >> 32])[i % 4]
+
+
+def weighted_preempted(M, k, weight, seed, stream_id, unit, s):
+    """k instances leave one after the other, each time one of those still there with probability proportional to
+    its weight: word i of sequence 0xFFFE scaled to the remaining total weight picks a point, the instance whose
+    stretch of the remaining weights (in ascending instance order) covers the point goes."""
+    there = list(range(M))
+    gone = np.zeros(M, dtype=np.uint8)
+    for i in range(k):
+        total = sum(int(weight[j]) for j in there)
+        point = (word_at(seed, stream_id, unit, s, 0xFFFE, i) * total) >> 32
+        for pos, j in enumerate(there):
+            point -= int(weight[j])
+            if point < 0:
+                gone[j] = 1
+                del there[pos]
+                break
+    return gone
+
+
+def zoned_preempted(M, k, zone, zone_weight, seed, stream_id, unit, s):
+    """Zones of unequal hazard: first the zone of each of the k departures (urn process, sequence 0xFFFF), then per
+    zone a uniform subset of its members by Floyd's method on their ranks (sequence = zone index)."""
+    Z = len(zone_weight)
+    members = [[j for j in range(M) if zone[j] == z] for z in range(Z)]
+    left = [len(m) for m in members]
+    for i in range(k):
+        total = sum(int(zone_weight[z]) * left[z] for z in range(Z))
+        point = (word_at(seed, stream_id, unit, s, 0xFFFF, i) * total) >> 32
+        for z in range(Z):
+            point -= int(zone_weight[z]) * left[z]
+            if point < 0:
+                left[z] -= 1
+                break
+    gone = np.zeros(M, dtype=np.uint8)
+    for z in range(Z):
+        size, kz = len(members[z]), len(members[z]) - left[z]
+        m = min(kz, size - kz)
+        chosen = set()
+        for i in range(m):
+            j = size - m + i
+            r = (word_at(seed, stream_id, unit, s, z, i) * (j + 1)) >> 32
+            chosen.add(j if r in chosen else r)
+        for rank, inst in enumerate(members[z]):
+            hit = rank in chosen
+            gone[inst] = (not hit) if kz > size - kz else hit
+    return gone
+
+
+def stage_occupancy(D, P, v):
+    """Survivors of every stage of the D x P grid, given the preemption vector of the grid."""
+    return D - np.asarray(v, dtype=np.int64).reshape(D, P).sum(axis=0)
+
+
+def moves_to_width(occ, width):
+    """Instances that must receive the state of a stage so that every stage has `width` holders."""
+    return int(np.maximum(0, width - np.asarray(occ)).sum())

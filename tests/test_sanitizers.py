@@ -11,7 +11,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 ORACLE_MODULES = ["tests/test_oracle_extremes.py", "tests/test_oracle_sampler.py", "tests/test_oracle_groups.py",
                   "tests/test_oracle_pool_all.py", "tests/test_oracle_zones.py", "tests/test_oracle_rounds.py",
-                  "tests/test_oracle_tables_dp.py", "tests/test_oracle_replay.py"]
+                  "tests/test_oracle_tables_dp.py", "tests/test_oracle_replay.py", "tests/test_oracle_weights.py",
+                  "tests/test_oracle_moves.py"]
 
 
 def _child_env(runtime, extra):
