@@ -134,6 +134,13 @@ typedef struct parcae_problem {
                                      state-transfer round of an inter-stage migration INTO
                                      configuration c, finite, >= 0; see "Transfer rounds"  */
     const parcae_profile *profile; /* HOST or NULL: profiling hooks, read before the call returns */
+    const uint8_t *inst_weight;   /* DEVICE [nq][N] or NULL: hazard weight 1..255 of every instance; see
+                                     "A weight per instance" below; not together with n_zones > 0  */
+    const float *cost_move;       /* DEVICE [nq][C] or NULL (= 0): seconds per instance that must receive
+                                     state in an inter-stage migration INTO configuration c; see
+                                     "Moved instances" below; not together with cost_round; needs hist_occ */
+    uint32_t *hist_occ;           /* DEVICE [nq][T][L] uint32, used with cost_move only: the stage-occupancy
+                                     statistic, written by the evaluation, read by the planning calls    */
 } parcae_problem;
 
 /*
@@ -190,6 +197,14 @@ typedef struct parcae_problem {
  * One zone gives the uniform draw bit for bit.  Everything downstream
  * (histograms, tables, weights, plan) is unchanged.
  *
+ * A weight per instance (section 5.1 again: an estimate per instance in place of equal probabilities).
+ * With inst_weight, instance j of the pool has the hazard weight inst_weight[q][j] and the k preempted
+ * instances leave one after the other, each time one of those still there with probability proportional
+ * to its weight (successive weighted sampling without replacement): for i = 0..k-1,
+ * total = sum of the weights still there, r = (word(0xFFFE, i) * total) >> 32, and the instance that goes
+ * is the first one, in ascending order, at which the running sum of the weights still there exceeds r.
+ * Exactly k words per scenario.  Equal weights give every k-subset the same probability.
+ *
  * Per scenario (section 5.2, section 7): occ_s = alive instances of stage s;
  * d_min = min over s of occ_s (pipelines that intra-stage re-routing can
  * complete; 0 = a stage lost every replica, only a checkpoint rollback
@@ -223,6 +238,24 @@ typedef struct parcae_problem {
  *   cost_r = min(cost[.][2], cost[.][1] + b * (float)(r - 1)) in float,
  * and teff = (((float)n0 * tau + (float)n1 * e_0) + inter + (float)n3 * e_2) / (float)S.
  * With b == 0 (or cost_round NULL) the formula above applies unchanged.
+ *
+ * Moved instances (section 8.4 read the other way: the transfer cost grows with the number of instances that
+ * must receive state; alpha-beta model with alpha = cost[.][1], beta = cost_move).  With b = cost_move[q][c'] > 0
+ * an inter-stage migration of a scenario to width w costs cost[.][1] + b * moves, moves = sum over the stages
+ * of max(0, w - occ_s): the instances that must receive a stage's state so that every stage has w holders.
+ * The inputs must keep the dearest such migration, cost[.][1] + b * (D_c' - 1) * P_c', within
+ * min(tau, cost[.][2]) (PARCAE_EINVAL per query otherwise): it then never costs more than a re-partition or
+ * than the interval lasts, no cap or clamp binds, and the expectation is linear in the move counts.
+ * The evaluation keeps a third statistic for it: hist_occ[q][t][off[c] + j] = number of stages with exactly j
+ * alive instances, summed over the scenarios of the unit with d_min >= 1 (bin 0 stays empty; with multi-GPU
+ * instances j counts GPU pipelines, as in the other histograms).  For a width w,
+ *   total_moves = sum over 1 <= j < w, j <= D of hist_occ[j] * (w - j)     (64-bit)
+ * is the number of moves over all scenarios of the unit (scenarios that need no inter-stage migration have
+ * no stage below w), and teff replaces (float)n2 * e_1 by
+ *   inter = (float)n2 * e_1 - b * (float)total_moves   (each product rounded, then the difference; the count
+ *           converted to float with round-to-nearest-even)
+ * as in the formula for transfer rounds.  The planning calls then take the route that writes the transition
+ * weights to the workspace, whatever the batch size.
  *
  * Liveput tables (Eq. 1, Eq. 4), all float, sums in ascending bin order,
  * acc = acc + (float)count * thr (product and sum rounded separately):
@@ -363,7 +396,8 @@ int parcae_debug_sample(const parcae_problem *p, int32_t q, int32_t t, int32_t c
  *      interval that actually happened (availability true_avail[q][i] -> a, stream id + 2 i + 1), without the
  *      feasibility test; re-partition formula if nothing was running; 0 if nothing runs afterwards.
  *      total[q] accumulates the rewards in float in step order.
- *   p->avail is ignored.  The pool flag, group_size and all tables of p apply.
+ *   p->avail is ignored.  The pool flag, group_size and all tables of p apply, except that a cost per moved
+ *   instance (cost_move) is refused with PARCAE_EINVAL.
  *   true_avail  DEVICE in  [nq][n_steps + 1]
  *   windows     DEVICE in  [n_steps][nq][T + 1], windows[i][q][0] = true_avail[q][i]; may be NULL for
  *               PARCAE_REPLAY_REACTIVE

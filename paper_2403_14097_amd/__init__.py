@@ -70,6 +70,7 @@ class parcae_problem(ct.Structure):
         ("group_size", ct.c_int32), ("n_zones", ct.c_int32),
         ("zone", ct.c_void_p), ("zone_weight", ct.c_void_p), ("cost_round", ct.c_void_p),
         ("profile", ct.POINTER(parcae_profile)),
+        ("inst_weight", ct.c_void_p), ("cost_move", ct.c_void_p), ("hist_occ", ct.c_void_p),
     ]
 
 
@@ -155,6 +156,9 @@ class Problem:
     zone: "object" = None         # uint8 [nq, N] device, zone of every instance
     zone_weight: "object" = None  # int32 view of uint32 [nq, PARCAE_MAX_ZONES] device
     cost_round: "object" = None   # float32 [nq, C] device: seconds per further transfer round, or None
+    inst_weight: "object" = None  # uint8 [nq, N] device: hazard weight of every instance, or None
+    cost_move: "object" = None    # float32 [nq, C] device: seconds per instance that must receive state, or None
+    hist_occ: "object" = None     # int32 view of uint32 [nq, T, L] device: stage-occupancy statistic (with cost_move)
     profile_events: Optional[tuple] = None   # raw hipEvent_t handles (before sampling, after sampling, before plan,
                                              # after plan; each an int or None) for the library to record
     _profile: object = field(default=None, repr=False)
@@ -189,7 +193,8 @@ class Problem:
             ct.cast(self._cfg_arr, ct.POINTER(parcae_config)),
             _ptr(self.avail), _ptr(self.thr), _ptr(self.cost), _ptr(self.seed), _ptr(self.stream_id),
             _ptr(self.cur_config), int(self.group_size),
-            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight), _ptr(self.cost_round), prof)
+            int(self.n_zones), _ptr(self.zone), _ptr(self.zone_weight), _ptr(self.cost_round), prof,
+            _ptr(self.inst_weight), _ptr(self.cost_move), _ptr(self.hist_occ) if self.cost_move is not None else None)
 
     def workspace(self):
         """Device workspace of the size the library asks for (allocated once per Problem)."""
@@ -236,6 +241,14 @@ def upload(batch, device="cuda:0", n_scenarios: Optional[int] = None) -> Problem
         torch = _require_gpu()
         import numpy as np
         prob.cost_round = torch.from_numpy(np.array(batch.cost_round, dtype=np.float32, order="C")).to(device)
+    if getattr(batch, "inst_weight", None) is not None:
+        torch = _require_gpu()
+        import numpy as np
+        prob.inst_weight = torch.from_numpy(np.array(batch.inst_weight, dtype=np.uint8, order="C")).to(device)
+    if getattr(batch, "cost_move", None) is not None:
+        torch = _require_gpu()
+        import numpy as np
+        prob.cost_move = torch.from_numpy(np.array(batch.cost_move, dtype=np.float32, order="C")).to(device)
     return prob
 
 
@@ -266,6 +279,7 @@ class EvalOut:
     teff: "object"       # [nq, T, C]
     gain: "object"
     status: "object"     # [nq]
+    hist_occ: "object" = None   # int32 view of uint32 [nq, T, L]: stage-occupancy statistic, with cost_move only
 
 
 @dataclass
@@ -285,7 +299,7 @@ def alloc_eval_out(p: Problem, tables: bool = True) -> EvalOut:
     f = lambda *s: torch.empty(s, dtype=torch.float32, device=dev)  # noqa: E731
     i = lambda *s: torch.empty(s, dtype=torch.int32, device=dev)    # noqa: E731
     return EvalOut(i(nq, T, L), i(nq, T, L), f(nq, 3, T, C) if tables else None, f(nq, T, C) if tables else None,
-                   f(nq, T, C) if tables else None, i(nq))
+                   f(nq, T, C) if tables else None, i(nq), i(nq, T, L) if p.cost_move is not None else None)
 
 
 def alloc_plan_out(p: Problem, full: bool = True) -> PlanOut:
@@ -299,6 +313,7 @@ def alloc_plan_out(p: Problem, full: bool = True) -> PlanOut:
 
 def parcae_liveput_eval(p: Problem, out: Optional[EvalOut] = None) -> EvalOut:
     out = out or alloc_eval_out(p)
+    p.hist_occ = out.hist_occ          # the third statistic travels in the problem structure
     ws, nbytes = p.workspace()
     cs = p.c_struct()
     _check(load_library().parcae_liveput_eval(ct.byref(cs), _ptr(out.hist_int), _ptr(out.hist_min), _ptr(out.liveput),
@@ -320,6 +335,7 @@ def parcae_plan_from_hist(p: Problem, hist_int, hist_min, out: Optional[PlanOut]
 def parcae_liveput_plan(p: Problem, ev: Optional[EvalOut] = None, out: Optional[PlanOut] = None):
     ev = ev or alloc_eval_out(p)
     out = out or alloc_plan_out(p)
+    p.hist_occ = ev.hist_occ
     ws, nbytes = p.workspace()
     cs = p.c_struct()
     _check(load_library().parcae_liveput_plan(ct.byref(cs), _ptr(ev.hist_int), _ptr(ev.hist_min), _ptr(ev.liveput),
@@ -332,6 +348,7 @@ def parcae_liveput_plan(p: Problem, ev: Optional[EvalOut] = None, out: Optional[
 def parcae_liveput_plan_static(p: Problem, ev: EvalOut, out: PlanOut):
     """parcae_liveput_plan on the library's built-in workspace; the output buffers must be passed in (this call
     allocates nothing)."""
+    p.hist_occ = ev.hist_occ
     cs = p.c_struct()
     _check(load_library().parcae_liveput_plan_static(ct.byref(cs), _ptr(ev.hist_int), _ptr(ev.hist_min), _ptr(ev.liveput),
                                                      _ptr(ev.teff), _ptr(ev.gain), _ptr(out.F), _ptr(out.bp),

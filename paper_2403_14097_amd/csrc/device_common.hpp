@@ -39,6 +39,9 @@ struct Batch {
     const uint8_t* zone;          // [nq][N] zone of every instance, or null
     const uint32_t* zone_weight;  // [nq][kMaxZones] hazard weight of every zone, or null
     const float* cost_round;      // [nq][C] seconds per further state-transfer round of an inter-stage migration, or null
+    const uint8_t* inst_weight;   // [nq][N] hazard weight of every instance (1..255), or null
+    const float* cost_move;       // [nq][C] seconds per instance that must receive state in an inter-stage migration, or null
+    uint32_t* hist_occ;           // [nq][T][L] stage-occupancy statistic (with cost_move), or null
 };
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }

@@ -315,6 +315,85 @@ __device__ __forceinline__ void sample_mask_zoned(Mask<NW>& mask, uint32_t* lds_
     static_for<NW>([&](auto i) { mask.w[i.value] = lds_col[i.value * stride]; });
 }
 
+// ------------------------------------------------------------------ a hazard weight per instance
+
+// How a unit's scenarios are drawn: every instance equally likely, zones of unequal hazard, or a weight per instance.
+enum DrawKind { kDrawUniform = 0, kDrawZoned = 1, kDrawWeighted = 2 };
+
+// Weights of the pool of one unit, staged once per work item by the wave that owns it (section 5.1: the
+// equal-probability assumption replaced by an estimate per instance).
+struct WeightCtx {
+    uint32_t packed;        // lane L: the weights of instances 4L .. 4L + 3, one per byte, 0 beyond the pool
+    const uint8_t* bytes;   // LDS [260]: the same weights, one per instance, for per-lane look-ups
+    uint32_t total;         // sum over the pool
+};
+
+// All 64 lanes of the wave must be active.  A weight of 0 (refused by the input checks) counts as 1.
+__device__ __forceinline__ WeightCtx weight_setup(const Batch& b, int q, int M, uint8_t* bytes)
+{
+    const int lane = lane_id();
+    const uint8_t* wq = b.inst_weight + (int64_t)q * b.N;
+    WeightCtx wc;
+    wc.bytes = bytes;
+    uint32_t packed = 0u, sum = 0u;
+    static_for<4>([&](auto x) {
+        const int j = 4 * lane + x.value;
+        uint32_t w = 0u;
+        if (j < M) {
+            w = wq[j];
+            w = w < 1u ? 1u : w;
+        }
+        bytes[j] = (uint8_t)w;
+        packed |= w << (8 * x.value);
+        sum += w;
+    });
+    if (lane < 4) bytes[256 + lane] = 0u;  // a look-up one past the pool (cannot happen for valid input) finds 0
+    for (int sh = 1; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh);
+    wc.packed = packed;
+    wc.total = sum;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return wc;
+}
+
+// Preempted set of scenario s by successive weighted sampling without replacement: k times, word i of sequence
+// 0xFFFE scaled to the weight still there picks a point, and the first instance (ascending) at which the running
+// sum of the weights still there exceeds the point goes.  All lanes walk the instances in step (the weight of
+// instance j is a scalar), each with its own set: the instance that goes is the number of instances whose running
+// sum does not exceed the point, because running sums never decrease.
+template <int NW>
+__device__ __forceinline__ void sample_mask_weighted(Mask<NW>& mask, const WeightCtx& wc, int M, int k, uint32_t s,
+                                                     uint32_t unit, uint32_t stream_id, const PhiloxKeys& ks)
+{
+    mask.clear();
+    uint32_t total = wc.total;
+    for (int i0 = 0; i0 < k; i0 += 4) {
+        const Philox4 blk = philox4x32_10(s, 0xFFFE0000u + (uint32_t)(i0 >> 2), unit, stream_id, ks);
+        static_for<4>([&](auto x) {
+            if (i0 + x.value < k) {
+                const uint32_t point = __umulhi(blk.x[x.value], total);
+                uint32_t running = 0u, victim = 0u;
+                static_for<NW>([&](auto W) {
+                    const uint32_t there = ~mask.w[W.value];
+                    int quads = (M - 32 * W.value + 3) >> 2;  // packed weight words that cover instances of this mask word
+                    quads = quads < 0 ? 0 : (quads > 8 ? 8 : quads);
+                    for (int p = 0; p < quads; ++p) {
+                        const uint32_t four = (uint32_t)__builtin_amdgcn_readlane((int)wc.packed, 8 * W.value + p);
+                        static_for<4>([&](auto y) {
+                            const uint32_t w = (four >> (8 * y.value)) & 0xffu;
+                            const uint32_t on = (uint32_t)__builtin_amdgcn_sbfe((int)there, (uint32_t)(4 * p + y.value), 1u);
+                            running += on & w;
+                            victim += running <= point ? 1u : 0u;
+                        });
+                    }
+                });
+                mask.set(victim);
+                total -= wc.bytes[victim];
+            }
+        });
+    }
+}
+
 // ------------------------------------------------------------------ reducer
 
 // Bits at multiples of P inside a 32-bit word (P a power of two <= 32).
@@ -630,6 +709,33 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
     });
 }
 
+// ------------------------------------------------------------------ stage-occupancy statistic
+
+// For a scenario in which every stage kept a survivor (d_min >= 1): one count per stage into the bin of its number
+// of survivors (section 8.4: what an inter-stage migration costs depends on how many instances must receive state,
+// and that follows from these counts for every target width).  Works for any depth: stage s owns the bits
+// s, s + P, s + 2 P, ... of the mask; first[i] = first such bit of word i for the current stage, kept in step.
+template <int NW>
+__device__ __forceinline__ void stage_occupancy_add(const Mask<NW>& mask, int rows, int P, int group, int d_min,
+                                                    uint32_t* bins_occ)
+{
+    const uint32_t period = P < 32 ? period_comb(P) : 1u;
+    int first[NW];
+    static_for<NW>([&](auto i) {
+        int r = (-32 * i.value) % P;
+        first[i.value] = r < 0 ? r + P : r;
+    });
+    for (int s = 0; s < P; ++s) {
+        int gone = 0;
+        static_for<NW>([&](auto i) {
+            const uint32_t comb = first[i.value] < 32 ? period << first[i.value] : 0u;
+            gone += __popc(mask.w[i.value] & comb);
+            first[i.value] = first[i.value] + 1 == P ? 0 : first[i.value] + 1;
+        });
+        if (d_min >= 1) atomicAdd(&bins_occ[(rows - gone) * group], 1u);
+    }
+}
+
 // ------------------------------------------------------------------ histogram update
 
 // One LDS atomic per lane.  Lanes that hit the same bin are serialised by the LDS bank, not by the
@@ -683,10 +789,13 @@ __global__ void __launch_bounds__(256) prep_hist_kernel(Batch b, WorkQueue wq, u
         int M, k;
         unit_pool(b, q, t, cr.D, cr.P, M, k);
         int bin;
-        const uint32_t v =
-            (unit_closed_form(cr.D / b.group, cr.P, M, k, bin) && j == bin * b.group) ? (uint32_t)b.S : 0u;
+        const bool single = unit_closed_form(cr.D / b.group, cr.P, M, k, bin) && j == bin * b.group;
+        const uint32_t v = single ? (uint32_t)b.S : 0u;
         hist_int[e] = v;
         hist_min[e] = v;
+        // stage-occupancy statistic of such a unit: every stage of every scenario has `bin` survivors, and a unit
+        // that lost a stage (bin 0) counts nothing
+        if (b.hist_occ) b.hist_occ[e] = (single && bin >= 1) ? (uint32_t)b.S * (uint32_t)cr.P : 0u;
     }
 }
 
@@ -740,41 +849,48 @@ __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col,
     }
 }
 
-// One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.  zc: zones of the pool, or null for the
-// uniform draw.
-template <int NW, bool kZoned, int KIND>
+// One wave, scenarios [s_begin, s_end) of one unit, 64 at a time.  zc / wc: zones or weights of the pool for the
+// draws that are not uniform.  kMoves adds the stage-occupancy statistic (bins_occ).
+template <int NW, int kDraw, bool kMoves, int KIND>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int M, int k, uint32_t unit,
                                                 uint32_t stream_id, const PhiloxKeys& ks, uint32_t s_begin,
                                                 uint32_t s_end, uint32_t* lds_col, uint32_t* bins_int,
-                                                uint32_t* bins_min, const ZoneCtx* zc)
+                                                uint32_t* bins_min, uint32_t* bins_occ, const ZoneCtx* zc,
+                                                const WeightCtx* wc)
 {
     const int rows = cr.D / group;  // pipelines of the instance grid
     for (uint32_t s = s_begin + (uint32_t)lane_id(); s < s_end; s += kWave) {
         int n_int, d_min;
         Mask<NW> mask;
-        if constexpr (kZoned) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
+        if constexpr (kDraw == kDrawZoned) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
+        else if constexpr (kDraw == kDrawWeighted) sample_mask_weighted<NW>(mask, *wc, M, k, s, unit, stream_id, ks);
         else draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
         if (M > rows * cr.P) mask.keep_below(rows * cr.P);  // idle instances of the pool are not on the grid
         reduce_kind<NW, KIND>(mask, rows, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int * group, true);
         hist_add(bins_min, d_min * group, true);
+        if constexpr (kMoves) stage_occupancy_add<NW>(mask, rows, cr.P, group, d_min, bins_occ);
     }
 }
 
 // Persistent kernel: every wave pulls (unit, chunk) items from the work queue until it is empty, so waves never
 // wait for each other and units without sampling cost nothing here.  Item i is chunk i % n_chunks of
 // list[i / n_chunks]; a chunk is chunk_len consecutive scenarios.  Each wave owns a slice of the LDS bins.
-// kZoned selects the non-uniform draw (a kernel of its own, so the uniform one keeps its registers).
-template <bool kZoned>
-__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(kZoned ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
+// kDraw selects how scenarios are drawn and kMoves adds the stage-occupancy statistic (kernels of their own, so
+// the plain one keeps its registers).
+template <int kDraw, bool kMoves>
+__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu((kDraw != kDrawUniform || kMoves) ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {
     constexpr int kWaves = kEvalThreads / kWave;
-    __shared__ uint32_t bins_all[kWaves][2 * (kMaxInstances + 1)];
+    constexpr bool kZoned = kDraw == kDrawZoned;
+    constexpr bool kWeighted = kDraw == kDrawWeighted;
+    __shared__ uint32_t bins_all[kWaves][(kMoves ? 3 : 2) * (kMaxInstances + 1)];
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
     __shared__ uint8_t zone_perm[kZoned ? kWaves : 1][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kZoned ? kWaves : 1][kMaxZones * 8];
+    __shared__ uint8_t weight_bytes[kWeighted ? kWaves : 1][260];
     const int lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
     uint32_t* bins = bins_all[wave];
@@ -840,7 +956,8 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
         const int nb = cr.D + 1;
         uint32_t* bins_int = bins;
         uint32_t* bins_min = bins + nb;
-        for (int i = lane; i < 2 * nb; i += kWave) bins[i] = 0u;
+        uint32_t* bins_occ = bins + 2 * nb;  // used with kMoves only
+        for (int i = lane; i < (kMoves ? 3 : 2) * nb; i += kWave) bins[i] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -852,19 +969,21 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
         s_end = s_end > (uint32_t)b.S ? (uint32_t)b.S : s_end;
 
         ZoneCtx zc;
+        WeightCtx wc;
         if constexpr (kZoned) zc = zone_setup(b, q, M, zone_perm[wave], zone_mask[wave]);
+        if constexpr (kWeighted) wc = weight_setup(b, q, M, weight_bytes[wave]);
         with_reducer_kind(cr.D / b.group, cr.P, cr.log2P, [&](auto kind) {
             constexpr int K = decltype(kind)::value;
             // kinds that need more than 32 stages cannot meet a one-word pool
             if (M <= 32) {
                 if constexpr (K != kPow2Words && K != kAnyLarge)
-                    eval_unit_chunk<1, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+                    eval_unit_chunk<1, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
             } else if (M <= 64) {
-                eval_unit_chunk<2, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+                eval_unit_chunk<2, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
             } else if (M <= 128) {
-                eval_unit_chunk<4, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+                eval_unit_chunk<4, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
             } else {
-                eval_unit_chunk<8, kZoned, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, &zc);
+                eval_unit_chunk<8, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
             }
         });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -880,6 +999,11 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
                 if (vi) atomicAdd(&hist_int[base + i], vi);
                 if (vm) atomicAdd(&hist_min[base + i], vm);
             }
+            if constexpr (kMoves) {
+                const uint32_t vo = bins_occ[i];
+                if (n_chunks == 1) b.hist_occ[base + i] = vo;
+                else if (vo) atomicAdd(&b.hist_occ[base + i], vo);
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -889,11 +1013,12 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
 // One scenario through the same code path the histogram kernel takes for a unit of this size.
 template <int NW>
 __device__ __forceinline__ void debug_one(const CfgRec cr, int group, uint32_t* lds_col, int M, int k, uint32_t s, uint32_t unit,
-                                          uint32_t stream_id, const PhiloxKeys& ks, const ZoneCtx* zc,
+                                          uint32_t stream_id, const PhiloxKeys& ks, const ZoneCtx* zc, const WeightCtx* wc,
                                           uint32_t* mask_out, int& n_int, int& d_min)
 {
     Mask<NW> mask;
-    if (zc) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
+    if (wc) sample_mask_weighted<NW>(mask, *wc, M, k, s, unit, stream_id, ks);
+    else if (zc) sample_mask_zoned<NW>(mask, lds_col, kEvalThreads, *zc, k, s, unit, stream_id, ks);
     else draw_scenario<NW>(mask, lds_col, M, k, s, unit, stream_id, ks);
     static_for<8>([&](auto i) {
         if constexpr (i.value < NW) mask_out[i.value] = mask.w[i.value];
@@ -915,31 +1040,43 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     __shared__ uint32_t lmask[8 * kEvalThreads];
     __shared__ uint8_t zone_perm[kEvalThreads / kWave][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kEvalThreads / kWave][kMaxZones * 8];
+    __shared__ uint8_t weight_bytes[kEvalThreads / kWave][260];
     const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
     const CfgRec cr = b.cfg[c];
     int M, k;
     unit_pool(b, q, t, cr.D, cr.P, M, k);
     ZoneCtx zones;
+    WeightCtx weights;
     const ZoneCtx* zc = nullptr;
-    if (b.n_zones > 0) {  // every lane takes part in building the tables, also those past the last scenario
-        const int wave = (int)threadIdx.x / kWave;
+    const WeightCtx* wc = nullptr;
+    const int wave = (int)threadIdx.x / kWave;
+    if (b.inst_weight) {  // every lane takes part in building the tables, also those past the last scenario
+        weights = weight_setup(b, q, M, weight_bytes[wave]);
+        wc = &weights;
+    } else if (b.n_zones > 0) {
         zones = zone_setup(b, q, M, zone_perm[wave], zone_mask[wave]);
         zc = &zones;
     }
-    if (x >= ns) return;
+    // No lane leaves early: the weighted draw reads the weights out of other lanes' registers, so every lane runs
+    // the draw (lanes past the last scenario redo scenario s0) and only the stores are predicated.
+    const bool live = x < ns;
+    const uint32_t xs = live ? x : 0u;
     const uint64_t seed = b.seed[q];
     const PhiloxKeys ks = philox_keys((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32));
     const uint32_t stream_id = (b.stream_id ? b.stream_id[q] : 0u) + b.stream_offset;
     const uint32_t unit = (uint32_t)(t * b.C + c);
     uint32_t* lds_col = lmask + threadIdx.x;
-    uint32_t* out = masks + (size_t)x * 8;
+    uint32_t out[8];
     int n_int, d_min;
-    if (M <= 32) debug_one<1>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
-    else if (M <= 64) debug_one<2>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
-    else if (M <= 128) debug_one<4>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
-    else debug_one<8>(cr, b.group, lds_col, M, k, s0 + x, unit, stream_id, ks, zc, out, n_int, d_min);
-    n_int_out[x] = n_int;
-    d_min_out[x] = d_min;
+    if (M <= 32) debug_one<1>(cr, b.group, lds_col, M, k, s0 + xs, unit, stream_id, ks, zc, wc, out, n_int, d_min);
+    else if (M <= 64) debug_one<2>(cr, b.group, lds_col, M, k, s0 + xs, unit, stream_id, ks, zc, wc, out, n_int, d_min);
+    else if (M <= 128) debug_one<4>(cr, b.group, lds_col, M, k, s0 + xs, unit, stream_id, ks, zc, wc, out, n_int, d_min);
+    else debug_one<8>(cr, b.group, lds_col, M, k, s0 + xs, unit, stream_id, ks, zc, wc, out, n_int, d_min);
+    if (live) {
+        static_for<8>([&](auto i) { masks[(size_t)x * 8 + i.value] = out[i.value]; });
+        n_int_out[x] = n_int;
+        d_min_out[x] = d_min;
+    }
 }
 
 }  // namespace parcae

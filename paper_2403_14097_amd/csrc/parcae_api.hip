@@ -84,6 +84,8 @@ int check_problem(const parcae_problem* p, CfgRec* table, size_t table_cap, Layo
     if (p->group_size < 0 || p->group_size > 64) return PARCAE_EINVAL;
     if (p->n_zones < 0 || p->n_zones > PARCAE_MAX_ZONES) return PARCAE_EINVAL;
     if (p->n_zones > 0 && (!p->zone || !p->zone_weight)) return PARCAE_EINVAL;
+    if (p->n_zones > 0 && p->inst_weight) return PARCAE_EINVAL;     // zones or a weight per instance, not both
+    if (p->cost_move && (p->cost_round || !p->hist_occ)) return PARCAE_EINVAL;
     const int group = p->group_size > 1 ? p->group_size : 1;
     int64_t L = 0;
     int max_row = 0;
@@ -108,6 +110,11 @@ int check_problem(const parcae_problem* p, CfgRec* table, size_t table_cap, Layo
         max_row = g.D + 1 > max_row ? g.D + 1 : max_row;
     }
     if ((int64_t)p->n_queries * p->n_intervals * L >= (int64_t)1 << 40) return PARCAE_EINVAL;
+    if (p->cost_move) {  // a bin of the stage-occupancy statistic counts up to S * P stages
+        int max_depth = 0;
+        for (int c = 0; c < p->n_configs; ++c) max_depth = p->configs[c].P > max_depth ? p->configs[c].P : max_depth;
+        if ((int64_t)p->n_scenarios * max_depth >= (int64_t)1 << 32) return PARCAE_EINVAL;
+    }
     if (lay) {
         lay->L = L;
         lay->max_row = max_row;
@@ -119,7 +126,9 @@ int check_problem(const parcae_problem* p, CfgRec* table, size_t table_cap, Layo
         lay->list_off = lay->queue_off + kAlign * (1 + parcae::kQueueShards);  // item count, then one line per shard counter
         lay->w_off = lay->list_off + align_up(sizeof(uint32_t) * n_units);
         // the per-query planner needs more LDS per candidate; where it does not fit the weights go through memory
-        lay->stepwise = p->n_queries < kFusedMinQueries || pick_plan_cap(p->n_configs, *lay, 0, true) < 0;
+        // (and with a cost per moved instance the weights always go through memory)
+        lay->stepwise = p->n_queries < kFusedMinQueries || pick_plan_cap(p->n_configs, *lay, 0, true) < 0 ||
+                        p->cost_move != nullptr;
         const size_t w_bytes = lay->stepwise ? sizeof(float) * n_units * (size_t)p->n_configs : 0;
         const size_t f_bytes =
             lay->stepwise ? sizeof(float) * (size_t)p->n_queries * ((size_t)p->n_intervals + 1) * (size_t)p->n_configs : 0;
@@ -156,6 +165,9 @@ Batch make_batch(const parcae_problem* p, const Layout& lay, void* ws)
     b.cur_config = p->cur_config;
     b.n_zones = p->n_zones; b.zone = p->zone; b.zone_weight = p->zone_weight;
     b.cost_round = p->cost_round;
+    b.inst_weight = p->inst_weight;
+    b.cost_move = p->cost_move;
+    b.hist_occ = p->cost_move ? p->hist_occ : nullptr;
     return b;
 }
 
@@ -244,12 +256,18 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
 
     const int64_t eval_blocks = parcae::eval_grid_blocks(cus, n_units * n_chunks);
     if (p->profile && record(p->profile->event_before_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
-    if (b.n_zones > 0)
-        parcae::eval_hist_kernel<true><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
-            b, wq, n_chunks, chunk_len, hist_int, hist_min);
-    else
-        parcae::eval_hist_kernel<false><<<dim3((unsigned)eval_blocks), dim3(parcae::kEvalThreads), 0, st>>>(
-            b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    const dim3 grid((unsigned)eval_blocks), block(parcae::kEvalThreads);
+    const bool moves = b.cost_move != nullptr;
+    if (b.inst_weight) {
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawWeighted, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawWeighted, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    } else if (b.n_zones > 0) {
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawZoned, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawZoned, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    } else {
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawUniform, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawUniform, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+    }
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     if (p->profile && record(p->profile->event_after_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
 
@@ -342,7 +360,7 @@ int compute_units(int* cus)
 bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layout& lay)
 {
     int cus = 0;
-    if (p->n_configs > parcae::kWaveMaxConfigs || compute_units(&cus) != PARCAE_OK) return false;
+    if (p->n_configs > parcae::kWaveMaxConfigs || p->cost_move || compute_units(&cus) != PARCAE_OK) return false;
     WaveLaunch wl;
     return pick_wave_launch(p->n_queries, p->n_intervals, p->n_configs, lay.L,
                             parcae::wave_geometry(table, p->n_configs), cus, &wl);
@@ -369,7 +387,7 @@ int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, 
 {
     unsigned char* base = static_cast<unsigned char*>(ws);
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
-    if (b.C <= parcae::kWaveMaxConfigs) {
+    if (b.C <= parcae::kWaveMaxConfigs && !b.cost_move) {
         int cus = 0;
         if (compute_units(&cus) != PARCAE_OK) return PARCAE_EHIP;
         const parcae::WaveGeom g = parcae::wave_geometry(table, b.C);
@@ -688,6 +706,7 @@ int parcae_replay(const parcae_problem* problem, int32_t n_steps, const int32_t*
     if (mode != PARCAE_REPLAY_PROACTIVE && mode != PARCAE_REPLAY_REACTIVE) return PARCAE_EINVAL;
     const bool plans = mode == PARCAE_REPLAY_PROACTIVE;
     if (plans && !windows) return PARCAE_EINVAL;
+    if (p->cost_move) return PARCAE_EINVAL;  // the replay's reward has no cost per moved instance
     if ((int64_t)p->n_queries * ((int64_t)n_steps + 1) >= (int64_t)1 << 31) return PARCAE_EINVAL;
     if ((int64_t)p->n_queries * n_steps * ((int64_t)p->n_intervals + 1) >= (int64_t)1 << 40) return PARCAE_EINVAL;
     const parcae_problem q = replay_problem(p, windows ? windows : true_avail);

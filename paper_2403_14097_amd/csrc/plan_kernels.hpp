@@ -65,6 +65,18 @@ __device__ __forceinline__ float inter_seconds_by_rounds(Tail tail, int w, float
     return acc;
 }
 
+// Inter-stage share of the expected effective seconds when an inter-stage migration costs c_inter + move_sec per
+// instance that must receive state (section 8.4, alpha-beta model): n2 scenarios at max(0, tau - c_inter) each, less
+// move_sec for every instance moved over all of them.  occ = the unit's stage-occupancy statistic (bins 0..D): a stage
+// with j < w survivors needs w - j instances, and only scenarios that need an inter-stage migration have such stages.
+__device__ __forceinline__ float inter_seconds_by_moves(const uint32_t* occ, int D, int w, uint32_t n2, float e1,
+                                                        float move_sec)
+{
+    unsigned long long total_moves = 0ull;
+    for (int j = 1; j <= D && j < w; ++j) total_moves += (unsigned long long)occ[j] * (unsigned long long)(w - j);
+    return __fsub_rn(__fmul_rn((float)n2, e1), __fmul_rn(move_sec, __ull2float_rn(total_moves)));
+}
+
 // teff with the inter-stage share given as a sum of seconds (see the header's teff() with transfer rounds).
 __device__ __forceinline__ float teff_with_inter(uint32_t n0, uint32_t n01, uint32_t h0, int w, uint32_t S, float tau,
                                                  float e0, float e2, float inter)
@@ -108,6 +120,21 @@ __device__ __forceinline__ int query_inputs_bad(const Batch& b, const CfgRec* cf
         for (int c = tid; c < b.C; c += nthreads) {
             const float v = b.cost_round[(int64_t)q * b.C + c];
             if (!(v >= 0.0f) || !(v < __builtin_inff())) my_bad = 1;
+        }
+    }
+    if (b.inst_weight) {
+        for (int j = tid; j < b.N; j += nthreads)
+            if (b.inst_weight[(int64_t)q * b.N + j] < 1u) my_bad = 1;
+    }
+    if (b.cost_move) {
+        // the dearest inter-stage migration into c (every stage down to one holder) must not cost more than a
+        // re-partition or than the interval lasts: the expectation is then linear in the move counts
+        for (int c = tid; c < b.C; c += nthreads) {
+            const float v = b.cost_move[(int64_t)q * b.C + c];
+            const float* co = b.cost + ((int64_t)q * b.C + c) * 3;
+            const float worst = (float)((cfg[c].D - 1) * cfg[c].P);
+            const float cap = co[2] < b.tau ? co[2] : b.tau;
+            if (!(v >= 0.0f) || !(v < __builtin_inff()) || !(co[1] + v * worst <= cap)) my_bad = 1;
         }
     }
     if (b.n_zones > 0) {
@@ -181,8 +208,15 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
     const float fS = (float)S;
     const float full = th[d_star];
     const float round_sec = b.cost_round ? b.cost_round[(int64_t)q * b.C + c] : 0.0f;
+    const float move_sec = b.cost_move ? b.cost_move[(int64_t)q * b.C + c] : 0.0f;
     float te;
-    if (round_sec == 0.0f) {
+    if (move_sec != 0.0f) {
+        const uint32_t n3 = d_star >= 1 ? hm[0] : 0u;
+        const float inter = inter_seconds_by_moves(b.hist_occ + qt * b.L + cr.off, cr.D, d_star, S - n01 - n3,
+                                                   max0(__fsub_rn(b.tau, co[1])), move_sec);
+        te = teff_with_inter(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
+                             max0(__fsub_rn(b.tau, co[2])), inter);
+    } else if (round_sec == 0.0f) {
         te = teff_from_counts(n0, n01, hm[0], d_star, S, b.tau, max0(__fsub_rn(b.tau, co[0])),
                               max0(__fsub_rn(b.tau, co[1])), max0(__fsub_rn(b.tau, co[2])));
     } else {
@@ -417,8 +451,11 @@ __device__ __forceinline__ void load_chunk(const Batch& b, int q, int t, int c_l
 
 // Weight of a same-depth transition c -> c2 (both feasible, not a cold start): throughput of c2 times the expected
 // effective seconds of unit (t, c) read at the width of c2.  `first` = first bin of the rows held in LDS.
+// occ_step / move_sec: with a cost per moved instance, the stage-occupancy statistic of the step (all candidates,
+// in memory) and the rate of the target; otherwise null / 0.
 template <bool kRounds>
-__device__ __forceinline__ float same_depth_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2)
+__device__ __forceinline__ float same_depth_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2,
+                                                   const uint32_t* occ_step = nullptr, float move_sec = 0.0f)
 {
     // every table value is loaded before the first use, so that the loads travel together
     const CfgRec a = sh.cfg[c], z = sh.cfg[c2];
@@ -430,6 +467,11 @@ __device__ __forceinline__ float same_depth_weight(const Batch& b, const PlanSha
     const uint32_t t_int = sh.tail_int[o + at], t_min = sh.tail_min[o + at];
     const uint32_t n0 = z.D <= a.D ? t_int : 0u, n01 = z.D <= a.D ? t_min : 0u;
     const uint32_t h0 = sh.tail_min[o];
+    if (move_sec != 0.0f) {
+        const uint32_t n3 = h0;  // the width of a target is at least 1
+        const float inter = inter_seconds_by_moves(occ_step + a.off, a.D, z.D, (uint32_t)b.S - n01 - n3, e1, move_sec);
+        return __fmul_rn(full, teff_with_inter(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, e0, e2, inter));
+    }
     if constexpr (kRounds) {
         const float round_sec = sh.rnd[3 * c2 + 2];
         if (round_sec != 0.0f) {
@@ -442,13 +484,15 @@ __device__ __forceinline__ float same_depth_weight(const Batch& b, const PlanSha
     return __fmul_rn(full, teff_from_counts(n0, n01, h0, z.D, (uint32_t)b.S, b.tau, e0, e1, e2));
 }
 
-// W_t[c][c'] for a source c inside the chunk that starts at bin `first`.
-__device__ __forceinline__ float transition_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2)
+// W_t[c][c'] for a source c inside the chunk that starts at bin `first`.  occ_step, move: see same_depth_weight.
+__device__ __forceinline__ float transition_weight(const Batch& b, const PlanShared& sh, int first, int c, int c2,
+                                                   const uint32_t* occ_step = nullptr, const float* move = nullptr)
 {
     if (sh.cold)  // nothing is running: the first configuration comes up at its re-partition cost
         return (c == c2 && sh.to_ok[c2]) ? __fmul_rn(sh.full[c2], sh.e[3 * c2 + 2]) : kNegInf;
     if (!sh.from_ok[c] || !sh.to_ok[c2]) return kNegInf;
     if (sh.cfg[c].P != sh.cfg[c2].P) return __fmul_rn(sh.full[c2], sh.e[3 * c2 + 2]);
+    if (move) return same_depth_weight<false>(b, sh, first, c, c2, occ_step, move[c2]);
     return b.cost_round ? same_depth_weight<true>(b, sh, first, c, c2) : same_depth_weight<false>(b, sh, first, c, c2);
 }
 
@@ -464,6 +508,8 @@ __global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const
     load_query_tables(b, q, cap, sh);
     load_step_flags(b, q, t, sh);
     float* Wt = W + ((int64_t)q * b.T + t) * b.C * b.C;
+    const uint32_t* occ_step = b.cost_move ? b.hist_occ + ((int64_t)q * b.T + t) * b.L : nullptr;
+    const float* move = b.cost_move ? b.cost_move + (int64_t)q * b.C : nullptr;
     for (int ch = 0; ch < sh.n_chunks; ++ch) {
         const int c_lo = sh.chunk_start[ch], c_hi = sh.chunk_start[ch + 1];
         load_chunk(b, q, t, c_lo, c_hi, hist_int, hist_min, sh);
@@ -472,7 +518,7 @@ __global__ void __launch_bounds__(256) transition_kernel(Batch b, int cap, const
         for (int i = threadIdx.x; i < cells; i += blockDim.x) {
             const int c = c_lo + i / b.C;
             const int c2 = i % b.C;
-            Wt[(int64_t)c * b.C + c2] = transition_weight(b, sh, first, c, c2);
+            Wt[(int64_t)c * b.C + c2] = transition_weight(b, sh, first, c, c2, occ_step, move);
         }
     }
 }

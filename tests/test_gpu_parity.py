@@ -660,9 +660,174 @@ def test_transfer_round_costs_in_the_replay_and_bad_values(pk):
     assert list(_np(pl.status)) == [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, 0]
 
 
+# ------------------------------------------------------------------ a hazard weight per instance
+
+def test_weighted_scenarios_one_by_one(pk):
+    """Successive weighted sampling instance by instance: every mask width, counts past the half (no complement
+    here), idle instances, multi-GPU instances, extreme weights."""
+    rng = pi.SplitMix64(777)
+    cases = [  # D, P, group, a_prev (-1: used pool), a_next, largest weight
+        (2, 3, 1, -1, 4, 9), (3, 4, 1, -1, 7, 255), (8, 4, 1, -1, 20, 3), (4, 8, 1, -1, 6, 16), (16, 4, 1, -1, 33, 255),
+        (8, 8, 1, -1, 60, 2), (2, 32, 1, -1, 31, 40), (16, 8, 1, -1, 100, 7), (4, 32, 1, -1, 20, 255),
+        (32, 8, 1, -1, 128, 5), (2, 128, 1, -1, 250, 100), (1, 256, 1, -1, 3, 255), (5, 7, 1, -1, 18, 12),
+        (11, 23, 1, -1, 140, 30), (3, 65, 1, -1, 111, 8), (64, 1, 1, 80, 41, 6), (3, 4, 1, 20, 13, 255),
+        (8, 16, 1, 200, 120, 9), (16, 4, 4, -1, 9, 20), (8, 4, 2, 30, 22, 200), (6, 2, 1, -1, 12, 4),
+        (6, 2, 1, -1, 0, 4), (7, 9, 1, -1, 62, 1), (1, 1, 1, -1, 0, 77),
+    ]
+    for D, P, g, a_prev, a_next, wmax in cases:
+        cfg = np.asarray([[D, P]], np.int32)
+        b = pi.custom_batch(256, cfg, [[max(a_prev, 0), a_next]], thr_per_pipeline=[1.0], n_scenarios=64, seed=23,
+                            group_size=g)
+        b.inst_weight = np.asarray([[rng.randint(1, wmax) for _ in range(256)]], np.uint8)
+        b.stream_id[:] = 4
+        p = pk.upload(b)
+        if a_prev >= 0:
+            p.flags = pk.PARCAE_POOL_ALL
+        ns, s0 = 200, 17
+        masks, n_int, d_min = pk.parcae_debug_sample(p, 0, 0, 0, s0, ns)
+        _sync()
+        om, oi, od = oracle.debug_sample(D, P, a_next, int(b.seed[0]), 4, 0, s0, ns, a_prev=a_prev, group=g,
+                                         zone=b.inst_weight[0], weight="instances")
+        assert np.array_equal(_np(masks, np.uint32), om), (D, P, g, a_prev, a_next)
+        assert np.array_equal(_np(n_int), oi) and np.array_equal(_np(d_min), od), (D, P, g, a_prev, a_next)
+
+
+def _check_all_outputs(pk, b, q, ev, pl, W, S, pool_all=False):
+    r = oracle.run_query(b, q, n_scenarios=S, n_threads=8, pool_all=pool_all)
+    assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int), "hist_int"
+    assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min), "hist_min"
+    if r.hist_occ is not None:
+        assert np.array_equal(_np(ev.hist_occ[q], np.uint32), r.hist_occ), "hist_occ"
+    assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f)
+    assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f)
+    assert np.all(np.abs(_np(ev.gain[q]) - r.tables.gain_d) <= REL * np.abs(r.tables.gain_d))
+    assert np.array_equal(_np(W[q]), r.W_f), "W"
+    fin = np.isfinite(r.W_d)
+    assert np.all(np.abs(_np(W[q])[fin] - r.W_d[fin]) <= REL * np.abs(r.W_d[fin]))
+    assert np.array_equal(_np(pl.bp[q]), r.plan.bp) and np.array_equal(_np(pl.F[q]), r.plan.F)
+    assert np.array_equal(_np(pl.plan[q]), r.plan.plan) and float(pl.objective[q]) == r.plan.objective
+    assert int(pl.status[q]) == (pk.PARCAE_OK if r.plan.feasible else pk.PARCAE_EINFEASIBLE)
+    return r
+
+
+@pytest.mark.parametrize("name,S,nq,pool_all", [("tiny", 256, 1, False), ("small", 1000, 1, False),
+                                                ("medium", 700, 1, True), ("large", 200, 1, False),
+                                                ("sweep", 500, 40, False), ("sweep", 300, 36, True)])
+def test_weighted_full_parity(pk, name, S, nq, pool_all):
+    b = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None).with_weights(max_weight=255 if nq == 36 else 8)
+    p = pk.upload(b)
+    if pool_all:
+        p.flags = pk.PARCAE_POOL_ALL
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in sorted({0, nq // 2, nq - 1}):
+        _check_all_outputs(pk, b, q, ev, pl, W, S, pool_all)
+    # the weights matter: the same batch drawn uniformly gives other histograms
+    u = pk.upload(pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None))
+    if pool_all:
+        u.flags = pk.PARCAE_POOL_ALL
+    ev_u = pk.parcae_liveput_eval(u)
+    _sync()
+    assert not np.array_equal(_np(ev_u.hist_min), _np(ev.hist_min))
+
+
+def test_weighted_replay_and_bad_weights(pk):
+    import torch
+    from oracle import replay as rp
+    nq, H = 3, 4
+    spec = pi.WorkloadSpec("replay", nq, 48, 12, 60.0, (2, 4, 8, 16), 2, 5, 12, 0.1, False, 2, 200)
+    b = pi.make_batch(spec, seed=91)
+    b_plan = b.take(range(nq))
+    b_plan.n_intervals = 6
+    b_plan.avail = np.ascontiguousarray(b.avail[:, :7])
+    b_plan = b_plan.with_weights(max_weight=20)
+    true, win = _replay_inputs(b, H, 2)
+    win = np.ascontiguousarray(win[:, :, :7])
+    p = pk.upload(b_plan)
+    for mode in (pk.PARCAE_REPLAY_PROACTIVE, pk.PARCAE_REPLAY_REACTIVE):
+        chosen, reward, total = pk.parcae_replay(p, torch.from_numpy(true).cuda(),
+                                                 torch.from_numpy(win).cuda() if mode == pk.PARCAE_REPLAY_PROACTIVE else None, mode)
+        _sync()
+        for q in range(nq):
+            r = rp.replay(b_plan, q, true[q], win[:, q, :], mode, n_threads=8)
+            assert np.array_equal(_np(chosen[q]), r.chosen) and np.array_equal(_np(reward[q]), r.reward), (mode, q)
+    bad = pi.workload("sweep", n_scenarios=64, n_queries=4).with_weights()
+    bad.inst_weight[2, 40] = 0
+    _, pl = pk.parcae_liveput_plan(pk.upload(bad))
+    _sync()
+    assert list(_np(pl.status)) == [0, 0, pk.PARCAE_EINVAL, 0]
+
+
+# ------------------------------------------------------------------ cost per instance that must receive state
+
+@pytest.mark.parametrize("name,S,nq,dense,extra", [("tiny", 256, 1, False, ""), ("small", 1000, 1, False, ""),
+                                                    ("medium", 600, 1, True, ""), ("large", 200, 1, False, "pool"),
+                                                    ("sweep", 500, 40, False, ""), ("sweep", 300, 33, False, "zones"),
+                                                    ("sweep", 300, 34, False, "weights"), ("small", 2500, 1, False, "pool")])
+def test_cost_per_moved_instance_full_parity(pk, name, S, nq, dense, extra):
+    """The third statistic (stage occupancies) from every sampling kernel variant, tables and weights with the move
+    cost, plans through the weights in memory for few and for many queries."""
+    b = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None, dense=dense).with_moves()
+    if extra == "zones":
+        b = b.with_zones(3)
+    if extra == "weights":
+        b = b.with_weights()
+    b.cost_move[:, ::5] = 0.0                  # some candidates keep the fixed inter-stage cost
+    p = pk.upload(b)
+    if extra == "pool":
+        p.flags = pk.PARCAE_POOL_ALL
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    pl2 = pk.parcae_plan_from_hist(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in sorted({0, nq // 2, nq - 1}):
+        r = _check_all_outputs(pk, b, q, ev, pl, W, S, extra == "pool")
+        assert r.hist_occ.sum() > 0
+    for f in ("F", "bp", "plan", "start", "objective", "status"):
+        assert np.array_equal(_np(getattr(pl2, f)), _np(getattr(pl, f))), f
+    # the move cost is felt
+    b0 = pi.workload(name, n_scenarios=S, n_queries=nq if nq > 1 else None, dense=dense)
+    if extra == "zones":
+        b0 = b0.with_zones(3)
+    if extra == "weights":
+        b0 = b0.with_weights()
+    p0 = pk.upload(b0)
+    if extra == "pool":
+        p0.flags = pk.PARCAE_POOL_ALL
+    W0 = pk.parcae_transition_weights(p0, ev.hist_int, ev.hist_min)
+    _sync()
+    w, w0 = _np(W[0]), _np(W0[0])
+    fin = np.isfinite(w0)
+    assert np.all(w[fin] <= w0[fin]) and np.any(w[fin] < w0[fin])
+
+
+def test_cost_per_moved_instance_multi_gpu_instances_and_bad_values(pk):
+    spec = pi.WorkloadSpec("quad", 3, 64, 6, 60.0, (2, 4, 8, 16), 2, 6, 16, 0.1, False, 2, 400)
+    walk = pi.make_batch(spec, seed=21)
+    cfg = pi.candidate_list(256, (2, 4, 8, 16), 2)
+    cfg = cfg[(cfg[:, 0] % 4 == 0) & (cfg[:, 0] * cfg[:, 1] <= 256) & (cfg[:, 0] <= 64)]
+    g = pi.custom_batch(64, cfg, walk.avail, thr_per_pipeline=[1.0 + 0.05 * p for _, p in cfg], n_scenarios=400, p_min=2,
+                        group_size=4, seed=8).with_moves()
+    p = pk.upload(g)
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in range(3):
+        _check_all_outputs(pk, g, q, ev, pl, W, 400)
+    bad = pi.workload("sweep", n_scenarios=64, n_queries=5).with_moves()
+    bad.cost_move[1, 3] = -1.0
+    bad.cost_move[2, 0] = np.inf
+    c = int(np.argmax((bad.configs[:, 0] - 1) * bad.configs[:, 1]))
+    bad.cost_move[3, c] = 100.0            # the dearest inter-stage migration would outlast the interval
+    _, pl = pk.parcae_liveput_plan(pk.upload(bad))
+    _sync()
+    assert list(_np(pl.status)) == [0, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, pk.PARCAE_EINVAL, 0]
+
+
 # ------------------------------------------------------------------ randomly drawn problems
 
-def _random_problem(rng):
+def _random_problem(rng, with_moves=True):
     """A small problem with every option drawn at random: sizes, depth list, pool, instance size, zones, round
     costs, start state, scenario count (mostly not a power of two), queries on either side of the planner switch."""
     group = [1, 1, 1, 2, 4][rng.randint(0, 4)]
@@ -691,10 +856,16 @@ def _random_problem(rng):
     for q in range(nq):
         b.cur_config[q] = [-2, -1, rng.randint(0, len(cfg) - 1)][rng.randint(0, 2)]
         b.stream_id[q] = rng.randint(0, 1000)
-    if rng.randint(0, 2) == 0:
+    draw = rng.randint(0, 3)
+    if draw == 0:
         b = b.with_zones(rng.randint(1, 4), seed=rng.randint(1, 999), max_weight=[3, 255][rng.randint(0, 1)])
-    if rng.randint(0, 2) == 0:
+    elif draw == 1:
+        b = b.with_weights(seed=rng.randint(1, 999), max_weight=[2, 16][rng.randint(0, 1)])
+    refine = rng.randint(0, 3)
+    if refine == 0:
         b = b.with_rounds(0.0, 25.0, seed=rng.randint(1, 999))
+    elif refine == 1 and with_moves:
+        b = b.with_moves(seed=rng.randint(1, 999))
     return b, rng.randint(0, 1) == 1
 
 
@@ -709,11 +880,13 @@ def test_random_problems_match_the_oracle(pk):
         W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
         _sync()
         tag = (case, b.n_instances, b.n_configs, b.n_queries, b.n_intervals, b.n_scenarios, b.group_size, b.n_zones,
-               b.cost_round is not None, pool_all)
+               b.cost_round is not None, b.inst_weight is not None, b.cost_move is not None, pool_all)
         for q in range(b.n_queries):
             r = oracle.run_query(b, q, n_threads=8, pool_all=pool_all)
             assert np.array_equal(_np(ev.hist_int[q], np.uint32), r.hist_int), tag
             assert np.array_equal(_np(ev.hist_min[q], np.uint32), r.hist_min), tag
+            if r.hist_occ is not None:
+                assert np.array_equal(_np(ev.hist_occ[q], np.uint32), r.hist_occ), tag
             assert np.array_equal(_np(ev.liveput[q]), r.tables.liveput_f), tag
             assert np.array_equal(_np(ev.teff[q]), r.tables.teff_f) and np.array_equal(_np(ev.gain[q]), r.tables.gain_f), tag
             assert np.array_equal(_np(W[q]), r.W_f), tag
@@ -778,7 +951,7 @@ def test_replay_on_randomly_drawn_problems(pk):
     from oracle import replay as rp
     rng = pi.SplitMix64(0xBEEF)
     for case in range(16):
-        b, pool_all = _random_problem(rng)
+        b, pool_all = _random_problem(rng, with_moves=False)       # the replay takes no cost per moved instance
         nq, T, N = b.n_queries, b.n_intervals, b.n_instances
         H = rng.randint(1, 5)
         true = np.asarray([[rng.randint(0, N) for _ in range(H + 1)] for _ in range(nq)], np.int32)

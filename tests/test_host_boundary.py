@@ -88,8 +88,13 @@ def test_structure_size_field():
     assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
     prob.struct_size = pk.parcae_problem.profile.offset      # a caller built before the profiling hooks existed
     prob.profile = ct.cast(0xdead0000, ct.POINTER(pk.parcae_profile))   # must not be read
+    prob.cost_move = 0x1000                                   # nor this (without its histogram it would be refused)
     assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
     prob.profile = None
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    prob.struct_size = full
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL   # cost_move without hist_occ
+    prob.cost_move = None
     prob.struct_size = full + 64                              # a newer caller
     assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
     for bad in (0, 4, pk.parcae_problem.cost_round.offset):
@@ -147,6 +152,35 @@ def test_zone_and_candidate_limits_are_checked_on_the_host():
                                      None) == pk.PARCAE_EINVAL
     assert lib.parcae_liveput_plan(ct.byref(big), fake, fake, None, None, None, None, None, fake, None, None, None,
                                    ws, out.value, None) == pk.PARCAE_EINVAL
+
+
+def test_weights_per_instance_and_cost_per_move_are_checked_on_the_host():
+    lib = pk.load_library()
+    out = ct.c_size_t(0)
+    fake = 0x1000
+    prob, keep = _problem([(1, 2), (2, 2), (1, 4)], nq=40)
+    plain = ct.c_size_t(0)
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(plain)) == pk.PARCAE_OK
+    prob.inst_weight = fake
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    prob.n_zones, prob.zone, prob.zone_weight = 2, fake, fake          # zones and instance weights exclude each other
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.n_zones = 0
+    prob.cost_move = fake                                               # needs its histogram
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.hist_occ = fake
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_OK
+    assert out.value > plain.value                                      # the weights go through the workspace
+    prob.cost_round = fake                                              # two refinements of the same cost
+    assert lib.parcae_workspace_bytes(ct.byref(prob), ct.byref(out)) == pk.PARCAE_EINVAL
+    prob.cost_round = None
+    need = ct.c_size_t(0)
+    assert lib.parcae_replay_workspace_bytes(ct.byref(prob), 3, pk.PARCAE_REPLAY_PROACTIVE, ct.byref(need)) == pk.PARCAE_OK
+    assert lib.parcae_replay(ct.byref(prob), 3, fake, fake, pk.PARCAE_REPLAY_PROACTIVE, fake, fake, fake, None, 0x100000,
+                             need.value, None) == pk.PARCAE_EINVAL      # the replay takes no cost per moved instance
+    deep, keep2 = _problem([(1, 256)], N=256, S=1 << 24)
+    deep.cost_move, deep.hist_occ = fake, fake                          # S * P would overflow a 32-bit bin
+    assert lib.parcae_workspace_bytes(ct.byref(deep), ct.byref(out)) == pk.PARCAE_EINVAL
 
 
 def test_reactive_replay_needs_no_planner():
