@@ -146,7 +146,7 @@ def cpu_baseline(batch, budget_queries: int, pool_all: bool = False, max_threads
 
 
 def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, pool_all=False, zones=0, rounds=False,
-            graph=False):
+            weights=False, moves=False, graph=False):
     """GPU legs of one workload: whole steps (wall clock), the sampling kernel and the plan (HIP events recorded by
     the library around them), the plan alone from stored histograms.  Returns (result dict, batch)."""
     import torch
@@ -155,6 +155,10 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
         batch = batch.with_zones(zones)
     if rounds:
         batch = batch.with_rounds()
+    if weights:
+        batch = batch.with_weights()
+    if moves:
+        batch = batch.with_moves()
     prob = pk.upload(batch, device="cuda:0")
     if pool_all:
         prob.flags = pk.PARCAE_POOL_ALL
@@ -221,8 +225,9 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
         graph_ms = (time.perf_counter() - t2) / steps * 1e3
 
     status = pl_out.status.cpu().numpy()
-    tag = batch.name + ("+pool-all" if pool_all else "") + (f"+zones{zones}" if zones else "") + ("+rounds" if rounds else "")
-    plain = not (dense or pool_all or zones or rounds)
+    tag = (batch.name + ("+pool-all" if pool_all else "") + (f"+zones{zones}" if zones else "") +
+           ("+rounds" if rounds else "") + ("+weights" if weights else "") + ("+moves" if moves else ""))
+    plain = not (dense or pool_all or zones or rounds or weights or moves)
     counter_tag = (batch.name + (f"x{nq}" if queries else "")) if plain else ""
     traffic, valu_insts = kernel_counters(counter_tag)
     achieved = alg_ops / kern_s
@@ -270,6 +275,9 @@ def main():
                     help="spread the instances over this many zones of unequal preemption hazard (0 = uniform)")
     ap.add_argument("--rounds", action="store_true",
                     help="inter-stage migration cost by state-transfer rounds (a per-candidate cost per further round)")
+    ap.add_argument("--weights", action="store_true", help="a hazard weight per instance (preemption not uniform)")
+    ap.add_argument("--moves", action="store_true",
+                    help="inter-stage migration cost per instance that must receive state (third histogram)")
     ap.add_argument("--graph", action="store_true",
                     help="also time replays of a HIP graph that captured one whole call (reported as "
                          "graph_replay_ms_per_step next to the eager figures; the call enqueues kernels only)")
@@ -307,7 +315,8 @@ def main():
 
     events = HipEvents()
     head, batch = measure(pk, pi, events, args.workload, args.steps, args.warmup, dense=args.dense, queries=args.queries,
-                          pool_all=args.pool_all, zones=args.zones, rounds=args.rounds, graph=args.graph)
+                          pool_all=args.pool_all, zones=args.zones, rounds=args.rounds, weights=args.weights,
+                          moves=args.moves, graph=args.graph)
     out = {
         "metric": "liveput_evals_per_sec",
         # scenarios that go through the sampler and the reducer, per second of the whole step; the units whose
@@ -347,7 +356,8 @@ def main():
     if "graph_replay_ms_per_step" in head:
         out["graph_replay_ms_per_step"] = head["graph_replay_ms_per_step"]
 
-    plain_sweep = args.workload == "sweep" and not (args.dense or args.pool_all or args.zones or args.rounds or args.queries)
+    plain_sweep = args.workload == "sweep" and not (args.dense or args.pool_all or args.zones or args.rounds or
+                                                    args.weights or args.moves or args.queries)
     if plain_sweep and not args.no_others:
         others = []
         for name, nq, k in (("large", None, 10), ("medium", 256, 5), ("large", 256, 2), ("medium", None, 20)):

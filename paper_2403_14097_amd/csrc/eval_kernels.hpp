@@ -324,7 +324,7 @@ enum DrawKind { kDrawUniform = 0, kDrawZoned = 1, kDrawWeighted = 2 };
 // equal-probability assumption replaced by an estimate per instance).
 struct WeightCtx {
     uint32_t packed;        // lane L: the weights of instances 4L .. 4L + 3, one per byte, 0 beyond the pool
-    const uint8_t* bytes;   // LDS [260]: the same weights, one per instance, for per-lane look-ups
+    const uint8_t* bytes;   // LDS [260], 4-byte aligned: the same weights, one per instance, for per-lane look-ups
     uint32_t total;         // sum over the pool
 };
 
@@ -358,37 +358,57 @@ __device__ __forceinline__ WeightCtx weight_setup(const Batch& b, int q, int M, 
 
 // Preempted set of scenario s by successive weighted sampling without replacement: k times, word i of sequence
 // 0xFFFE scaled to the weight still there picks a point, and the first instance (ascending) at which the running
-// sum of the weights still there exceeds the point goes.  All lanes walk the instances in step (the weight of
-// instance j is a scalar), each with its own set: the instance that goes is the number of instances whose running
-// sum does not exceed the point, because running sums never decrease.
+// sum of the weights still there exceeds the point goes.  All lanes walk the pool in step (the weights of a group of
+// four instances are one scalar word), each with its own set.  Running sums never decrease, so the number of groups
+// whose running sum does not exceed the point is the group of the instance that goes: a first pass adds the
+// weights still there four at a time (the four "still there" bits spread to bytes, one dot product per group), a
+// second pass walks the four instances of that group.
 template <int NW>
 __device__ __forceinline__ void sample_mask_weighted(Mask<NW>& mask, const WeightCtx& wc, int M, int k, uint32_t s,
                                                      uint32_t unit, uint32_t stream_id, const PhiloxKeys& ks)
 {
     mask.clear();
     uint32_t total = wc.total;
+    const uint32_t* by_four = reinterpret_cast<const uint32_t*>(wc.bytes);
     for (int i0 = 0; i0 < k; i0 += 4) {
         const Philox4 blk = philox4x32_10(s, 0xFFFE0000u + (uint32_t)(i0 >> 2), unit, stream_id, ks);
         static_for<4>([&](auto x) {
             if (i0 + x.value < k) {
                 const uint32_t point = __umulhi(blk.x[x.value], total);
-                uint32_t running = 0u, victim = 0u;
+                uint32_t running = 0u, group = 0u, before = 0u;
                 static_for<NW>([&](auto W) {
                     const uint32_t there = ~mask.w[W.value];
-                    int quads = (M - 32 * W.value + 3) >> 2;  // packed weight words that cover instances of this mask word
-                    quads = quads < 0 ? 0 : (quads > 8 ? 8 : quads);
-                    for (int p = 0; p < quads; ++p) {
-                        const uint32_t four = (uint32_t)__builtin_amdgcn_readlane((int)wc.packed, 8 * W.value + p);
-                        static_for<4>([&](auto y) {
-                            const uint32_t w = (four >> (8 * y.value)) & 0xffu;
-                            const uint32_t on = (uint32_t)__builtin_amdgcn_sbfe((int)there, (uint32_t)(4 * p + y.value), 1u);
-                            running += on & w;
-                            victim += running <= point ? 1u : 0u;
-                        });
-                    }
+                    // all eight groups of the word, unrolled (groups past the pool weigh nothing, and the running
+                    // sum has passed the point by then)
+                    static_for<8>([&](auto p) {
+                        const uint32_t four = (uint32_t)__builtin_amdgcn_readlane((int)wc.packed, 8 * W.value + p.value);
+                        // bits 4p .. 4p + 3 of `there`, one per byte: b0 + 2 b1 + 4 b2 + 8 b3 times (1 + 2^7 + 2^14 + 2^21)
+                        const uint32_t nibble = (there >> (4 * p.value)) & 0xfu;
+                        const uint32_t ones = (nibble * 0x00204081u) & 0x01010101u;
+                        running = __builtin_amdgcn_udot4(four, ones, running, false);
+                        const bool below = running <= point;
+                        group += below ? 1u : 0u;
+                        before = below ? running : before;
+                    });
                 });
-                mask.set(victim);
-                total -= wc.bytes[victim];
+                // the four instances of that group (a group index past the pool cannot come out of valid weights;
+                // the table has a zero entry there)
+                const uint32_t four = by_four[group < 64u ? group : 64u];
+                uint32_t there = 0u;
+                static_for<NW>([&](auto W) { there = (group >> 3) == (uint32_t)W.value ? ~mask.w[W.value] : there; });
+                const uint32_t nibble = (there >> (4u * (group & 7u))) & 0xfu;
+                uint32_t inside = 0u, went = 0u;
+                running = before;
+                static_for<4>([&](auto y) {
+                    const uint32_t w = (four >> (8 * y.value)) & 0xffu;
+                    const uint32_t on = 0u - ((nibble >> y.value) & 1u);
+                    running += on & w;
+                    const bool below = running <= point;
+                    inside += below ? 1u : 0u;
+                    went = (below || went != 0u) ? went : w;  // the weight at which the running sum first exceeds the point
+                });
+                mask.set(4u * group + inside);
+                total -= went;
             }
         });
     }
@@ -890,7 +910,7 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
     __shared__ uint8_t zone_perm[kZoned ? kWaves : 1][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kZoned ? kWaves : 1][kMaxZones * 8];
-    __shared__ uint8_t weight_bytes[kWeighted ? kWaves : 1][260];
+    __shared__ __align__(4) uint8_t weight_bytes[kWeighted ? kWaves : 1][260];
     const int lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
     uint32_t* bins = bins_all[wave];
@@ -1040,7 +1060,7 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     __shared__ uint32_t lmask[8 * kEvalThreads];
     __shared__ uint8_t zone_perm[kEvalThreads / kWave][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kEvalThreads / kWave][kMaxZones * 8];
-    __shared__ uint8_t weight_bytes[kEvalThreads / kWave][260];
+    __shared__ __align__(4) uint8_t weight_bytes[kEvalThreads / kWave][260];
     const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
     const CfgRec cr = b.cfg[c];
     int M, k;
