@@ -571,30 +571,46 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
         const float fl = is_cand ? Fcur : kNegInf;
         const float top = __int_as_float(lane_value(wave_prefix_max(__float_as_int(fl)), kWave - 1));
         const unsigned long long at_top = __ballot(is_cand && fl == top && top > kNegInf);
-        if (lane == 0) {
-            int last = at_top ? (int)__builtin_ctzll(at_top) : -1;
-            int32_t* pl = plan + (int64_t)q * T;
-            int st = 0;
-            if (last < 0) {
-                for (int t = 0; t < T; ++t) pl[t] = -1;
-                if (start) start[q] = -1;
-                st = einfeasible;
-            } else {
-                pl[T - 1] = last;
-                for (int t = T - 1; t >= 0; --t) {
-                    int prev;
-                    if (w.bp16) {
-                        const uint16_t v = w.bp16[t * C + last];
-                        prev = v == kNoPred16 ? -1 : (int)v;
-                    } else {
-                        prev = bpq[(int64_t)t * C + last];
+        int last = at_top ? (int)__builtin_ctzll(at_top) : -1;  // the same in every lane
+        int32_t* pl = plan + (int64_t)q * T;
+        int st = 0;
+        if (last < 0) {
+            for (int t = lane; t < T; t += kWave) pl[t] = -1;
+            if (lane == 0 && start) start[q] = -1;
+            st = einfeasible;
+        } else if (w.bp16) {
+            // walk back with the back-pointers of a step spread over the lanes (lane = candidate): following a
+            // pointer is one lane read, the row of the next step is loaded while the current one is followed, and
+            // lane t collects plan[t] so that the plan goes out in whole rows
+            for (int hi = T; hi > 0; hi -= kWave) {          // steps [lo, hi) at a time, latest first
+                const int lo = hi > kWave ? hi - kWave : 0;
+                int mine = -1;
+                for (int t = hi - 1; t >= lo; t -= 4) {      // four rows per round of loads
+                    int row[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) row[j] = (int)w.bp16[(t - j > 0 ? t - j : 0) * C + lc];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (t - j < lo) break;
+                        mine = lane == t - j - lo ? last : mine;  // plan[t] = the candidate the walk is at
+                        const int prev = __builtin_amdgcn_readlane(row[j], last);
+                        last = prev == (int)kNoPred16 ? 0 : prev;  // cannot happen on a finite path; keeps the walk in bounds
                     }
-                    if (prev < 0) prev = 0;  // cannot happen on a finite path; keeps the walk in bounds
-                    if (t >= 1) pl[t - 1] = prev;
-                    else if (start) start[q] = prev;
-                    last = prev;
                 }
+                if (lo + lane < hi) pl[lo + lane] = mine;
             }
+            if (lane == 0 && start) start[q] = last;
+        } else if (lane == 0) {
+            pl[T - 1] = last;
+            for (int t = T - 1; t >= 0; --t) {
+                int prev = bpq[(int64_t)t * C + last];
+                if (prev < 0) prev = 0;  // cannot happen on a finite path; keeps the walk in bounds
+                if (t >= 1) pl[t - 1] = prev;
+                else if (start) start[q] = prev;
+                last = prev;
+            }
+        }
+        if (lane == 0) {
             if (objective) objective[q] = top;
             if (status) status[q] = bad_inputs ? einval : st;
         }
