@@ -8,6 +8,7 @@
 #pragma once
 
 #include "device_common.hpp"
+#include "eval_launch.hpp"
 
 namespace parcae {
 
@@ -857,6 +858,78 @@ __global__ void __launch_bounds__(kBuildThreads) build_work_kernel(Batch b, Work
     if (need) wq.list[wave_base[wave] + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = (uint32_t)u;
 }
 
+// Small problems: everything that has to happen before the sampling kernel, in ONE workgroup and one launch.  The
+// candidate table arrives in the kernel's arguments and is written to the workspace for the kernels that follow; a
+// thread per unit clears the unit's histogram rows (or writes their single bin), and the units that need sampling
+// are appended to the work list by ballot and prefix inside the workgroup, so no counter has to be reset first.
+constexpr int kStageThreads = 1024;
+constexpr int kStageMaxConfigs = 64;
+constexpr int64_t kStageMaxUnits = 2 * kStageThreads;
+constexpr int64_t kStageMaxBins = 32 * kStageThreads;  // histogram words a thread writes one by one: few, or the launches pay
+struct StageTable {
+    CfgRec rec[kStageMaxConfigs];
+};
+
+__global__ void __launch_bounds__(kStageThreads) stage_small_kernel(Batch b, StageTable table, CfgRec* __restrict__ cfg_out,
+                                                                    WorkQueue wq, uint32_t* __restrict__ hist_int,
+                                                                    uint32_t* __restrict__ hist_min)
+{
+    constexpr int kWaves = kStageThreads / kWave;
+    __shared__ CfgRec cfg[kStageMaxConfigs];
+    __shared__ uint32_t wave_count[kWaves];
+    __shared__ uint32_t wave_base[kWaves];
+    __shared__ uint32_t listed;
+    const int tid = (int)threadIdx.x;
+    const int lane = lane_id();
+    const int wave = tid / kWave;
+    if (tid < b.C) {
+        cfg[tid] = table.rec[tid];
+        cfg_out[tid] = table.rec[tid];
+    }
+    if (tid < kQueueShards) wq.next[tid * kShardStride] = 0u;
+    if (tid == 0) listed = 0u;
+    __syncthreads();
+    const int64_t n_units = (int64_t)b.nq * b.T * b.C;
+    for (int64_t first = 0; first < n_units; first += kStageThreads) {
+        const int64_t u = first + tid;
+        bool need = false;
+        if (u < n_units) {
+            const int c = (int)(u % b.C);
+            const int64_t qt = u / b.C;
+            const int t = (int)(qt % b.T);
+            const int q = (int)(qt / b.T);
+            const CfgRec cr = cfg[c];
+            int M, k, bin;
+            unit_pool(b, q, t, cr.D, cr.P, M, k);
+            const bool closed = unit_closed_form(cr.D / b.group, cr.P, M, k, bin);
+            need = !closed;
+            const int at = closed ? bin * b.group : -1;
+            const int64_t row = qt * b.L + cr.off;
+            for (int j = 0; j <= cr.D; ++j) {
+                const uint32_t v = j == at ? (uint32_t)b.S : 0u;
+                hist_int[row + j] = v;
+                hist_min[row + j] = v;
+                if (b.hist_occ) b.hist_occ[row + j] = (j == at && bin >= 1) ? (uint32_t)b.S * (uint32_t)cr.P : 0u;
+            }
+        }
+        const unsigned long long votes = __ballot(need);
+        if (lane == 0) wave_count[wave] = (uint32_t)__popcll(votes);
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t sum = listed;
+            for (int w = 0; w < kWaves; ++w) {
+                wave_base[w] = sum;
+                sum += wave_count[w];
+            }
+            listed = sum;
+        }
+        __syncthreads();
+        if (need) wq.list[wave_base[wave] + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = (uint32_t)u;
+    }
+    __syncthreads();
+    if (tid == 0) *wq.count = listed;
+}
+
 // Draws scenario s of a unit into registers, by the path that fits the unit's size.
 template <int NW>
 __device__ __forceinline__ void draw_scenario(Mask<NW>& mask, uint32_t* lds_col, int M, int k, uint32_t s,
@@ -899,7 +972,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
 // kDraw selects how scenarios are drawn and kMoves adds the stage-occupancy statistic (kernels of their own, so
 // the plain one keeps its registers).
 template <int kDraw, bool kMoves>
-__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu((kDraw != kDrawUniform || kMoves) ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_chunks, int chunk_len,
+__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu((kDraw != kDrawUniform || kMoves) ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_resident_waves,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {
@@ -915,7 +988,11 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
     uint32_t* bins = bins_all[wave];
     uint32_t* lds_col = lmask + threadIdx.x;
-    const uint32_t total = *wq.count * (uint32_t)n_chunks;
+    // the length of an item follows from the number of units on the list (the same value in every wave)
+    const uint32_t n_listed = *wq.count;
+    const int chunk_len = pick_chunk_len((int64_t)n_listed, b.S, b.N, (int64_t)n_resident_waves);
+    const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
+    const uint32_t total = n_listed * (uint32_t)n_chunks;
     // Shard s holds the items g with g mod kQueueShards == s (neighbouring items cost about the same, whole ranges of
     // the list do not: interleaving gives every shard the same mix).  A wave claims `batch` items of its current
     // shard at a time; that is its home shard until it runs dry.  Then the wave looks at all shard counters AT ONCE
@@ -923,21 +1000,28 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     // different waves; a walk over the shards one probe after the other would cost a memory round trip per shard in
     // every wave at the end of the launch.  A wave leaves when no shard has items left; counters only grow, so that
     // point is reached.
+    // The first item of a wave is the one with the wave's own index: nothing to claim, so a launch with no more items
+    // than waves touches no counter at all (claims of single items by thousands of waves at once would queue up at
+    // the few counters).  The shards hand out the items past those.
+    const uint32_t n_waves = (uint32_t)gridDim.x * kWaves;
     auto shard_size = [&](uint32_t s) { return s < total ? (total - s + kQueueShards - 1u) / kQueueShards : 0u; };
-    uint32_t batch = total / ((uint32_t)gridDim.x * kWaves * kClaimsPerWave);
+    auto shard_first = [&](uint32_t s) { return s < n_waves ? (n_waves - s + kQueueShards - 1u) / kQueueShards : 0u; };
+    uint32_t batch = total / (n_waves * kClaimsPerWave);
     batch = batch < 1u ? 1u : (batch > 64u ? 64u : batch);
     const uint32_t wave_id = (uint32_t)blockIdx.x * kWaves + wave;
     uint32_t shard = wave_id % kQueueShards;
     uint32_t slot = 0u, slot_end = 0u;  // position inside the shard: item = slot * kQueueShards + shard
+    bool own_item = wave_id < total;
 
     for (;;) {
         bool drained = false;
-        while (slot == slot_end) {
+        while (!own_item && slot == slot_end) {
             const uint32_t size = shard_size(shard);
-            if (size > 0u) {
+            const uint32_t skip = shard_first(shard);
+            if (size > skip) {
                 uint32_t got = 0u;
                 if (lane == 0) got = atomicAdd(&wq.next[shard * kShardStride], batch);
-                const uint32_t first = __builtin_amdgcn_readfirstlane(got);
+                const uint32_t first = __builtin_amdgcn_readfirstlane(got) + skip;
                 if (first < size) {
                     slot = first;
                     slot_end = first + batch < size ? first + batch : size;
@@ -948,7 +1032,7 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
             if (lane < kQueueShards) {
                 const uint32_t taken =
                     __hip_atomic_load(&wq.next[lane * kShardStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                has_items = taken < shard_size((uint32_t)lane);
+                has_items = taken + shard_first((uint32_t)lane) < shard_size((uint32_t)lane);
             }
             const unsigned long long open = __ballot(has_items);
             if (open == 0ull) {
@@ -961,8 +1045,14 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
             shard = (uint32_t)__builtin_ctzll(rest);
         }
         if (drained) break;
-        const uint32_t item = slot * kQueueShards + shard;
-        ++slot;
+        uint32_t item;
+        if (own_item) {
+            item = wave_id;
+            own_item = false;
+        } else {
+            item = slot * kQueueShards + shard;
+            ++slot;
+        }
         const uint32_t unit_global = wq.list[item / (uint32_t)n_chunks];
         const int chunk = (int)(item % (uint32_t)n_chunks);
         const int tc = (int)(unit_global % (uint32_t)(b.T * b.C));

@@ -184,10 +184,8 @@ __global__ void __launch_bounds__(128) table_slice_kernel(TableSlice slice, int 
     if (i < count) dst[i] = slice.rec[i];
 }
 
-// Writes the candidate table into the workspace and, if asked, checks the device inputs of every query
-// (valid[q] in the workspace; the wave planner checks its own query and needs no such launch).
-int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const Batch& b, void* ws, hipStream_t st,
-                 bool validate = true)
+// Writes the candidate table into the workspace.
+int write_table(const CfgRec* table, size_t table_len, const Layout& lay, void* ws, hipStream_t st)
 {
     CfgRec* dst = reinterpret_cast<CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off);
     for (size_t first = 0; first < table_len; first += kTableSlice) {
@@ -198,10 +196,24 @@ int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const
         table_slice_kernel<<<dim3(1), dim3(128), 0, st>>>(slice, count, dst + first);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     }
-    if (!validate) return PARCAE_OK;
+    return PARCAE_OK;
+}
+
+// Checks the device inputs of every query (valid[q] in the workspace; needs the table in the workspace).
+int check_inputs(const Layout& lay, const Batch& b, void* ws, hipStream_t st)
+{
     int32_t* valid = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(ws) + lay.valid_off);
     parcae::validate_kernel<<<dim3((unsigned)b.nq), dim3(256), 0, st>>>(b, valid);
     return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
+}
+
+// Table into the workspace and, if asked, the input check (the wave planner checks its own query and needs none).
+int stage_inputs(const CfgRec* table, size_t table_len, const Layout& lay, const Batch& b, void* ws, hipStream_t st,
+                 bool validate = true)
+{
+    const int rc = write_table(table, table_len, lay, ws, st);
+    if (rc != PARCAE_OK || !validate) return rc;
+    return check_inputs(lay, b, ws, st);
 }
 
 int stage_inputs(const std::vector<CfgRec>& table, const Layout& lay, const Batch& b, void* ws, hipStream_t st,
@@ -232,46 +244,76 @@ parcae::WorkQueue make_queue(const Layout& lay, void* ws)
     return wq;
 }
 
+// What a call of launch_eval does besides the sampling itself.
+struct EvalOpts {
+    const CfgRec* table = nullptr;  // host copy of the candidate table if the workspace does not hold it yet
+    bool validate = false;          // with `table`: check the device inputs of every query once the table is in place
+    bool tables_later = false;      // the liveput tables are written by a kernel the caller launches afterwards
+};
+
 int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void* ws, uint32_t* hist_int,
-                uint32_t* hist_min, float* liveput, float* teff, float* gain, int32_t* status, hipStream_t st)
+                uint32_t* hist_min, float* liveput, float* teff, float* gain, int32_t* status, hipStream_t st,
+                const EvalOpts& opts = EvalOpts())
 {
     const int64_t n_units = (int64_t)b.nq * b.T * b.C;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return PARCAE_EHIP;
-    const int chunk_len = parcae::pick_chunk_len(n_units, b.S, b.N, (int64_t)cus * parcae::kEvalWavesPerCu);
-    const int n_chunks = (b.S + chunk_len - 1) / chunk_len;
-    if (n_units * n_chunks >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counter to overshoot
+    const bool moves = b.cost_move != nullptr;
+    const bool wide = moves || b.inst_weight || b.n_zones > 0;  // the variants with the larger register budget
+    const int resident_waves = cus * (wide ? parcae::kEvalWavesPerCuWide : parcae::kEvalWavesPerCu);
+    const int64_t max_items = parcae::max_eval_items(n_units, b.S, resident_waves);
+    if (max_items >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counters to overshoot
     const parcae::WorkQueue wq = make_queue(lay, ws);
 
-    const int64_t elems = (int64_t)b.nq * b.T * b.L;
-    int64_t prep_blocks = (elems + 255) / 256;
-    if (prep_blocks > 65536) prep_blocks = 65536;
-    parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, wq, hist_int, hist_min);
-    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
-    parcae::build_work_kernel<<<dim3((unsigned)((n_units + parcae::kBuildThreads - 1) / parcae::kBuildThreads)),
-                                dim3(parcae::kBuildThreads), 0, st>>>(b, wq);
-    if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    // a small problem whose table still has to reach the workspace: table, histogram rows and work list in one launch
+    const bool one_launch = opts.table && b.C <= parcae::kStageMaxConfigs && n_units <= parcae::kStageMaxUnits &&
+                            (int64_t)b.nq * b.T * b.L <= parcae::kStageMaxBins;
+    if (one_launch) {
+        parcae::StageTable tab;
+        std::memcpy(tab.rec, opts.table, sizeof(CfgRec) * (size_t)b.C);
+        if (b.C < parcae::kStageMaxConfigs)
+            std::memset(tab.rec + b.C, 0, sizeof(CfgRec) * (size_t)(parcae::kStageMaxConfigs - b.C));
+        parcae::stage_small_kernel<<<dim3(1), dim3(parcae::kStageThreads), 0, st>>>(
+            b, tab, reinterpret_cast<CfgRec*>(static_cast<unsigned char*>(ws) + lay.cfg_off), wq, hist_int, hist_min);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    } else if (opts.table) {
+        const int rc = write_table(opts.table, (size_t)b.C, lay, ws, st);
+        if (rc != PARCAE_OK) return rc;
+    }
+    if (opts.table && opts.validate) {
+        const int rc = check_inputs(lay, b, ws, st);
+        if (rc != PARCAE_OK) return rc;
+    }
+    if (!one_launch) {
+        const int64_t elems = (int64_t)b.nq * b.T * b.L;
+        int64_t prep_blocks = (elems + 255) / 256;
+        if (prep_blocks > 65536) prep_blocks = 65536;
+        parcae::prep_hist_kernel<<<dim3((unsigned)prep_blocks), dim3(256), 0, st>>>(b, wq, hist_int, hist_min);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+        parcae::build_work_kernel<<<dim3((unsigned)((n_units + parcae::kBuildThreads - 1) / parcae::kBuildThreads)),
+                                    dim3(parcae::kBuildThreads), 0, st>>>(b, wq);
+        if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
+    }
 
-    const int64_t eval_blocks = parcae::eval_grid_blocks(cus, n_units * n_chunks);
+    const int64_t eval_blocks = parcae::eval_grid_blocks(cus, max_items);
     if (p->profile && record(p->profile->event_before_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
     const dim3 grid((unsigned)eval_blocks), block(parcae::kEvalThreads);
-    const bool moves = b.cost_move != nullptr;
     if (b.inst_weight) {
-        if (moves) parcae::eval_hist_kernel<parcae::kDrawWeighted, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
-        else parcae::eval_hist_kernel<parcae::kDrawWeighted, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawWeighted, true><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawWeighted, false><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
     } else if (b.n_zones > 0) {
-        if (moves) parcae::eval_hist_kernel<parcae::kDrawZoned, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
-        else parcae::eval_hist_kernel<parcae::kDrawZoned, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawZoned, true><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawZoned, false><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
     } else {
-        if (moves) parcae::eval_hist_kernel<parcae::kDrawUniform, true><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
-        else parcae::eval_hist_kernel<parcae::kDrawUniform, false><<<grid, block, 0, st>>>(b, wq, n_chunks, chunk_len, hist_int, hist_min);
+        if (moves) parcae::eval_hist_kernel<parcae::kDrawUniform, true><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
+        else parcae::eval_hist_kernel<parcae::kDrawUniform, false><<<grid, block, 0, st>>>(b, wq, resident_waves, hist_int, hist_min);
     }
     if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
     if (p->profile && record(p->profile->event_after_sampling, st) != PARCAE_OK) return PARCAE_EHIP;
 
-    if (liveput || teff || gain) {
+    if ((liveput || teff || gain) && !opts.tables_later) {
         parcae::finalise_kernel<<<dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, st>>>(b, hist_int, hist_min,
                                                                                                  liveput, teff, gain);
         if (hipGetLastError() != hipSuccess) return PARCAE_EHIP;
@@ -368,23 +410,27 @@ bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layo
 
 int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
                         const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start,
-                        float* objective, int32_t* status, hipStream_t st);
+                        float* objective, int32_t* status, hipStream_t st, const parcae::TablesOut& tables);
 
-// The dynamic program, bracketed by the caller's profiling events if there are any.
+// The dynamic program, bracketed by the caller's profiling events if there are any.  `tables` (liveput tables to
+// write in the same launch) may be given only where takes_wave_planner() holds.
 int launch_plan(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
                 const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start, float* objective,
-                int32_t* status, hipStream_t st, const parcae_profile* prof = nullptr)
+                int32_t* status, hipStream_t st, const parcae_profile* prof = nullptr,
+                const parcae::TablesOut& tables = parcae::TablesOut{nullptr, nullptr, nullptr})
 {
     if (prof && record(prof->event_before_plan, st) != PARCAE_OK) return PARCAE_EHIP;
-    const int rc = launch_plan_kernels(b, table, lay, ws, hist_int, hist_min, F, bp, plan, start, objective, status, st);
+    const int rc =
+        launch_plan_kernels(b, table, lay, ws, hist_int, hist_min, F, bp, plan, start, objective, status, st, tables);
     if (rc != PARCAE_OK) return rc;
     return prof ? record(prof->event_after_plan, st) : PARCAE_OK;
 }
 
 int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
                         const uint32_t* hist_min, float* F, int32_t* bp, int32_t* plan, int32_t* start,
-                        float* objective, int32_t* status, hipStream_t st)
+                        float* objective, int32_t* status, hipStream_t st, const parcae::TablesOut& tables)
 {
+    const bool with_tables = tables.liveput || tables.teff || tables.gain;
     unsigned char* base = static_cast<unsigned char*>(ws);
     int32_t* bp_use = bp ? bp : reinterpret_cast<int32_t*>(base + lay.bp_off);
     if (b.C <= parcae::kWaveMaxConfigs && !b.cost_move) {
@@ -397,17 +443,22 @@ int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, 
             parcae::wave_fill_table(table, b.C, wt);
             // back-pointers that do not stay in local memory are walked through memory: the caller's, else the workspace's
             int32_t* bp_arg = wl.bp_in_lds ? bp : bp_use;
+            // workgroups past the last query write the liveput tables, a thread per unit
+            const int64_t n_units = (int64_t)b.nq * b.T * b.C;
+            const int64_t table_blocks = with_tables ? (n_units + wl.threads - 1) / wl.threads : 0;
+            const dim3 grid((unsigned)(b.nq + table_blocks)), block((unsigned)wl.threads);
             if (b.cost_round)
-                parcae::plan_wave_kernel<true><<<dim3((unsigned)b.nq), dim3((unsigned)wl.threads), wl.lds, st>>>(
+                parcae::plan_wave_kernel<true><<<grid, block, wl.lds, st>>>(
                     b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
-                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE, tables);
             else
-                parcae::plan_wave_kernel<false><<<dim3((unsigned)b.nq), dim3((unsigned)wl.threads), wl.lds, st>>>(
+                parcae::plan_wave_kernel<false><<<grid, block, wl.lds, st>>>(
                     b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
-                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE);
+                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE, tables);
             return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;
         }
     }
+    if (with_tables) return PARCAE_EINVAL;  // only the wave planner writes them
     if (lay.stepwise) {
         // few queries: every (query, step) writes its weights in parallel, then the DP runs on them
         const int cap = pick_plan_cap(b.C, lay, 0, false);
@@ -535,8 +586,10 @@ int parcae_liveput_eval(const parcae_problem* problem, uint32_t* hist_int, uint3
     if ((rc = check_workspace(lay, workspace, workspace_bytes)) != PARCAE_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, lay, b, workspace, st)) != PARCAE_OK) return rc;
-    return launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, status, st);
+    EvalOpts opts;
+    opts.table = table.data();
+    opts.validate = true;
+    return launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, status, st, opts);
 }
 
 int parcae_plan_from_hist(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* F,
@@ -578,12 +631,17 @@ int parcae_liveput_plan(const parcae_problem* problem, uint32_t* hist_int, uint3
     if (!plan_fits(p, lay)) return PARCAE_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, lay, b, workspace, st, !takes_wave_planner(p, table.data(), lay))) != PARCAE_OK)
+    // with the wave planner the input check and the liveput tables are part of the planner's launch
+    const bool wave = takes_wave_planner(p, table.data(), lay);
+    EvalOpts opts;
+    opts.table = table.data();
+    opts.validate = !wave;
+    opts.tables_later = wave;
+    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st, opts)) != PARCAE_OK)
         return rc;
-    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
-        return rc;
+    const parcae::TablesOut tables = wave ? parcae::TablesOut{liveput, teff, gain} : parcae::TablesOut{nullptr, nullptr, nullptr};
     return launch_plan(b, table.data(), lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st,
-                       p->profile);
+                       p->profile, tables);
 }
 
 int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int, uint32_t* hist_min, float* liveput,
@@ -604,12 +662,16 @@ int parcae_liveput_plan_static(const parcae_problem* problem, uint32_t* hist_int
     if ((rc = static_scratch(&workspace)) != PARCAE_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Batch b = make_batch(p, lay, workspace);
-    if ((rc = stage_inputs(table, (size_t)p->n_configs, lay, b, workspace, st, !takes_wave_planner(p, table, lay))) !=
-        PARCAE_OK)
+    const bool wave = takes_wave_planner(p, table, lay);
+    EvalOpts opts;
+    opts.table = table;
+    opts.validate = !wave;
+    opts.tables_later = wave;
+    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st, opts)) != PARCAE_OK)
         return rc;
-    if ((rc = launch_eval(p, b, lay, workspace, hist_int, hist_min, liveput, teff, gain, nullptr, st)) != PARCAE_OK)
-        return rc;
-    return launch_plan(b, table, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st, p->profile);
+    const parcae::TablesOut tables = wave ? parcae::TablesOut{liveput, teff, gain} : parcae::TablesOut{nullptr, nullptr, nullptr};
+    return launch_plan(b, table, lay, workspace, hist_int, hist_min, F, bp, plan, start, objective, status, st, p->profile,
+                       tables);
 }
 
 int parcae_transition_weights(const parcae_problem* problem, const uint32_t* hist_int, const uint32_t* hist_min, float* W,

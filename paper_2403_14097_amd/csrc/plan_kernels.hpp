@@ -169,20 +169,19 @@ __global__ void __launch_bounds__(256) status_from_valid_kernel(int nq, const in
 
 // ------------------------------------------------------------------ liveput tables (Eq. 1, Eq. 4)
 
-// One thread per unit (q, t, c).
-__global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* __restrict__ hist_int,
-                                                       const uint32_t* __restrict__ hist_min,
-                                                       float* __restrict__ liveput, float* __restrict__ teff,
-                                                       float* __restrict__ gain)
+// The tables of unit u = (q, t, c); `cfg` is the candidate table (in memory or in the kernel's arguments).
+__device__ __forceinline__ void finalise_unit(const Batch& b, const CfgRec* __restrict__ cfg, int64_t u,
+                                              const uint32_t* __restrict__ hist_int,
+                                              const uint32_t* __restrict__ hist_min, float* __restrict__ liveput,
+                                              float* __restrict__ teff, float* __restrict__ gain)
 {
     const int64_t n_units = (int64_t)b.nq * b.T * b.C;
-    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= n_units) return;
     const int c = (int)(u % b.C);
     const int64_t qt = u / b.C;
     const int t = (int)(qt % b.T);
     const int q = (int)(qt / b.T);
-    const CfgRec cr = b.cfg[c];
+    const CfgRec cr = cfg[c];
     int M, k;
     unit_pool(b, q, t, cr.D, cr.P, M, k);
     const uint32_t* hi = hist_int + qt * b.L + cr.off;
@@ -239,6 +238,15 @@ __global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* 
     }
     if (teff) teff[u] = te;
     if (gain) gain[u] = __fmul_rn(full, te);
+}
+
+// One thread per unit (q, t, c).
+__global__ void __launch_bounds__(256) finalise_kernel(Batch b, const uint32_t* __restrict__ hist_int,
+                                                       const uint32_t* __restrict__ hist_min,
+                                                       float* __restrict__ liveput, float* __restrict__ teff,
+                                                       float* __restrict__ gain)
+{
+    finalise_unit(b, b.cfg, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, hist_int, hist_min, liveput, teff, gain);
 }
 
 // ------------------------------------------------------------------ transition weights from histogram tails

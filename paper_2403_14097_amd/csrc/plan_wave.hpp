@@ -245,14 +245,28 @@ __device__ __forceinline__ void suffix_row_batched(uint32_t* tail_int, uint32_t*
     }
 }
 
-// One workgroup (1 to 8 waves) per query.
+// The liveput tables a launch of the planner may write along the way (all null: none).
+struct TablesOut {
+    float* liveput;
+    float* teff;
+    float* gain;
+};
+
+// One workgroup (1 to 8 waves) per query.  Workgroups past the last query write the liveput tables, one thread per
+// unit: they need the finished histograms just as the plan does, and as part of this launch they cost no launch of
+// their own.
 template <bool kRounds>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) plan_wave_kernel(
     Batch b, WaveTable table, WaveGeom g, int Tc, int bp_in_lds, const uint32_t* __restrict__ hist_int,
     const uint32_t* __restrict__ hist_min, float* __restrict__ F, int32_t* __restrict__ bp,
     int32_t* __restrict__ plan, int32_t* __restrict__ start, float* __restrict__ objective,
-    int32_t* __restrict__ status, int einval, int einfeasible)
+    int32_t* __restrict__ status, int einval, int einfeasible, TablesOut tables)
 {
+    if ((int)blockIdx.x >= b.nq) {
+        finalise_unit(b, table.rec, ((int64_t)blockIdx.x - b.nq) * blockDim.x + threadIdx.x, hist_int, hist_min,
+                      tables.liveput, tables.teff, tables.gain);
+        return;
+    }
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int bad_inputs;
     WaveShared w;
