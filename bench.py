@@ -32,9 +32,13 @@ HBM_PEAK_BYTES = 8e12
 # sources and launch shape (the files below); once one of them changes the figures are withheld (null) until the
 # counters are taken again.
 COUNTER_SOURCES = ("device_common.hpp", "eval_kernels.hpp", "eval_launch.hpp")
-COUNTER_SOURCE_SHA256 = ""
+COUNTER_SOURCE_SHA256 = "3269ae7ca453f65e5ffdd32d67e00e4c7c2bc9e25d692ea924699717a12b2ceb"
 COUNTERS = {
     # workload tag: (HBM bytes read, HBM bytes written, SQ_INSTS_VALU)
+    "sweep": (20293831, 70417510, 6151771411),
+    "large": (5655853, 15274854, 751720568),
+    "mediumx256": (10412381, 63291149, 5765180089),
+    "largex256": (18743007, 1830468422, 313462170378),
 }
 
 

@@ -35,12 +35,15 @@ __host__ __device__ inline int pick_chunk_len(int64_t n_sampled_units, int S, in
 }
 
 // The most items a launch can have under the rule above (the host checks it against the range of the queue
-// counters and sizes the grid with it): short launches have at most one item per resident wave or, if that is
-// more, one per unit; the others have items of at least 512 scenarios.
+// counters and sizes the grid with it): a short launch has at most one item per resident wave or, if that is more,
+// one per unit, and never more than one per two rounds of a unit; the others have items of at least 512 scenarios.
 inline int64_t max_eval_items(int64_t n_units, int S, int64_t n_waves)
 {
+    const int64_t rounds_per_unit = ((int64_t)S + 63) / 64;
     const int64_t long_items = n_units * (((int64_t)S + 511) / 512);
-    const int64_t short_items = n_waves > n_units ? n_waves : n_units;
+    int64_t short_items = n_waves > n_units ? n_waves : n_units;
+    const int64_t finest = n_units * ((rounds_per_unit + 1) / 2);
+    if (finest < short_items) short_items = finest;
     return long_items > short_items ? long_items : short_items;
 }
 
