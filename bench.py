@@ -264,6 +264,10 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
         "dp_roofline": {"bound": "hbm", "achieved": dp_bytes / dp_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
                         "frac": dp_bytes / dp_s / HBM_PEAK_BYTES, "algorithmic_bytes": dp_bytes,
                         "steps_in_chain": T, "us_per_step": dp_s * 1e6 / T,
+                        # latency floor of the chain: T dependent steps at 440 cycles (a step of the wave planner with
+                        # every load and scan removed, measured) plus 5 us of launch and set-up, at 2.4 GHz
+                        "latency_floor_ms": (T * 440 / 2.4e9 + 5e-6) * 1e3,
+                        "measured_over_floor": dp_s / (T * 440 / 2.4e9 + 5e-6),
                         "alu_frac_at_15_ops_per_cell": cells / dp_s * 15 / ALU_PEAK_LANE_OPS},
     }
     if graph_ms is not None:

@@ -736,10 +736,22 @@ __device__ __forceinline__ void reduce_mask(const Mask<NW>& mask, int D, int P, 
 // of survivors (section 8.4: what an inter-stage migration costs depends on how many instances must receive state,
 // and that follows from these counts for every target width).  Works for any depth: stage s owns the bits
 // s, s + P, s + 2 P, ... of the mask; first[i] = first such bit of word i for the current stage, kept in step.
+// The wave keeps 2, 4 or 8 copies of these bins (copy = lane mod copies, bin v of copy r at (v << shift) + r): most
+// lanes of a wave hit the same one or two bins, a stage at a time, and the local memory takes lanes that add to one
+// address one after the other; with a single copy those adds, one per stage and scenario, kept the local memory of
+// the compute unit busy for longer than the vector units need for the rest of the scenario.
+// Words of local memory per wave for the copies: as many as leave the kernel variant its resident waves.
+__host__ __device__ constexpr int occ_words(int draw) { return draw == kDrawUniform ? 384 : (draw == kDrawZoned ? 520 : 768); }
+__device__ __forceinline__ int occ_copies_shift(int nb, int words)
+{
+    return (nb << 3) <= words ? 3 : ((nb << 2) <= words ? 2 : ((nb << 1) <= words ? 1 : 0));
+}
+
 template <int NW>
 __device__ __forceinline__ void stage_occupancy_add(const Mask<NW>& mask, int rows, int P, int group, int d_min,
-                                                    uint32_t* bins_occ)
+                                                    uint32_t* bins_occ, int shift)
 {
+    const int copy = lane_id() & ((1 << shift) - 1);
     const uint32_t period = P < 32 ? period_comb(P) : 1u;
     int first[NW];
     static_for<NW>([&](auto i) {
@@ -753,7 +765,7 @@ __device__ __forceinline__ void stage_occupancy_add(const Mask<NW>& mask, int ro
             gone += __popc(mask.w[i.value] & comb);
             first[i.value] = first[i.value] + 1 == P ? 0 : first[i.value] + 1;
         });
-        if (d_min >= 1) atomicAdd(&bins_occ[(rows - gone) * group], 1u);
+        if (d_min >= 1) atomicAdd(&bins_occ[(((rows - gone) * group) << shift) + copy], 1u);
     }
 }
 
@@ -948,8 +960,8 @@ template <int NW, int kDraw, bool kMoves, int KIND>
 __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int M, int k, uint32_t unit,
                                                 uint32_t stream_id, const PhiloxKeys& ks, uint32_t s_begin,
                                                 uint32_t s_end, uint32_t* lds_col, uint32_t* bins_int,
-                                                uint32_t* bins_min, uint32_t* bins_occ, const ZoneCtx* zc,
-                                                const WeightCtx* wc)
+                                                uint32_t* bins_min, uint32_t* bins_occ, int occ_shift,
+                                                const ZoneCtx* zc, const WeightCtx* wc)
 {
     const int rows = cr.D / group;  // pipelines of the instance grid
     for (uint32_t s = s_begin + (uint32_t)lane_id(); s < s_end; s += kWave) {
@@ -962,7 +974,7 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
         reduce_kind<NW, KIND>(mask, rows, cr.P, cr.log2P, n_int, d_min);
         hist_add(bins_int, n_int * group, true);
         hist_add(bins_min, d_min * group, true);
-        if constexpr (kMoves) stage_occupancy_add<NW>(mask, rows, cr.P, group, d_min, bins_occ);
+        if constexpr (kMoves) stage_occupancy_add<NW>(mask, rows, cr.P, group, d_min, bins_occ, occ_shift);
     }
 }
 
@@ -972,14 +984,14 @@ __device__ __forceinline__ void eval_unit_chunk(const CfgRec cr, int group, int 
 // kDraw selects how scenarios are drawn and kMoves adds the stage-occupancy statistic (kernels of their own, so
 // the plain one keeps its registers).
 template <int kDraw, bool kMoves>
-__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu((kDraw != kDrawUniform || kMoves) ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_resident_waves,
+__global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(kDraw != kDrawUniform ? 5 : 7, 8))) eval_hist_kernel(Batch b, WorkQueue wq, int n_resident_waves,
                                                                  uint32_t* __restrict__ hist_int,
                                                                  uint32_t* __restrict__ hist_min)
 {
     constexpr int kWaves = kEvalThreads / kWave;
     constexpr bool kZoned = kDraw == kDrawZoned;
     constexpr bool kWeighted = kDraw == kDrawWeighted;
-    __shared__ uint32_t bins_all[kWaves][(kMoves ? 3 : 2) * (kMaxInstances + 1)];
+    __shared__ uint32_t bins_all[kWaves][2 * (kMaxInstances + 1) + (kMoves ? occ_words(kDraw) : 0)];
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
     __shared__ uint8_t zone_perm[kZoned ? kWaves : 1][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kZoned ? kWaves : 1][kMaxZones * 8];
@@ -1066,8 +1078,9 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
         const int nb = cr.D + 1;
         uint32_t* bins_int = bins;
         uint32_t* bins_min = bins + nb;
-        uint32_t* bins_occ = bins + 2 * nb;  // used with kMoves only
-        for (int i = lane; i < (kMoves ? 3 : 2) * nb; i += kWave) bins[i] = 0u;
+        uint32_t* bins_occ = bins + 2 * nb;  // used with kMoves only: (1 << occ_shift) copies of nb bins
+        const int occ_shift = occ_copies_shift(nb, occ_words(kDraw));
+        for (int i = lane; i < 2 * nb + (kMoves ? nb << occ_shift : 0); i += kWave) bins[i] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -1087,13 +1100,13 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
             // kinds that need more than 32 stages cannot meet a one-word pool
             if (M <= 32) {
                 if constexpr (K != kPow2Words && K != kAnyLarge)
-                    eval_unit_chunk<1, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
+                    eval_unit_chunk<1, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, occ_shift, &zc, &wc);
             } else if (M <= 64) {
-                eval_unit_chunk<2, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
+                eval_unit_chunk<2, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, occ_shift, &zc, &wc);
             } else if (M <= 128) {
-                eval_unit_chunk<4, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
+                eval_unit_chunk<4, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, occ_shift, &zc, &wc);
             } else {
-                eval_unit_chunk<8, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, &zc, &wc);
+                eval_unit_chunk<8, kDraw, kMoves, K>(cr, b.group, M, k, (uint32_t)tc, stream_id, ks, s_begin, s_end, lds_col, bins_int, bins_min, bins_occ, occ_shift, &zc, &wc);
             }
         });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1110,7 +1123,8 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
                 if (vm) atomicAdd(&hist_min[base + i], vm);
             }
             if constexpr (kMoves) {
-                const uint32_t vo = bins_occ[i];
+                uint32_t vo = 0u;
+                for (int r = 0; r < (1 << occ_shift); ++r) vo += bins_occ[(i << occ_shift) + r];
                 if (n_chunks == 1) b.hist_occ[base + i] = vo;
                 else if (vo) atomicAdd(&b.hist_occ[base + i], vo);
             }

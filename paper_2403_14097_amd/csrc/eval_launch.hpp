@@ -47,8 +47,8 @@ inline int64_t max_eval_items(int64_t n_units, int S, int64_t n_waves)
     return long_items > short_items ? long_items : short_items;
 }
 
-// Waves per compute unit that stay resident at the kernel's register budget (7 per SIMD for the uniform draw
-// without the stage-occupancy statistic, 5 per SIMD for the other variants).
+// Waves per compute unit that stay resident at the kernel's register budget (7 per SIMD for the uniform draw,
+// with or without the stage-occupancy statistic; 5 per SIMD for the zoned and the weighted draw).
 constexpr int kEvalWavesPerCu = 28;
 constexpr int kEvalWavesPerCuWide = 20;
 

@@ -261,7 +261,7 @@ int launch_eval(const parcae_problem* p, const Batch& b, const Layout& lay, void
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return PARCAE_EHIP;
     const bool moves = b.cost_move != nullptr;
-    const bool wide = moves || b.inst_weight || b.n_zones > 0;  // the variants with the larger register budget
+    const bool wide = b.inst_weight || b.n_zones > 0;  // the variants with the larger register budget
     const int resident_waves = cus * (wide ? parcae::kEvalWavesPerCuWide : parcae::kEvalWavesPerCu);
     const int64_t max_items = parcae::max_eval_items(n_units, b.S, resident_waves);
     if (max_items >= (int64_t)1 << 31) return PARCAE_EINVAL;  // leaves room for the queue counters to overshoot
