@@ -751,7 +751,19 @@ template <int NW>
 __device__ __forceinline__ void stage_occupancy_add(const Mask<NW>& mask, int rows, int P, int group, int d_min,
                                                     uint32_t* bins_occ, int shift)
 {
-    const int copy = lane_id() & ((1 << shift) - 1);
+    // bin of a stage with `gone` lost instances, in this lane's copy: top - gone * step
+    const uint32_t step = (uint32_t)group << shift;
+    const uint32_t top = (uint32_t)rows * step + (uint32_t)(lane_id() & ((1 << shift) - 1));
+    if ((P & (P - 1)) == 0 && P <= 32) {
+        // the depth divides 32: stage s owns the same bits s, s + P, ... of every word
+        uint32_t comb = period_comb(P);
+        for (int s = 0; s < P; ++s, comb <<= 1) {
+            uint32_t gone = 0u;
+            static_for<NW>([&](auto i) { gone += (uint32_t)__popc(mask.w[i.value] & comb); });
+            if (d_min >= 1) atomicAdd(&bins_occ[top - gone * step], 1u);
+        }
+        return;
+    }
     const uint32_t period = P < 32 ? period_comb(P) : 1u;
     int first[NW];
     static_for<NW>([&](auto i) {
@@ -759,13 +771,13 @@ __device__ __forceinline__ void stage_occupancy_add(const Mask<NW>& mask, int ro
         first[i.value] = r < 0 ? r + P : r;
     });
     for (int s = 0; s < P; ++s) {
-        int gone = 0;
+        uint32_t gone = 0u;
         static_for<NW>([&](auto i) {
             const uint32_t comb = first[i.value] < 32 ? period << first[i.value] : 0u;
-            gone += __popc(mask.w[i.value] & comb);
+            gone += (uint32_t)__popc(mask.w[i.value] & comb);
             first[i.value] = first[i.value] + 1 == P ? 0 : first[i.value] + 1;
         });
-        if (d_min >= 1) atomicAdd(&bins_occ[(((rows - gone) * group) << shift) + copy], 1u);
+        if (d_min >= 1) atomicAdd(&bins_occ[top - gone * step], 1u);
     }
 }
 

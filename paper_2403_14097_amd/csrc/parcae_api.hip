@@ -53,7 +53,7 @@ int pick_plan_cap(int C, const Layout& lay, size_t bp16_bytes, bool per_query)
     return cap >= lay.max_row ? (int)cap : -1;
 }
 
-// The caller's structure may be older (shorter) or newer (longer) than this build's: copies what both sides know,
+// The caller's structure may be older (shorter) or newer (longer) than this library's: copies what both sides know,
 // zero-fills the rest.  False if the pointer is null or the size is below the members every release has.
 constexpr size_t kMinProblemSize = offsetof(parcae_problem, cost_round) + sizeof(const float*);
 bool load_problem(const parcae_problem* in, parcae_problem* out)
