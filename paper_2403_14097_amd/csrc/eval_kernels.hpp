@@ -324,8 +324,8 @@ enum DrawKind { kDrawUniform = 0, kDrawZoned = 1, kDrawWeighted = 2 };
 // Weights of the pool of one unit, staged once per work item by the wave that owns it (section 5.1: the
 // equal-probability assumption replaced by an estimate per instance).
 struct WeightCtx {
-    uint32_t packed;        // lane L: the weights of instances 4L .. 4L + 3, one per byte, 0 beyond the pool
-    const uint8_t* bytes;   // LDS [260], 4-byte aligned: the same weights, one per instance, for per-lane look-ups
+    const uint8_t* bytes;   // LDS [272], 16-byte aligned: the weights, one per instance, 0 beyond the pool
+    uint32_t word_sum[8];   // sum of the weights of instances 32 W .. 32 W + 31 (the same in every lane)
     uint32_t total;         // sum over the pool
 };
 
@@ -336,8 +336,8 @@ __device__ __forceinline__ WeightCtx weight_setup(const Batch& b, int q, int M, 
     const uint8_t* wq = b.inst_weight + (int64_t)q * b.N;
     WeightCtx wc;
     wc.bytes = bytes;
-    uint32_t packed = 0u, sum = 0u;
-    static_for<4>([&](auto x) {
+    uint32_t sum = 0u;
+    static_for<4>([&](auto x) {  // lane L stages instances 4 L .. 4 L + 3
         const int j = 4 * lane + x.value;
         uint32_t w = 0u;
         if (j < M) {
@@ -345,12 +345,12 @@ __device__ __forceinline__ WeightCtx weight_setup(const Batch& b, int q, int M, 
             w = w < 1u ? 1u : w;
         }
         bytes[j] = (uint8_t)w;
-        packed |= w << (8 * x.value);
         sum += w;
     });
     if (lane < 4) bytes[256 + lane] = 0u;  // a look-up one past the pool (cannot happen for valid input) finds 0
-    for (int sh = 1; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh);
-    wc.packed = packed;
+    for (int sh = 1; sh < 8; sh <<= 1) sum += __shfl_xor(sum, sh);  // eight lanes hold a word of 32 instances
+    static_for<8>([&](auto W) { wc.word_sum[W.value] = (uint32_t)__builtin_amdgcn_readlane((int)sum, 8 * W.value); });
+    for (int sh = 8; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh);
     wc.total = sum;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -359,45 +359,53 @@ __device__ __forceinline__ WeightCtx weight_setup(const Batch& b, int q, int M, 
 
 // Preempted set of scenario s by successive weighted sampling without replacement: k times, word i of sequence
 // 0xFFFE scaled to the weight still there picks a point, and the first instance (ascending) at which the running
-// sum of the weights still there exceeds the point goes.  All lanes walk the pool in step (the weights of a group of
-// four instances are one scalar word), each with its own set.  Running sums never decrease, so the number of groups
-// whose running sum does not exceed the point is the group of the instance that goes: a first pass adds the
-// weights still there four at a time (the four "still there" bits spread to bytes, one dot product per group), a
-// second pass walks the four instances of that group.
+// sum of the weights still there exceeds the point goes.  Every lane has its own set and walks the pool in three
+// passes; running sums never decrease, so in each pass the number of parts whose running sum does not exceed the
+// point is the part that holds the instance: (1) the words of 32 instances, by the weight still there per word,
+// which the lane keeps up to date; (2) the eight groups of four instances of that word (the four "still there"
+// bits spread to bytes, one dot product with the four weights per group); (3) the four instances of that group.
 template <int NW>
 __device__ __forceinline__ void sample_mask_weighted(Mask<NW>& mask, const WeightCtx& wc, int M, int k, uint32_t s,
                                                      uint32_t unit, uint32_t stream_id, const PhiloxKeys& ks)
 {
     mask.clear();
     uint32_t total = wc.total;
+    uint32_t left[NW];  // weight still there, per word
+    static_for<NW>([&](auto W) { left[W.value] = wc.word_sum[W.value]; });
+    const uint4* by_sixteen = reinterpret_cast<const uint4*>(wc.bytes);
     const uint32_t* by_four = reinterpret_cast<const uint32_t*>(wc.bytes);
     for (int i0 = 0; i0 < k; i0 += 4) {
         const Philox4 blk = philox4x32_10(s, 0xFFFE0000u + (uint32_t)(i0 >> 2), unit, stream_id, ks);
         static_for<4>([&](auto x) {
             if (i0 + x.value < k) {
                 const uint32_t point = __umulhi(blk.x[x.value], total);
-                uint32_t running = 0u, group = 0u, before = 0u;
-                static_for<NW>([&](auto W) {
-                    const uint32_t there = ~mask.w[W.value];
-                    // all eight groups of the word, unrolled (groups past the pool weigh nothing, and the running
-                    // sum has passed the point by then)
-                    static_for<8>([&](auto p) {
-                        const uint32_t four = (uint32_t)__builtin_amdgcn_readlane((int)wc.packed, 8 * W.value + p.value);
-                        // bits 4p .. 4p + 3 of `there`, one per byte: b0 + 2 b1 + 4 b2 + 8 b3 times (1 + 2^7 + 2^14 + 2^21)
-                        const uint32_t nibble = (there >> (4 * p.value)) & 0xfu;
-                        const uint32_t ones = (nibble * 0x00204081u) & 0x01010101u;
-                        running = __builtin_amdgcn_udot4(four, ones, running, false);
-                        const bool below = running <= point;
-                        group += below ? 1u : 0u;
-                        before = below ? running : before;
-                    });
+                uint32_t running = 0u, word = 0u, before = 0u;
+                static_for<NW - 1>([&](auto W) {  // the last word takes what the others leave
+                    running += left[W.value];
+                    const bool below = running <= point;
+                    word += below ? 1u : 0u;
+                    before = below ? running : before;
                 });
-                // the four instances of that group (a group index past the pool cannot come out of valid weights;
-                // the table has a zero entry there)
-                const uint32_t four = by_four[group < 64u ? group : 64u];
                 uint32_t there = 0u;
-                static_for<NW>([&](auto W) { there = (group >> 3) == (uint32_t)W.value ? ~mask.w[W.value] : there; });
-                const uint32_t nibble = (there >> (4u * (group & 7u))) & 0xfu;
+                static_for<NW>([&](auto W) { there = word == (uint32_t)W.value ? ~mask.w[W.value] : there; });
+                // the 32 weights of that word, four to a register
+                const uint4 lo = by_sixteen[2u * word], hi = by_sixteen[2u * word + 1u];
+                const uint32_t fours[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                uint32_t group = 0u;
+                running = before;
+                static_for<8>([&](auto p) {
+                    // bits 4p .. 4p + 3 of `there`, one per byte: b0 + 2 b1 + 4 b2 + 8 b3 times (1 + 2^7 + 2^14 + 2^21)
+                    const uint32_t nibble = (there >> (4 * p.value)) & 0xfu;
+                    const uint32_t ones = (nibble * 0x00204081u) & 0x01010101u;
+                    running = __builtin_amdgcn_udot4(fours[p.value], ones, running, false);
+                    const bool below = running <= point;
+                    group += below ? 1u : 0u;
+                    before = below ? running : before;
+                });
+                // the four instances of that group (a group past the word cannot come out of weights that add up)
+                group = group < 8u ? group : 7u;
+                const uint32_t four = by_four[8u * word + group];
+                const uint32_t nibble = (there >> (4u * group)) & 0xfu;
                 uint32_t inside = 0u, went = 0u;
                 running = before;
                 static_for<4>([&](auto y) {
@@ -408,8 +416,9 @@ __device__ __forceinline__ void sample_mask_weighted(Mask<NW>& mask, const Weigh
                     inside += below ? 1u : 0u;
                     went = (below || went != 0u) ? went : w;  // the weight at which the running sum first exceeds the point
                 });
-                mask.set(4u * group + inside);
+                mask.set(32u * word + 4u * group + inside);
                 total -= went;
+                static_for<NW>([&](auto W) { left[W.value] -= word == (uint32_t)W.value ? went : 0u; });
             }
         });
     }
@@ -1007,7 +1016,7 @@ __global__ void __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_
     __shared__ uint32_t lmask[8 * kEvalThreads];  // sets of units with more than 64 instances, [word][lane]
     __shared__ uint8_t zone_perm[kZoned ? kWaves : 1][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kZoned ? kWaves : 1][kMaxZones * 8];
-    __shared__ __align__(4) uint8_t weight_bytes[kWeighted ? kWaves : 1][260];
+    __shared__ __align__(16) uint8_t weight_bytes[kWeighted ? kWaves : 1][272];
     const int lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // the same in every lane
     uint32_t* bins = bins_all[wave];
@@ -1176,7 +1185,7 @@ __global__ void __launch_bounds__(kEvalThreads) debug_sample_kernel(Batch b, int
     __shared__ uint32_t lmask[8 * kEvalThreads];
     __shared__ uint8_t zone_perm[kEvalThreads / kWave][kMaxZones * 256];
     __shared__ uint32_t zone_mask[kEvalThreads / kWave][kMaxZones * 8];
-    __shared__ __align__(4) uint8_t weight_bytes[kEvalThreads / kWave][260];
+    __shared__ __align__(16) uint8_t weight_bytes[kEvalThreads / kWave][272];
     const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
     const CfgRec cr = b.cfg[c];
     int M, k;
