@@ -32,13 +32,17 @@ HBM_PEAK_BYTES = 8e12
 # sources and launch shape (the files below); once one of them changes the figures are withheld (null) until the
 # counters are taken again.
 COUNTER_SOURCES = ("device_common.hpp", "eval_kernels.hpp", "eval_launch.hpp")
-COUNTER_SOURCE_SHA256 = "3269ae7ca453f65e5ffdd32d67e00e4c7c2bc9e25d692ea924699717a12b2ceb"
+COUNTER_SOURCE_SHA256 = "379310ad9f833a9a31c8b0ad427a44b1418f0d02a8b306f15e76722588f325a0"
 COUNTERS = {
     # workload tag: (HBM bytes read, HBM bytes written, SQ_INSTS_VALU)
-    "sweep": (20293831, 70417510, 6151771411),
-    "large": (5655853, 15274854, 751720568),
-    "mediumx256": (10412381, 63291149, 5765180089),
-    "largex256": (18743007, 1830468422, 313462170378),
+    "sweep": (20617049, 70430458, 6151778544),
+    "large": (5636118, 15277581, 751720812),
+    "mediumx256": (10514396, 63292691, 5765179059),
+    "largex256": (18981020, 1830475872, 313462174193),
+    "sweep+pool-all": (28359937, 109491437, 8746616120),
+    "sweep+zones3": (21967842, 70333990, 28050559389),
+    "sweep+moves": (20619661, 102800499, 7353864723),
+    "sweep+weights": (21825953, 69995437, 63733331739),
 }
 
 
@@ -127,6 +131,26 @@ def _soname_loaded(name: str) -> bool:
             return any(name in line for line in fh)
     except OSError:
         return False
+
+
+def measured_copy_bandwidth() -> float:
+    """Bytes per second (read + written) of a plain device-to-device copy of 1 GiB: what a streaming kernel reaches
+    on this machine, for comparison with the 8 TB/s figure the plan's HBM fraction is quoted against."""
+    import torch
+    src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")   # written once, so every page is backed
+    dst = torch.zeros_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    sec = a.elapsed_time(b) / 5 / 1e3
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2.0 * (1 << 30) / sec
 
 
 def cpu_baseline(batch, budget_queries: int, pool_all: bool = False, max_threads: int | None = None):
@@ -240,7 +264,7 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
     tag = (batch.name + ("+pool-all" if pool_all else "") + (f"+zones{zones}" if zones else "") +
            ("+rounds" if rounds else "") + ("+weights" if weights else "") + ("+moves" if moves else ""))
     plain = not (dense or pool_all or zones or rounds or weights or moves)
-    counter_tag = (batch.name + (f"x{nq}" if queries else "")) if plain else ""
+    counter_tag = (batch.name + (f"x{nq}" if queries else "")) if plain else ("" if (dense or queries) else tag)
     traffic, valu_insts = kernel_counters(counter_tag)
     achieved = alg_ops / kern_s
     # the plan reads both histograms once and writes F and the back-pointers: its algorithmic HBM bytes
@@ -257,6 +281,8 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
                      "unit": "T lane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
                      "issue_frac": None if valu_insts is None else valu_insts * 64 / kern_s / ALU_PEAK_LANE_OPS,
                      "model_ops": alg_ops, "executed_valu_wave_instructions": valu_insts,
+                     # method operations per executed lane operation (above 1: the kernel issues fused forms)
+                     "useful_op_efficiency": None if valu_insts is None else alg_ops / (valu_insts * 64.0),
                      "traffic": traffic, "traffic_unit": "bytes per launch (HBM read + written)",
                      "kernel": "eval_hist_kernel"},
         # The plan is T dependent steps per query, so it cannot reach a throughput peak; what bounds a batch is the
@@ -361,6 +387,9 @@ def main():
         "dp_roofline": head["dp_roofline"],
         "roofline": head["roofline"],
     }
+    copy_bps = measured_copy_bandwidth()
+    out["dp_roofline"]["measured_copy_GBps"] = copy_bps / 1e9
+    out["dp_roofline"]["frac_of_measured_copy"] = out["dp_roofline"]["achieved"] * 1e9 / copy_bps
     out["roofline"]["note"] = (
         "frac = model_ops / kernel time / peak: model_ops is the textbook operation count of the method, the sum over "
         "units of S * A(M, k, P) (see algorithmic_lane_ops); issue_frac = executed vector instructions x 64 lanes / "
