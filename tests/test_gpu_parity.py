@@ -158,6 +158,44 @@ def test_batched_queries_parity(pk):
         _check_query_against_oracle(pk, b, q, ev, pl, 1000, check_W=W)
 
 
+@pytest.mark.parametrize("name,nq,S", [("medium", 2, 300), ("medium", 3, 200), ("small", 5, 333), ("small", 6, 257)])
+def test_batches_on_either_side_of_the_one_launch_staging(pk, name, nq, S):
+    """Small batches are staged by a single workgroup (table, histogram rows, work list), larger ones by three
+    kernels; 1800 and 1800 units take the first route (the second round of the workgroup's loop too), 2700 and 2160
+    the other.  Everything the call writes is compared for every query."""
+    b = pi.workload(name, n_queries=nq, n_scenarios=S)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    W = pk.parcae_transition_weights(p, ev.hist_int, ev.hist_min)
+    _sync()
+    for q in range(nq):
+        _check_all_outputs(pk, b, q, ev, pl, W, S)
+    # the evaluation alone takes the same staging and writes the same histograms and tables
+    ev2 = pk.parcae_liveput_eval(p)
+    _sync()
+    for f in ("hist_int", "hist_min", "liveput", "teff", "gain"):
+        assert np.array_equal(_np(getattr(ev, f)), _np(getattr(ev2, f))), f
+
+
+@pytest.mark.parametrize("keep", ["liveput", "teff", "gain"])
+def test_a_single_table_from_the_planning_call(pk, keep):
+    """The planner's launch writes the liveput tables the caller asked for and leaves the others alone."""
+    b = pi.workload("small", n_scenarios=500)
+    p = pk.upload(b)
+    full, _ = pk.parcae_liveput_plan(p)
+    _sync()
+    ev = pk.alloc_eval_out(p)
+    for f in ("liveput", "teff", "gain"):
+        if f != keep:
+            setattr(ev, f, None)
+    pl = pk.alloc_plan_out(p)
+    pk.parcae_liveput_plan(p, ev, pl)
+    _sync()
+    assert np.array_equal(_np(getattr(ev, keep)), _np(getattr(full, keep)))
+    r = oracle.run_query(b, 0, n_scenarios=500)
+    assert np.array_equal(_np(pl.plan[0]), r.plan.plan)
+
+
 def test_many_queries_take_the_per_query_planning_kernel(pk):
     """Forty queries: enough for the one-block-per-query planner (weights formed on the fly in LDS)."""
     b = pi.workload("sweep", n_queries=40, n_scenarios=300)
