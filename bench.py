@@ -55,12 +55,19 @@ def counter_digest() -> str:
     return digest.hexdigest()
 
 
+LIVE_COUNTERS = {}   # workload tag: counters taken in this run (see live_counters)
+
+
 def kernel_counters(workload_tag: str):
-    """(HBM bytes per launch, executed VALU wave-instructions per launch) of the sampling kernel, or (None, None)."""
+    """(HBM bytes per launch, executed VALU wave-instructions per launch, where they come from) of the sampling
+    kernel, or (None, None, None)."""
+    if workload_tag in LIVE_COUNTERS:
+        read, written, valu = LIVE_COUNTERS[workload_tag]
+        return read + written, valu, "rocprofv3 --pmc child runs of this bench run"
     if workload_tag not in COUNTERS or counter_digest() != COUNTER_SOURCE_SHA256:
-        return None, None
+        return None, None, None
     read, written, valu = COUNTERS[workload_tag]
-    return read + written, valu
+    return read + written, valu, "rocprofv3 --pmc runs summarised in profiles/ (kernel sources unchanged since)"
 
 
 def algorithmic_lane_ops(configs, avail, n_scenarios, pool_all=False, zoned=False):
@@ -131,6 +138,58 @@ def _soname_loaded(name: str) -> bool:
             return any(name in line for line in fh)
     except OSError:
         return False
+
+
+def live_counters(timeout_s: float = 150.0):
+    """Counters of the sampling kernel on the headline workload, taken in THIS run: three child processes under
+    `rocprofv3 --pmc` (FETCH_SIZE, WRITE_SIZE, SQ_INSTS_VALU; one counter set per run), each a short run of this
+    script that also launches a plain elementwise kernel of known size, which scales the two byte counters.
+    Must be called before this process touches the GPU (the children are started with fork + exec).
+    Returns (bytes read, bytes written, SQ_INSTS_VALU) per launch, or None if anything goes wrong."""
+    import csv
+    import shutil
+    import subprocess
+    import tempfile
+    rocprof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(rocprof):
+        return None
+    script = os.path.abspath(__file__)
+    env = dict(os.environ, TMPDIR="/tmp")
+    found = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE", "SQ_INSTS_VALU"):
+        out_dir = tempfile.mkdtemp(prefix="parcae_pmc_", dir="/tmp")
+        try:
+            cmd = [rocprof, "--pmc", counter, "--output-format", "csv", "-d", out_dir, "-o", "x", "--",
+                   sys.executable, script, "--counter-child"]
+            done = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL,
+                                  timeout=timeout_s)
+            if done.returncode != 0:
+                return None
+            kernel, copy = [], []
+            for root, _dirs, files in os.walk(out_dir):
+                for name in files:
+                    if not name.endswith("counter_collection.csv"):
+                        continue
+                    with open(os.path.join(root, name), newline="") as fh:
+                        for row in csv.DictReader(fh):
+                            if row.get("Counter_Name") != counter:
+                                continue
+                            if "eval_hist_kernel" in row["Kernel_Name"]:
+                                kernel.append(float(row["Counter_Value"]))
+                            elif "FunctorOnSelf_add" in row["Kernel_Name"]:
+                                copy.append(float(row["Counter_Value"]))
+            if not kernel or (counter != "SQ_INSTS_VALU" and not copy):
+                return None
+            value = sum(kernel) / len(kernel)
+            if counter != "SQ_INSTS_VALU":
+                # the elementwise kernel reads 1 GiB and writes 1 GiB; the counters are in KiB up to a constant factor
+                value = value * (1 << 30) / (sum(copy) / len(copy))
+            found[counter] = value
+        except (OSError, subprocess.SubprocessError, ValueError, KeyError):
+            return None
+        finally:
+            shutil.rmtree(out_dir, ignore_errors=True)
+    return found["FETCH_SIZE"], found["WRITE_SIZE"], found["SQ_INSTS_VALU"]
 
 
 def measured_copy_bandwidth() -> float:
@@ -265,7 +324,7 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
            ("+rounds" if rounds else "") + ("+weights" if weights else "") + ("+moves" if moves else ""))
     plain = not (dense or pool_all or zones or rounds or weights or moves)
     counter_tag = (batch.name + (f"x{nq}" if queries else "")) if plain else ("" if (dense or queries) else tag)
-    traffic, valu_insts = kernel_counters(counter_tag)
+    traffic, valu_insts, counter_source = kernel_counters(counter_tag)
     achieved = alg_ops / kern_s
     # the plan reads both histograms once and writes F and the back-pointers: its algorithmic HBM bytes
     dp_bytes = nq * T * batch.hist_len * 8 + nq * (T + 1) * C * 4 + nq * T * C * 4
@@ -284,6 +343,7 @@ def measure(pk, pi, events, name, steps, warmup, *, dense=False, queries=None, p
                      # method operations per executed lane operation (above 1: the kernel issues fused forms)
                      "useful_op_efficiency": None if valu_insts is None else alg_ops / (valu_insts * 64.0),
                      "traffic": traffic, "traffic_unit": "bytes per launch (HBM read + written)",
+                     "counter_source": counter_source,
                      "kernel": "eval_hist_kernel"},
         # The plan is T dependent steps per query, so it cannot reach a throughput peak; what bounds a batch is the
         # HBM traffic it cannot avoid (histograms read once, F and back-pointers written once).
@@ -327,6 +387,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=None, help="queries the CPU baseline runs")
     ap.add_argument("--cpu-threads", type=int, default=None, help="threads the CPU baseline may use (default: all)")
+    ap.add_argument("--no-live-counters", action="store_true",
+                    help="do not take the sampling kernel's counters in this run (three short rocprofv3 --pmc child "
+                         "runs before the measurement); the stored ones are used while the kernel sources match")
+    ap.add_argument("--counter-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel three times (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -335,6 +399,16 @@ def main():
         print("bench.py: this path runs on one GPU; --gpus N with N > 1 is not supported "
               "(queries would shard across GPUs with no exchange, which this program does not launch)", file=sys.stderr)
         sys.exit(2)
+
+    if args.counter_child:   # a short run of the headline workload under the profiler, with the calibration kernel
+        args.steps, args.warmup, args.calibrate_copy = 2, 1, True
+        args.no_others = args.no_cpu_baseline = args.no_live_counters = True
+    plain_sweep = args.workload == "sweep" and not (args.dense or args.pool_all or args.zones or args.rounds or
+                                                    args.weights or args.moves or args.queries)
+    if plain_sweep and not args.no_live_counters:
+        live = live_counters()   # before anything here touches the GPU
+        if live is not None:
+            LIVE_COUNTERS["sweep"] = tuple(int(round(v)) for v in live)
 
     import torch
 
@@ -393,16 +467,16 @@ def main():
     out["roofline"]["note"] = (
         "frac = model_ops / kernel time / peak: model_ops is the textbook operation count of the method, the sum over "
         "units of S * A(M, k, P) (see algorithmic_lane_ops); issue_frac = executed vector instructions x 64 lanes / "
-        "kernel time / peak, from SQ_INSTS_VALU of the rocprofv3 run summarised in profiles/ (null when the kernel "
-        "has changed since); the kernel issues fused forms (64-bit multiply-add, three-input logic, bit-sliced "
+        "kernel time / peak, from SQ_INSTS_VALU; traffic from FETCH_SIZE and WRITE_SIZE scaled by an elementwise "
+        "kernel of known size; counter_source says whether the counters were taken in this run (three rocprofv3 --pmc "
+        "child runs before the measurement) or are the stored ones of profiles/, which are withheld (null) once the "
+        "kernel sources change; the kernel issues fused forms (64-bit multiply-add, three-input logic, bit-sliced "
         "counters), so it executes fewer operations than the model counts; peak = 256 CUs x 4 SIMDs x 32 lanes/cycle "
         "x 2.4 GHz, the rate of simple 32-bit vector ops; multiplies, shifts, compares and popcounts issue at half "
         "that rate")
     if "graph_replay_ms_per_step" in head:
         out["graph_replay_ms_per_step"] = head["graph_replay_ms_per_step"]
 
-    plain_sweep = args.workload == "sweep" and not (args.dense or args.pool_all or args.zones or args.rounds or
-                                                    args.weights or args.moves or args.queries)
     if plain_sweep and not args.no_others:
         others = []
         for name, nq, k in (("large", None, 10), ("medium", 256, 5), ("large", 256, 2), ("medium", None, 20)):
