@@ -140,7 +140,7 @@ def _soname_loaded(name: str) -> bool:
         return False
 
 
-def live_counters(timeout_s: float = 150.0):
+def live_counters(timeout_s: float = 60.0):
     """Counters of the sampling kernel on the headline workload, taken in THIS run: three child processes under
     `rocprofv3 --pmc` (FETCH_SIZE, WRITE_SIZE, SQ_INSTS_VALU; one counter set per run), each a short run of this
     script that also launches a plain elementwise kernel of known size, which scales the two byte counters.
