@@ -343,6 +343,23 @@ def test_full_size_sweep_sampled(pk):
         _check_query_against_oracle(pk, b, q, ev, pl, b.n_scenarios)
 
 
+@pytest.mark.parametrize("name,units,plans", [("medium", 120, 6), ("large", 24, 2)])
+def test_full_size_batches_of_256_queries_sampled(pk, name, units, plans):
+    """256 queries of the medium and of the large shape in one launch, at their full scenario counts: the launch
+    configurations the benchmark reports beside the sweep.  Sampled units against the oracle, every status, and the
+    tables and plans of a few queries from the histograms the GPU produced."""
+    b = pi.workload(name, n_queries=256)
+    p = pk.upload(b)
+    ev, pl = pk.parcae_liveput_plan(p)
+    _sync()
+    rng = np.random.default_rng(23)
+    n = _sampled_unit_check(pk, b, ev, rng, units, b.n_scenarios)
+    assert n == units
+    assert np.all(_np(pl.status) == 0)
+    for q in rng.choice(b.n_queries, size=plans, replace=False):
+        _plan_check_from_gpu_histograms(pk, b, int(q), ev, pl)
+
+
 def _closed_form_rows(b, q, k, S):
     """Histogram [T, L] of query q holding only the units whose scenarios are all alike by the definition of the
     draw: nothing preempted (k = 0: every pipeline intact, bin D) or everything preempted (k = M: bin 0)."""
