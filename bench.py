@@ -148,6 +148,7 @@ def live_counters(timeout_s: float = 60.0):
     Returns (bytes read, bytes written, SQ_INSTS_VALU) per launch, or None if anything goes wrong."""
     import csv
     import shutil
+    import signal
     import subprocess
     import tempfile
     rocprof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
@@ -161,9 +162,19 @@ def live_counters(timeout_s: float = 60.0):
         try:
             cmd = [rocprof, "--pmc", counter, "--output-format", "csv", "-d", out_dir, "-o", "x", "--",
                    sys.executable, script, "--counter-child"]
-            done = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL,
-                                  timeout=timeout_s)
-            if done.returncode != 0:
+            # a process group of its own, so that a run that does not end can be ended with everything it started
+            child = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL,
+                                     start_new_session=True)
+            try:
+                child.wait(timeout=timeout_s)
+            except subprocess.TimeoutExpired:
+                try:
+                    os.killpg(child.pid, signal.SIGKILL)
+                except OSError:
+                    pass
+                child.wait()
+                return None
+            if child.returncode != 0:
                 return None
             kernel, copy = [], []
             for root, _dirs, files in os.walk(out_dir):
