@@ -307,7 +307,8 @@ int parcae_liveput_eval(const parcae_problem *p, uint32_t *hist_int, uint32_t *h
 /*
  * Look-ahead plan from histograms computed earlier (section 6.3 notes that the
  * sampling can be done in advance; Eq. 6).
- *   hist_int, hist_min  DEVICE in  [nq][T][L]
+ *   hist_int, hist_min  DEVICE in  [nq][T][L]: histograms of an evaluation with the same n_scenarios (the bins of
+ *                       a unit add up to it; other contents give a plan without meaning, never a fault)
  *   F                   DEVICE out [nq][T + 1][C] float, or NULL
  *   bp                  DEVICE out [nq][T][C] int32, or NULL
  *   plan                DEVICE out [nq][T] int32, required

@@ -356,7 +356,7 @@ struct WaveLaunch {
     size_t lds;
 };
 
-bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g, int cus, WaveLaunch* out)
+bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g, int cus, bool packed, WaveLaunch* out)
 {
     // A handful of queries with long candidate lists: one workgroup per query leaves the chip empty while it works
     // through the weights and back-pointers of every step, and writing the weights out with a workgroup per
@@ -370,7 +370,7 @@ bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g
     int resident = (nq + cus - 1) / cus;  // workgroups that should share a compute unit
     resident = resident < 1 ? 1 : (resident > 8 ? 8 : resident);
     const size_t budget = std::min(kMaxPlanLds, kLdsPerCu / (size_t)resident - kPlanStaticLds);
-    const size_t per_step = parcae::wave_step_lds(C, (int)L, g);
+    const size_t per_step = parcae::wave_step_lds(C, (int)L, g, packed);
     for (int attempt = 0; attempt < 4; ++attempt) {
         const bool bp16 = (attempt & 1) == 0 && bp16_bytes_for(T, C) != 0;
         const size_t room = attempt < 2 ? budget : kMaxPlanLds;
@@ -398,6 +398,10 @@ int compute_units(int* cus)
     return PARCAE_OK;
 }
 
+// Whether the wave planner keeps the two tails of a bin in one word: every count has to stay below 2^16, and the
+// weights by transfer rounds read the tails one histogram at a time.
+bool wave_tails_packed(int n_scenarios, const float* cost_round) { return n_scenarios < 65536 && !cost_round; }
+
 // Whether the plan of this problem goes to the wave planner (which checks the device inputs itself).
 bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layout& lay)
 {
@@ -405,7 +409,8 @@ bool takes_wave_planner(const parcae_problem* p, const CfgRec* table, const Layo
     if (p->n_configs > parcae::kWaveMaxConfigs || p->cost_move || compute_units(&cus) != PARCAE_OK) return false;
     WaveLaunch wl;
     return pick_wave_launch(p->n_queries, p->n_intervals, p->n_configs, lay.L,
-                            parcae::wave_geometry(table, p->n_configs), cus, &wl);
+                            parcae::wave_geometry(table, p->n_configs), cus, wave_tails_packed(p->n_scenarios, p->cost_round),
+                            &wl);
 }
 
 int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, void* ws, const uint32_t* hist_int,
@@ -438,7 +443,8 @@ int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, 
         if (compute_units(&cus) != PARCAE_OK) return PARCAE_EHIP;
         const parcae::WaveGeom g = parcae::wave_geometry(table, b.C);
         WaveLaunch wl;
-        if (pick_wave_launch(b.nq, b.T, b.C, lay.L, g, cus, &wl)) {
+        const bool packed = wave_tails_packed(b.S, b.cost_round);
+        if (pick_wave_launch(b.nq, b.T, b.C, lay.L, g, cus, packed, &wl)) {
             parcae::WaveTable wt;
             parcae::wave_fill_table(table, b.C, wt);
             // back-pointers that do not stay in local memory are walked through memory: the caller's, else the workspace's
@@ -448,11 +454,15 @@ int launch_plan_kernels(const Batch& b, const CfgRec* table, const Layout& lay, 
             const int64_t table_blocks = with_tables ? (n_units + wl.threads - 1) / wl.threads : 0;
             const dim3 grid((unsigned)(b.nq + table_blocks)), block((unsigned)wl.threads);
             if (b.cost_round)
-                parcae::plan_wave_kernel<true><<<grid, block, wl.lds, st>>>(
+                parcae::plan_wave_kernel<true, false><<<grid, block, wl.lds, st>>>(
+                    b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
+                    status, PARCAE_EINVAL, PARCAE_EINFEASIBLE, tables);
+            else if (packed)
+                parcae::plan_wave_kernel<false, true><<<grid, block, wl.lds, st>>>(
                     b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
                     status, PARCAE_EINVAL, PARCAE_EINFEASIBLE, tables);
             else
-                parcae::plan_wave_kernel<false><<<grid, block, wl.lds, st>>>(
+                parcae::plan_wave_kernel<false, false><<<grid, block, wl.lds, st>>>(
                     b, wt, g, wl.steps_per_chunk, wl.bp_in_lds, hist_int, hist_min, F, bp_arg, plan, start, objective,
                     status, PARCAE_EINVAL, PARCAE_EINFEASIBLE, tables);
             return hipGetLastError() == hipSuccess ? PARCAE_OK : PARCAE_EHIP;

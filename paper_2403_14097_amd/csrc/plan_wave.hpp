@@ -104,9 +104,11 @@ __host__ __device__ inline size_t wave_fixed_lds(int C, int T, const WaveGeom& g
     if (bp_in_lds) o += (2 * (size_t)T * (size_t)C + 15) & ~(size_t)15;
     return o + 32;  // alignment of the per-chunk arrays
 }
-__host__ __device__ inline size_t wave_step_lds(int C, int L, const WaveGeom& g)
+// `packed`: the two tails of a bin share a word (scenario counts below 2^16, see plan_wave_kernel)
+__host__ __device__ inline size_t wave_step_lds(int C, int L, const WaveGeom& g, bool packed)
 {
-    return 8 * (size_t)L + 4 * (size_t)C * g.ws + 4 * (size_t)g.cpad + 4 * (size_t)C + (size_t)round_up4(C);
+    return (packed ? 4 : 8) * (size_t)L + 4 * (size_t)C * g.ws + 4 * (size_t)g.cpad + 4 * (size_t)C +
+           (size_t)round_up4(C);
 }
 
 struct WaveShared {
@@ -130,7 +132,7 @@ struct WaveShared {
 };
 
 __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, int T, int Tc, const WaveGeom& g,
-                                           bool bp_in_lds, WaveShared& w)
+                                           bool bp_in_lds, bool packed, WaveShared& w)
 {
     size_t o = 0;
     w.ps.cfg = reinterpret_cast<CfgRec*>(smem + o); o += sizeof(CfgRec) * (size_t)C;
@@ -150,8 +152,8 @@ __device__ __forceinline__ void wave_carve(unsigned char* smem, int C, int L, in
         w.bp16 = reinterpret_cast<uint16_t*>(smem + o);
         o += (2 * (size_t)T * (size_t)C + 15) & ~(size_t)15;
     }
-    w.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)Tc * L;
-    w.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)Tc * L;
+    w.tail_int = reinterpret_cast<uint32_t*>(smem + o); o += 4 * (size_t)Tc * L;  // packed: both tails, int | min << 16
+    w.tail_min = reinterpret_cast<uint32_t*>(smem + o); o += packed ? 0 : 4 * (size_t)Tc * L;
     o = (o + 15) & ~(size_t)15;
     w.wsame = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)Tc * C * g.ws;
     w.feff = reinterpret_cast<float*>(smem + o); o += 4 * (size_t)Tc * g.cpad;
@@ -245,6 +247,26 @@ __device__ __forceinline__ void suffix_row_batched(uint32_t* tail_int, uint32_t*
     }
 }
 
+// The same on rows whose words hold both histograms, hist_int | hist_min << 16: while a unit has fewer than 2^16
+// scenarios no partial sum of either half reaches 2^16, so one 32-bit addition adds both halves.
+__device__ __forceinline__ void suffix_row_batched_packed(uint32_t* tail, int o, int D)
+{
+    uint32_t r = 0u;
+    for (int j = D; j >= 1; j -= 8) {
+        uint32_t v[8];
+        static_for<8>([&](auto x) {
+            const int at = j - x.value >= 1 ? j - x.value : 1;
+            v[x.value] = tail[o + at];
+        });
+        static_for<8>([&](auto x) {
+            if (j - x.value >= 1) {
+                r += v[x.value];
+                tail[o + j - x.value] = r;
+            }
+        });
+    }
+}
+
 // The liveput tables a launch of the planner may write along the way (all null: none).
 struct TablesOut {
     float* liveput;
@@ -255,7 +277,9 @@ struct TablesOut {
 // One workgroup (1 to 8 waves) per query.  Workgroups past the last query write the liveput tables, one thread per
 // unit: they need the finished histograms just as the plan does, and as part of this launch they cost no launch of
 // their own.
-template <bool kRounds>
+// kPacked (without transfer rounds, fewer than 2^16 scenarios): the two tails of a bin share a word of local memory,
+// which halves the suffix sums and the room the rows of a step take, so that more steps fit a chunk.
+template <bool kRounds, bool kPacked>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) plan_wave_kernel(
     Batch b, WaveTable table, WaveGeom g, int Tc, int bp_in_lds, const uint32_t* __restrict__ hist_int,
     const uint32_t* __restrict__ hist_min, float* __restrict__ F, int32_t* __restrict__ bp,
@@ -271,7 +295,8 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
     __shared__ int bad_inputs;
     WaveShared w;
     const int C = b.C, T = b.T, L = b.L;
-    wave_carve(smem, C, L, T, Tc, g, bp_in_lds != 0, w);
+    static_assert(!(kRounds && kPacked), "the weights by transfer rounds read the tails one histogram at a time");
+    wave_carve(smem, C, L, T, Tc, g, bp_in_lds != 0, kPacked, w);
     const int q = blockIdx.x;
     const int tid = (int)threadIdx.x, nthreads = (int)blockDim.x;
     const int lane = tid & (kWave - 1);
@@ -301,8 +326,12 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
         static_for<kWaveRowRegs>([&](auto x) {
             const int i = x.value * nthreads + tid;
             if (i < words) {
-                w.tail_int[i] = next_int[x.value];
-                w.tail_min[i] = next_min[x.value];
+                if constexpr (kPacked) {
+                    w.tail_int[i] = next_int[x.value] | (next_min[x.value] << 16);
+                } else {
+                    w.tail_int[i] = next_int[x.value];
+                    w.tail_min[i] = next_min[x.value];
+                }
             }
         });
     };
@@ -377,7 +406,8 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
         for (int row = tid; row < n * C; row += nthreads) {
             const int ti = fast_div(row, g.inv_C);
             const CfgRec cr = w.ps.cfg[row - ti * C];
-            suffix_row_batched(w.tail_int, w.tail_min, ti * L + cr.off, cr.D);
+            if constexpr (kPacked) suffix_row_batched_packed(w.tail_int, ti * L + cr.off, cr.D);
+            else suffix_row_batched(w.tail_int, w.tail_min, ti * L + cr.off, cr.D);
         }
         __syncthreads();
         // phase A: weights of the same-depth transitions, four pairs at a time (loads of the four travel together)
@@ -407,12 +437,24 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
                 float4 tg[4];
                 static_for<4>([&](auto k) {
                     const uint32_t* ri = w.tail_int + ti[k.value] * L;
-                    const uint32_t* rm = w.tail_min + ti[k.value] * L;
-                    t_int[k.value] = ri[cell[k.value].x & 0xffffu];
-                    t_min[k.value] = rm[cell[k.value].x & 0xffffu];
-                    h0[k.value] = rm[cell[k.value].x >> 16];
+                    if constexpr (kPacked) {
+                        t_int[k.value] = ri[cell[k.value].x & 0xffffu];  // both tails; taken apart below
+                        h0[k.value] = ri[cell[k.value].x >> 16];
+                    } else {
+                        const uint32_t* rm = w.tail_min + ti[k.value] * L;
+                        t_int[k.value] = ri[cell[k.value].x & 0xffffu];
+                        t_min[k.value] = rm[cell[k.value].x & 0xffffu];
+                        h0[k.value] = rm[cell[k.value].x >> 16];
+                    }
                     tg[k.value] = w.tgt[cell[k.value].y & 0xffu];
                 });
+                if constexpr (kPacked) {
+                    static_for<4>([&](auto k) {
+                        t_min[k.value] = t_int[k.value] >> 16;
+                        t_int[k.value] &= 0xffffu;
+                        h0[k.value] >>= 16;
+                    });
+                }
                 static_for<4>([&](auto k) {
                     // a target wider than the source keeps nothing (the width of a target is at least 1)
                     const bool keep = (cell[k.value].y & 0x80000000u) != 0u;
