@@ -380,6 +380,13 @@ bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g
         const int64_t by_regs = (int64_t)parcae::kWaveRowRegs * threads / L;
         tc = std::min(std::min(tc, (int64_t)parcae::kWave - 1), std::min(by_regs, (int64_t)T));  // lane i keeps the availability of step i
         if (tc < 1) continue;
+        // the back-pointers of a chunk are one item per (step, candidate) and thread: a chunk that needs one more
+        // round of the workgroup for a few items is cut back to whole rounds if that costs no further chunk
+        const int64_t rounds = tc * C / threads;
+        if (rounds >= 1 && tc * C > rounds * threads) {
+            const int64_t fit = rounds * threads / C;
+            if (fit >= 1 && (T + fit - 1) / fit == (T + tc - 1) / tc) tc = fit;
+        }
         out->threads = threads;
         out->steps_per_chunk = (int)tc;
         out->bp_in_lds = bp16 ? 1 : 0;
