@@ -410,22 +410,24 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
             else suffix_row_batched(w.tail_int, w.tail_min, ti * L + cr.off, cr.D);
         }
         __syncthreads();
-        // phase A: weights of the same-depth transitions, four pairs at a time (loads of the four travel together)
+        // phase A: weights of the same-depth transitions, four pairs per thread at a time (the loads of the four
+        // travel together); what is left for a last round of at most two per thread is done two at a time
         const int n_pairs = n * g.ncells;
-        for (int e0 = tid; e0 < n_pairs; e0 += 4 * nthreads) {
-            int ti[4];
-            uint2 cell[4];
-            bool live[4];
-            static_for<4>([&](auto k) {
+        auto weights_of = [&](auto width, int e0) __attribute__((always_inline)) {
+            constexpr int kW = decltype(width)::value;
+            int ti[kW];
+            uint2 cell[kW];
+            bool live[kW];
+            static_for<kW>([&](auto k) {
                 const int e = e0 + k.value * nthreads;
                 live[k.value] = e < n_pairs;
                 const int ec = live[k.value] ? e : e0;
                 ti[k.value] = fast_div(ec, g.inv_ncells);
                 cell[k.value] = w.cell[ec - ti[k.value] * g.ncells];
             });
-            float wt[4];
+            float wt[kW];
             if constexpr (kRounds) {
-                static_for<4>([&](auto k) {
+                static_for<kW>([&](auto k) {
                     PlanShared ps = w.ps;
                     ps.tail_int = w.tail_int + ti[k.value] * L;
                     ps.tail_min = w.tail_min + ti[k.value] * L;
@@ -433,9 +435,9 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
                                                           (int)(cell[k.value].y & 0xffu));
                 });
             } else {
-                uint32_t t_int[4], t_min[4], h0[4];
-                float4 tg[4];
-                static_for<4>([&](auto k) {
+                uint32_t t_int[kW], t_min[kW], h0[kW];
+                float4 tg[kW];
+                static_for<kW>([&](auto k) {
                     const uint32_t* ri = w.tail_int + ti[k.value] * L;
                     if constexpr (kPacked) {
                         t_int[k.value] = ri[cell[k.value].x & 0xffffu];  // both tails; taken apart below
@@ -449,13 +451,13 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
                     tg[k.value] = w.tgt[cell[k.value].y & 0xffu];
                 });
                 if constexpr (kPacked) {
-                    static_for<4>([&](auto k) {
+                    static_for<kW>([&](auto k) {
                         t_min[k.value] = t_int[k.value] >> 16;
                         t_int[k.value] &= 0xffffu;
                         h0[k.value] >>= 16;
                     });
                 }
-                static_for<4>([&](auto k) {
+                static_for<kW>([&](auto k) {
                     // a target wider than the source keeps nothing (the width of a target is at least 1)
                     const bool keep = (cell[k.value].y & 0x80000000u) != 0u;
                     const uint32_t n0 = keep ? t_int[k.value] : 0u, n01 = keep ? t_min[k.value] : 0u;
@@ -463,9 +465,14 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
                                                                             tg[k.value].y, tg[k.value].z, tg[k.value].w));
                 });
             }
-            static_for<4>([&](auto k) {
+            static_for<kW>([&](auto k) {
                 if (live[k.value]) w.wsame[ti[k.value] * C * g.ws + (int)((cell[k.value].y >> 8) & 0xffffu)] = wt[k.value];
             });
+        };
+        {
+            int e0 = tid;
+            for (; e0 + 2 * nthreads < n_pairs; e0 += 4 * nthreads) weights_of(std::integral_constant<int, 4>{}, e0);
+            if (e0 < n_pairs) weights_of(std::integral_constant<int, 2>{}, e0);
         }
         __syncthreads();
         // chain: values only
