@@ -35,14 +35,14 @@ COUNTER_SOURCES = ("device_common.hpp", "eval_kernels.hpp", "eval_launch.hpp")
 COUNTER_SOURCE_SHA256 = "379310ad9f833a9a31c8b0ad427a44b1418f0d02a8b306f15e76722588f325a0"
 COUNTERS = {
     # workload tag: (HBM bytes read, HBM bytes written, SQ_INSTS_VALU)
-    "sweep": (20617049, 70430458, 6151778544),
-    "large": (5636118, 15277581, 751720812),
-    "mediumx256": (10514396, 63292691, 5765179059),
-    "largex256": (18981020, 1830475872, 313462174193),
-    "sweep+pool-all": (28359937, 109491437, 8746616120),
-    "sweep+zones3": (21967842, 70333990, 28050559389),
-    "sweep+moves": (20619661, 102800499, 7353864723),
-    "sweep+weights": (21825953, 69995437, 63733331739),
+    "sweep": (20344448, 70427680, 6151778111),
+    "large": (6082054, 15285261, 751724030),
+    "mediumx256": (10513189, 63299283, 5765183733),
+    "largex256": (19096143, 1830480864, 313462177343),
+    "sweep+pool-all": (28243460, 109488813, 8746618723),
+    "sweep+zones3": (21876636, 70331680, 28050556938),
+    "sweep+moves": (20642953, 102797069, 7353867706),
+    "sweep+weights": (21691145, 69988845, 63733328703),
 }
 
 
