@@ -378,7 +378,7 @@ bool pick_wave_launch(int nq, int T, int C, int64_t L, const parcae::WaveGeom& g
         if (fixed + per_step > room) continue;
         int64_t tc = (int64_t)((room - fixed) / per_step);
         const int64_t by_regs = (int64_t)parcae::kWaveRowRegs * threads / L;
-        tc = std::min(std::min(tc, (int64_t)parcae::kWave - 1), std::min(by_regs, (int64_t)T));  // lane i keeps the availability of step i
+        tc = std::min(std::min(tc, (int64_t)32), std::min(by_regs, (int64_t)T));  // one bit per step of a chunk in a 32-bit mask
         if (tc < 1) continue;
         // the back-pointers of a chunk are one item per (step, candidate) and thread: a chunk that needs one more
         // round of the workgroup for a few items is cut back to whole rounds if that costs no further chunk

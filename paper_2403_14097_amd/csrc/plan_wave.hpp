@@ -484,18 +484,18 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
             const int n4 = g.gp / 4;
             // whether this lane's candidate may be left / entered at each step of the chunk (constraint D * P <= N of
             // Eq. 6, memory floor, the current configuration at t = 0), one bit per step, before the dependent steps
-            unsigned long long from_bits = 0ull, to_bits = 0ull;
+            uint32_t from_bits = 0u, to_bits = 0u;  // a chunk has at most 32 steps
             for (int ti = 0; ti < n; ++ti) {
                 const int t = t0 + ti;
                 const bool from = used <= b.group * w.av[t] && deep && (t > 0 || cur < 0 || lane == cur);
                 const bool to = used <= b.group * w.av[t + 1] && deep;
-                from_bits |= (unsigned long long)(from && is_cand) << ti;
-                to_bits |= (unsigned long long)to << ti;
+                from_bits |= (uint32_t)(from && is_cand) << ti;
+                to_bits |= (uint32_t)to << ti;
             }
             for (int ti = 0; ti < n; ++ti) {
                 const int t = t0 + ti;
-                const bool from = (from_bits >> ti) & 1ull;
-                const bool to = (to_bits >> ti) & 1ull;
+                const bool from = (from_bits >> ti) & 1u;
+                const bool to = (to_bits >> ti) & 1u;
                 const float fe = from ? Fcur : kNegInf;
                 float* frow = w.feff + ti * g.cpad;
                 if (is_cand) frow[gslot + lane - lo] = fe;
