@@ -523,13 +523,15 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))
                     const int after = lane_value(sm, hi < kWave ? hi : 0);
                     const int ob = lo > 0 ? before : kNegInfBits, oa = hi < kWave ? after : kNegInfBits;
                     other = __fadd_rn(__int_as_float(ob > oa ? ob : oa), reach);
-                    fn = other;
+                    // the maximum as a tree (a maximum does not depend on the order): the step waits for the deepest
+                    // path of dependent instructions, not for their number
+                    float m[4];
                     static_for<4>([&](auto k) {
                         const float s0 = __fadd_rn(f[k.value].x, x[k.value].x), s1 = __fadd_rn(f[k.value].y, x[k.value].y);
                         const float s2 = __fadd_rn(f[k.value].z, x[k.value].z), s3 = __fadd_rn(f[k.value].w, x[k.value].w);
-                        fn = __builtin_fmaxf(__builtin_fmaxf(fn, s0), s1);
-                        fn = __builtin_fmaxf(__builtin_fmaxf(fn, s2), s3);
+                        m[k.value] = __builtin_fmaxf(__builtin_fmaxf(s0, s1), __builtin_fmaxf(s2, s3));
                     });
+                    fn = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(m[0], m[1]), __builtin_fmaxf(m[2], m[3])), other);
                     for (int i0 = 4; i0 < n4; i0 += 4) {  // depth groups of more than 16 candidates
                         static_for<4>([&](auto k) {
                             const int i = i0 + k.value < n4 ? i0 + k.value : n4 - 1;
