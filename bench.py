@@ -32,17 +32,17 @@ HBM_PEAK_BYTES = 8e12
 # sources and launch shape (the files below); once one of them changes the figures are withheld (null) until the
 # counters are taken again.
 COUNTER_SOURCES = ("device_common.hpp", "eval_kernels.hpp", "eval_launch.hpp")
-COUNTER_SOURCE_SHA256 = "379310ad9f833a9a31c8b0ad427a44b1418f0d02a8b306f15e76722588f325a0"
+COUNTER_SOURCE_SHA256 = "2acce2d943f4f1777ecd874a84d9f6c7be181a7fd3ac921350616c60e9b674c1"
 COUNTERS = {
     # workload tag: (HBM bytes read, HBM bytes written, SQ_INSTS_VALU)
-    "sweep": (20344448, 70427680, 6151778111),
-    "large": (6082054, 15285261, 751724030),
-    "mediumx256": (10513189, 63299283, 5765183733),
-    "largex256": (19096143, 1830480864, 313462177343),
-    "sweep+pool-all": (28243460, 109488813, 8746618723),
-    "sweep+zones3": (21876636, 70331680, 28050556938),
-    "sweep+moves": (20642953, 102797069, 7353867706),
-    "sweep+weights": (21691145, 69988845, 63733328703),
+    "sweep": (20523553, 46566496, 6116129796),
+    "large": (5831181, 15271962, 751717061),
+    "mediumx256": (10511269, 36863526, 5734618211),
+    "largex256": (18611679, 933758758, 312438217035),
+    "sweep+pool-all": (28277247, 58024378, 8686218050),
+    "sweep+zones3": (22025575, 46375386, 27995753187),
+    "sweep+moves": (20538611, 63833370, 7291402457),
+    "sweep+weights": (22242043, 46544288, 63678165359),
 }
 
 

@@ -15,8 +15,10 @@ namespace parcae {
 //    rounds instead of 11; items of one round pay more for their table loads and for the adds into the shared
 //    histogram rows than for their scenarios, so an item has at least two.)
 //  * Longer launches take 1024 (long enough to pay for the claim and the table loads, short enough that the last
-//    items do not leave the chip half empty), very long ones gain a little from 2048; pools of more than 128
-//    instances cost about twice as much per scenario, so their items are half as long.
+//    items do not leave the chip half empty); very long ones (1024 rounds or more per wave) take 4096, which is as
+//    fast as 2048 or a little faster on every batch measured and makes a unit of up to 4096 scenarios a single item:
+//    its bins are then stored once instead of added to memory by every item.  Pools of more than 128 instances cost
+//    about twice as much per scenario, so their items are half as long.
 __host__ __device__ inline int pick_chunk_len(int64_t n_sampled_units, int S, int n_instances, int64_t n_waves)
 {
     const int64_t rounds_per_unit = ((int64_t)S + 63) / 64;
@@ -28,7 +30,7 @@ __host__ __device__ inline int pick_chunk_len(int64_t n_sampled_units, int S, in
         while (rounds < rounds_per_unit && n_sampled_units * ((rounds_per_unit + rounds - 1) / rounds) > n_waves) ++rounds;
         chunk = 64 * (int)rounds;
     } else {
-        chunk = rounds_per_wave >= 1024 ? 2048 : 1024;
+        chunk = rounds_per_wave >= 1024 ? 4096 : 1024;
         if (n_instances > 128) chunk /= 2;
     }
     return S < chunk ? S : chunk;
